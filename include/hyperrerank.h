@@ -1,0 +1,208 @@
+/*
+ * hyperrerank - C ABI of the MI355X reranker scoring library.
+ *
+ * The method (HyperRAG, Section 3.3 Property 1 and Section 4.2): a decoder-only
+ * reranker scores a (document, query) pair on the sequence [document ; query].
+ * Because attention is lower-triangular and the document always starts the
+ * sequence, every layer's K/V of the document can be computed once, stored, and
+ * reused for any query; scoring then runs only the short query suffix through
+ * the layers while attending to the stored document K/V ("static document
+ * prefix | query suffix" KV layout).  This library keeps the stored K/V in a
+ * paged pool in HBM and implements that scoring pass for a batch of pairs.
+ *
+ * Conventions
+ *   - "host" pointers are ordinary CPU memory, read during the call only.
+ *   - "device" pointers are HBM addresses on the current HIP device.  The
+ *     library never allocates or frees device memory: pools, packed weights,
+ *     workspaces and outputs are all caller-owned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls that take a stream enqueue work and return without waiting.
+ *   - Every call returns HR_OK (0) or a negative hr_status.  On error nothing
+ *     is enqueued and no library state changes.  Nothing throws or aborts.
+ *   - All matrices are row-major [out][in]; activations use the model dtype
+ *     (HR_F32 or HR_BF16); norm gains and scores are fp32.
+ *   - A page holds 16 consecutive tokens of one document for one (layer,
+ *     kv head): K as [16][head_dim] and V transposed; the in-pool arrangement
+ *     is private to the library (use hr_doc_kv_write to fill it).
+ */
+#ifndef HYPERRERANK_H
+#define HYPERRERANK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HR_PAGE_TOKENS 16
+
+typedef enum hr_status {
+    HR_OK = 0,
+    HR_ERR_INVALID_ARG = -1,       /* null pointer, non-positive count, bad enum                    */
+    HR_ERR_POOL_TOO_SMALL = -2,    /* device buffer smaller than hr_kv_pool_bytes                    */
+    HR_ERR_PAGE_RANGE = -3,        /* page id < 0 or >= num_pages                                     */
+    HR_ERR_PAGE_IN_USE = -4,       /* writing a page that already holds a document                    */
+    HR_ERR_PAGE_DUP = -5,          /* the same page id twice in one document                          */
+    HR_ERR_LEN_RANGE = -6,         /* document / query length <= 0 or above the supported maximum    */
+    HR_ERR_TABLE_SHORT = -7,       /* page-table row too short, or -1 / unwritten page inside it     */
+    HR_ERR_TOKEN_RANGE = -8,       /* token id < 0 or >= vocab                                        */
+    HR_ERR_WORKSPACE_SMALL = -9,   /* workspace smaller than hr_rerank_workspace_bytes                */
+    HR_ERR_UNSUPPORTED_SHAPE = -10,/* model / pool shape the kernels do not cover                     */
+    HR_ERR_DEVICE = -11,           /* a HIP runtime call failed (no device, launch error)            */
+    HR_ERR_POOL_FULL = -12,        /* hr_kv_pool_alloc_pages: not enough free pages                   */
+    HR_ERR_MISMATCH = -13          /* pool and model disagree (layers, kv heads, head_dim, dtype)    */
+} hr_status;
+
+typedef enum hr_dtype { HR_F32 = 0, HR_BF16 = 1, HR_FP8_E4M3 = 2 } hr_dtype;
+
+/* Paged document-KV pool.  kv_dtype: HR_F32, HR_BF16, or HR_FP8_E4M3 (OCP E4M3, one fp32 scale
+ * per (layer, page, kv head) for K and one for V; value = decode(code) * scale).  The 8-bit form
+ * follows Section 4.1 "KV-cache Quantization" / Appendix B (KV8, expanded after loading). */
+typedef struct hr_pool_cfg {
+    int32_t n_layers;
+    int32_t n_kv_heads;
+    int32_t head_dim;      /* multiple of 16, at most 256 */
+    int32_t page_tokens;   /* must be HR_PAGE_TOKENS */
+    int32_t num_pages;
+    int32_t kv_dtype;      /* hr_dtype */
+} hr_pool_cfg;
+
+/* Reranker: pre-norm decoder blocks with RMSNorm, rotate-half RoPE, grouped-query attention,
+ * SwiGLU, no biases; score = logit[yes_id] - logit[no_id] at the last query token with the
+ * embedding matrix as the (tied) head, after the final RMSNorm. */
+typedef struct hr_model_cfg {
+    int32_t n_layers;
+    int32_t hidden;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;    /* divides n_q_heads */
+    int32_t head_dim;
+    int32_t ffn;
+    int32_t vocab;
+    int32_t yes_id;
+    int32_t no_id;
+    int32_t dtype;         /* HR_F32 or HR_BF16: weights and activations */
+    float rope_base;
+    float rms_eps;
+} hr_model_cfg;
+
+/* Device pointers to the caller's weights.  The per-layer members are HOST arrays of n_layers
+ * DEVICE pointers.  Matrices are in the model dtype; norm gains are fp32. */
+typedef struct hr_weight_ptrs {
+    const void* embedding;        /* device [vocab][hidden] */
+    const float* final_norm;      /* device [hidden] */
+    const void* const* wq;        /* [n_q_heads*head_dim][hidden] */
+    const void* const* wk;        /* [n_kv_heads*head_dim][hidden] */
+    const void* const* wv;        /* [n_kv_heads*head_dim][hidden] */
+    const void* const* wo;        /* [hidden][n_q_heads*head_dim] */
+    const void* const* wg;        /* [ffn][hidden] */
+    const void* const* wu;        /* [ffn][hidden] */
+    const void* const* wd;        /* [hidden][ffn] */
+    const float* const* norm1;    /* [hidden] pre-attention gain */
+    const float* const* norm2;    /* [hidden] pre-MLP gain */
+} hr_weight_ptrs;
+
+typedef struct hr_pool hr_pool;     /* host-side handle: layout + page bookkeeping */
+typedef struct hr_model hr_model;   /* host-side handle: config + packed-weight pointers */
+
+const char* hr_status_str(int status);
+
+/* Text of the HIP error behind the calling thread's most recent HR_ERR_DEVICE ("" if none). */
+const char* hr_last_error(void);
+
+/* ---- document-KV pool (the stored per-document KV of Section 3.3 / 4.2, kept resident in HBM) ---- */
+
+/* Bytes of device memory a pool of this shape needs; 0 if cfg is invalid. */
+size_t hr_kv_pool_bytes(const hr_pool_cfg* cfg);
+
+/* Bind a pool to caller-owned device memory `dev_mem` (>= hr_kv_pool_bytes, 256-byte aligned).
+ * Pure host work: nothing is enqueued; all pages start free.  *out is freed by hr_kv_pool_destroy
+ * (which does not touch dev_mem). */
+int hr_kv_pool_create(const hr_pool_cfg* cfg, void* dev_mem, size_t bytes, hr_pool** out);
+void hr_kv_pool_destroy(hr_pool* pool);
+
+/* Number of free pages, or a negative status. */
+int64_t hr_kv_pool_free_pages(const hr_pool* pool);
+
+/* Reserve the n lowest-numbered free pages and return their ids in page_ids_out (host).  Reserved
+ * pages can be written once with hr_doc_kv_write and are released with hr_doc_kv_free. */
+int hr_kv_pool_alloc_pages(hr_pool* pool, int32_t n, int32_t* page_ids_out);
+
+/* Store one document's K/V (stage one of the two-stage inference) into the pages the caller names.
+ *   page_ids      host, ceil(doc_len/16) distinct ids, each free or reserved
+ *   k_dev, v_dev  device, logical layout [n_layers][doc_len][n_kv_heads][head_dim] in kv_dtype
+ *                 (fp8: E4M3 codes, one byte each); K is post-RoPE at positions 0..doc_len-1
+ *   k_scales_dev, v_scales_dev   fp8 only: device fp32 [n_layers][n_pages][n_kv_heads]; else NULL
+ * One HBM->HBM scatter kernel is enqueued on `stream`; the tail of a short last page is zeroed.
+ * The source buffers must stay valid until that kernel has run. */
+int hr_doc_kv_write(hr_pool* pool, int32_t doc_len, const int32_t* page_ids,
+                    const void* k_dev, const void* v_dev,
+                    const float* k_scales_dev, const float* v_scales_dev, void* stream);
+
+/* Mark pages free again (contents are left as they are). */
+int hr_doc_kv_free(hr_pool* pool, const int32_t* page_ids, int32_t n);
+
+/* ---- weights ---- */
+
+/* Bytes of device memory for the library's packed copy of the layer weights
+ * (fused QKV rows, interleaved gate/up rows); 0 if cfg is invalid. */
+size_t hr_weights_pack_bytes(const hr_model_cfg* cfg);
+
+/* Build the packed copy inside caller-owned `pack_dev` (copy kernels on `stream`) and return a
+ * handle.  The embedding and the norm gains are borrowed (must outlive the handle); the per-layer
+ * matrices may be released once `stream` has drained. */
+int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* weights,
+                    void* pack_dev, size_t pack_bytes, void* stream, hr_model** out);
+void hr_model_destroy(hr_model* model);
+
+/* ---- scoring (stage two: only the query suffix is computed) ---- */
+
+/* Workspace bytes for one hr_rerank_score call of this size; 0 on invalid arguments. */
+size_t hr_rerank_workspace_bytes(const hr_model* model, int32_t n_pairs, int64_t total_q_tokens,
+                                 int32_t pt_stride);
+
+/* scores[p] for p < n_pairs.  For pair p the query tokens sit at positions doc_lens[p] + 0,1,..,
+ * attend to all doc_lens[p] cached document keys (found through page_table row p) and causally to
+ * the query keys before them; the score is read at the last query token.
+ *   page_table    host int32 [n_pairs][pt_stride]; row p lists ceil(doc_lens[p]/16) written pages,
+ *                 the rest of the row is ignored (-1 by convention)
+ *   doc_lens      host int32 [n_pairs], each >= 0 (0: no cached document, plain causal pass)
+ *   query_tokens  host int32, the pairs' query token ids back to back (sum of query_lens entries)
+ *   query_lens    host int32 [n_pairs], each >= 1
+ *   workspace_dev device scratch, >= hr_rerank_workspace_bytes, 256-byte aligned, private to this
+ *                 call until `stream` has drained
+ *   scores_dev    device fp32 [n_pairs]
+ * The pool is only read.  Host arrays may be reused as soon as the call returns. */
+int hr_rerank_score(hr_model* model, const hr_pool* pool, int32_t n_pairs,
+                    const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
+                    const int32_t* query_tokens, const int32_t* query_lens,
+                    void* workspace_dev, size_t workspace_bytes, float* scores_dev, void* stream);
+
+/* The host-side checks hr_rerank_score performs before it enqueues anything, on their own: no
+ * device work, no model handle needed.  Returns HR_OK or the status hr_rerank_score would return
+ * for these arguments (lengths, page-table rows, page states, token ids, pool/model agreement). */
+int hr_rerank_validate(const hr_model_cfg* cfg, const hr_pool* pool, int32_t n_pairs,
+                       const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
+                       const int32_t* query_tokens, const int32_t* query_lens);
+
+/* ---- same-GPU reference without reuse: full prefill of [document ; query] per pair ---- */
+/* (Section 3.3 "Potential 1": what the scoring pass is compared with.) */
+size_t hr_rerank_full_workspace_bytes(const hr_model* model, int32_t n_pairs, int64_t total_tokens);
+
+/* scores[p] from one causal pass over the concatenation of doc_tokens and query_tokens of pair p;
+ * no pool is involved.  doc_tokens / query_tokens are flat host int32 arrays, pair after pair. */
+int hr_rerank_score_full(hr_model* model, int32_t n_pairs,
+                         const int32_t* doc_tokens, const int32_t* doc_lens,
+                         const int32_t* query_tokens, const int32_t* query_lens,
+                         void* workspace_dev, size_t workspace_bytes, float* scores_dev, void* stream);
+
+/* ---- introspection for benchmarks ---- */
+
+/* Name of the kernel family a model/pool combination runs ("generic", "mfma"); never NULL. */
+const char* hr_attention_path(const hr_model* model, const hr_pool* pool);
+const char* hr_gemm_path(const hr_model* model);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYPERRERANK_H */

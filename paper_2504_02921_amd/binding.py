@@ -1,0 +1,312 @@
+"""ctypes binding of libhyperrerank.so: the same entry points as include/hyperrerank.h.
+
+Only argument marshalling happens here.  PyTorch provides device memory and
+streams; every step of the scoring pass runs inside the library's HIP kernels.
+There is no fallback: if the shared library is missing, importing this module
+raises.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhyperrerank.so")
+
+HR_F32, HR_BF16, HR_FP8_E4M3 = 0, 1, 2
+DTYPE_CODE = {"f32": HR_F32, "bf16": HR_BF16, "fp8": HR_FP8_E4M3}
+PAGE_TOKENS = 16
+
+STATUS = {
+    0: "HR_OK", -1: "HR_ERR_INVALID_ARG", -2: "HR_ERR_POOL_TOO_SMALL", -3: "HR_ERR_PAGE_RANGE",
+    -4: "HR_ERR_PAGE_IN_USE", -5: "HR_ERR_PAGE_DUP", -6: "HR_ERR_LEN_RANGE", -7: "HR_ERR_TABLE_SHORT",
+    -8: "HR_ERR_TOKEN_RANGE", -9: "HR_ERR_WORKSPACE_SMALL", -10: "HR_ERR_UNSUPPORTED_SHAPE",
+    -11: "HR_ERR_DEVICE", -12: "HR_ERR_POOL_FULL", -13: "HR_ERR_MISMATCH",
+}
+HR_OK = 0
+for _code, _name in STATUS.items():
+    globals()[_name] = _code
+
+
+class hr_pool_cfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("page_tokens", C.c_int32), ("num_pages", C.c_int32), ("kv_dtype", C.c_int32)]
+
+
+class hr_model_cfg(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32),
+                ("yes_id", C.c_int32), ("no_id", C.c_int32), ("dtype", C.c_int32),
+                ("rope_base", C.c_float), ("rms_eps", C.c_float)]
+
+
+_PP = C.POINTER(C.c_void_p)
+
+
+class hr_weight_ptrs(C.Structure):
+    _fields_ = [("embedding", C.c_void_p), ("final_norm", C.c_void_p),
+                ("wq", _PP), ("wk", _PP), ("wv", _PP), ("wo", _PP), ("wg", _PP), ("wu", _PP), ("wd", _PP),
+                ("norm1", _PP), ("norm2", _PP)]
+
+
+EXPORTS = [
+    "hr_status_str", "hr_last_error", "hr_kv_pool_bytes", "hr_kv_pool_create", "hr_kv_pool_destroy", "hr_kv_pool_free_pages",
+    "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_free", "hr_weights_pack_bytes", "hr_weights_load",
+    "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_validate",
+    "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_attention_path", "hr_gemm_path",
+]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2504_02921_amd.build "
+                          "or __graft_entry__.build()); there is no CPU fallback")
+    # PyTorch ships its own HIP runtime; it must be the one this library binds to, or streams and
+    # allocations made by torch would belong to a different runtime instance.  Loading torch first
+    # puts its libamdhip64 (same soname) in the process before ours is resolved.
+    import torch  # noqa: F401
+    bundled = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    if os.path.exists(bundled):
+        C.CDLL(bundled, mode=C.RTLD_GLOBAL)
+    lib = C.CDLL(LIB_PATH)
+    i32p = C.POINTER(C.c_int32)
+    sig = {
+        "hr_status_str": (C.c_char_p, [C.c_int]),
+        "hr_last_error": (C.c_char_p, []),
+        "hr_kv_pool_bytes": (C.c_size_t, [C.POINTER(hr_pool_cfg)]),
+        "hr_kv_pool_create": (C.c_int, [C.POINTER(hr_pool_cfg), C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]),
+        "hr_kv_pool_destroy": (None, [C.c_void_p]),
+        "hr_kv_pool_free_pages": (C.c_int64, [C.c_void_p]),
+        "hr_kv_pool_alloc_pages": (C.c_int, [C.c_void_p, C.c_int32, i32p]),
+        "hr_doc_kv_write": (C.c_int, [C.c_void_p, C.c_int32, i32p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+        "hr_doc_kv_free": (C.c_int, [C.c_void_p, i32p, C.c_int32]),
+        "hr_weights_pack_bytes": (C.c_size_t, [C.POINTER(hr_model_cfg)]),
+        "hr_weights_load": (C.c_int, [C.POINTER(hr_model_cfg), C.POINTER(hr_weight_ptrs), C.c_void_p, C.c_size_t,
+                                      C.c_void_p, C.POINTER(C.c_void_p)]),
+        "hr_model_destroy": (None, [C.c_void_p]),
+        "hr_rerank_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int64, C.c_int32]),
+        "hr_rerank_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, i32p, C.c_int32, i32p, i32p, i32p,
+                                      C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+        "hr_rerank_validate": (C.c_int, [C.POINTER(hr_model_cfg), C.c_void_p, C.c_int32, i32p, C.c_int32, i32p, i32p, i32p]),
+        "hr_rerank_full_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int64]),
+        "hr_rerank_score_full": (C.c_int, [C.c_void_p, C.c_int32, i32p, i32p, i32p, i32p, C.c_void_p, C.c_size_t,
+                                           C.c_void_p, C.c_void_p]),
+        "hr_attention_path": (C.c_char_p, [C.c_void_p, C.c_void_p]),
+        "hr_gemm_path": (C.c_char_p, [C.c_void_p]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+lib = _load()
+
+
+class HrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        detail = lib.hr_last_error().decode() if status == -11 else ""
+        super().__init__(f"{where}: {STATUS.get(status, status)} ({lib.hr_status_str(status).decode()}) {detail}")
+
+
+def check(status: int, where: str) -> None:
+    if status != HR_OK:
+        raise HrError(status, where)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int32)
+
+
+def _i32p(a: Optional[np.ndarray]):
+    if a is None:
+        return None
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _stream_ptr(stream=None) -> C.c_void_p:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+# ----------------------------------------------------------------------------------------------
+# thin, same-named wrappers (raw pointers in, status out)
+# ----------------------------------------------------------------------------------------------
+def make_pool_cfg(n_layers, n_kv_heads, head_dim, num_pages, kv_dtype) -> hr_pool_cfg:
+    return hr_pool_cfg(n_layers, n_kv_heads, head_dim, PAGE_TOKENS, num_pages, DTYPE_CODE.get(kv_dtype, kv_dtype))
+
+
+def make_model_cfg(m) -> hr_model_cfg:
+    """m: any object with the ModelCfg fields of the workload generators."""
+    return hr_model_cfg(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab,
+                        m.yes_id, m.no_id, DTYPE_CODE[m.dtype], float(m.rope_base), float(m.rms_eps))
+
+
+def hr_kv_pool_bytes(cfg: hr_pool_cfg) -> int:
+    return int(lib.hr_kv_pool_bytes(C.byref(cfg)))
+
+
+def hr_kv_pool_create(cfg: hr_pool_cfg, dev_ptr: int, nbytes: int):
+    out = C.c_void_p()
+    st = lib.hr_kv_pool_create(C.byref(cfg), C.c_void_p(dev_ptr), nbytes, C.byref(out))
+    return st, out
+
+
+def hr_weights_pack_bytes(cfg: hr_model_cfg) -> int:
+    return int(lib.hr_weights_pack_bytes(C.byref(cfg)))
+
+
+# ----------------------------------------------------------------------------------------------
+# convenience holders: own the torch tensors behind the handles
+# ----------------------------------------------------------------------------------------------
+class KVPool:
+    """Device buffer + library handle of one paged document-KV pool."""
+
+    def __init__(self, n_layers: int, n_kv_heads: int, head_dim: int, num_pages: int, kv_dtype: str, device="cuda:0"):
+        import torch
+        self.cfg = make_pool_cfg(n_layers, n_kv_heads, head_dim, num_pages, kv_dtype)
+        self.kv_dtype = kv_dtype
+        nbytes = hr_kv_pool_bytes(self.cfg)
+        if nbytes == 0:
+            raise HrError(HR_ERR_INVALID_ARG, "hr_kv_pool_bytes")
+        self.mem = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+        st, self.handle = hr_kv_pool_create(self.cfg, self.mem.data_ptr(), nbytes)
+        check(st, "hr_kv_pool_create")
+
+    def write(self, doc_len: int, page_ids, k, v, k_scale=None, v_scale=None, stream=None) -> None:
+        """k, v: device tensors [L][doc_len][n_kv][d] in the pool dtype (uint8 codes for fp8)."""
+        ids = _i32(page_ids)
+        assert k.is_contiguous() and v.is_contiguous() and k.is_cuda and v.is_cuda
+        ks = C.c_void_p(k_scale.data_ptr()) if k_scale is not None else None
+        vs = C.c_void_p(v_scale.data_ptr()) if v_scale is not None else None
+        st = lib.hr_doc_kv_write(self.handle, int(doc_len), _i32p(ids), C.c_void_p(k.data_ptr()), C.c_void_p(v.data_ptr()),
+                                 ks, vs, _stream_ptr(stream))
+        check(st, "hr_doc_kv_write")
+
+    def free(self, page_ids) -> None:
+        ids = _i32(page_ids)
+        check(lib.hr_doc_kv_free(self.handle, _i32p(ids), len(ids)), "hr_doc_kv_free")
+
+    def alloc(self, n: int) -> np.ndarray:
+        out = np.zeros(n, np.int32)
+        check(lib.hr_kv_pool_alloc_pages(self.handle, n, _i32p(out)), "hr_kv_pool_alloc_pages")
+        return out
+
+    @property
+    def free_pages(self) -> int:
+        return int(lib.hr_kv_pool_free_pages(self.handle))
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib.hr_kv_pool_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+_LAYER_KINDS = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "norm1", "norm2")
+
+
+class Model:
+    """Uploads weights (numpy fp32 arrays holding values of the model dtype), packs them, keeps the handle."""
+
+    def __init__(self, model_cfg, weights, device="cuda:0"):
+        import torch
+        self.m = model_cfg
+        self.device = device
+        self.cfg = make_model_cfg(model_cfg)
+        tdt = torch.float32 if model_cfg.dtype == "f32" else torch.bfloat16
+
+        def up(a, dt):
+            return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device=device, dtype=dt)
+
+        self.embedding = up(weights.get("embedding", -1), tdt)
+        self.final_norm = up(weights.get("final_norm", -1), torch.float32)
+        L = model_cfg.n_layers
+        per_layer: Dict[str, List] = {k: [] for k in _LAYER_KINDS}
+        for l in range(L):
+            for k in _LAYER_KINDS:
+                per_layer[k].append(up(weights.get(k, l), torch.float32 if k.startswith("norm") else tdt))
+        self.norm1, self.norm2 = per_layer["norm1"], per_layer["norm2"]
+        arrays = {k: (C.c_void_p * L)(*[t.data_ptr() for t in per_layer[k]]) for k in _LAYER_KINDS}
+        ptrs = hr_weight_ptrs(self.embedding.data_ptr(), self.final_norm.data_ptr(),
+                              *[C.cast(arrays[k], _PP) for k in _LAYER_KINDS])
+        nbytes = hr_weights_pack_bytes(self.cfg)
+        if nbytes == 0:
+            raise HrError(HR_ERR_INVALID_ARG, "hr_weights_pack_bytes")
+        self.pack = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        out = C.c_void_p()
+        st = lib.hr_weights_load(C.byref(self.cfg), C.byref(ptrs), C.c_void_p(self.pack.data_ptr()), nbytes,
+                                 _stream_ptr(), C.byref(out))
+        check(st, "hr_weights_load")
+        self.handle = out
+        torch.cuda.synchronize()
+        del per_layer, arrays          # the matrices now live in the packed copy
+        self._ws = None
+
+    def _workspace(self, nbytes: int):
+        import torch
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = None
+            self._ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        return self._ws
+
+    def gemm_path(self) -> str:
+        return lib.hr_gemm_path(self.handle).decode()
+
+    def attention_path(self, pool: KVPool) -> str:
+        return lib.hr_attention_path(self.handle, pool.handle).decode()
+
+    def score(self, pool: KVPool, page_table, doc_lens, query_tokens, query_lens, out=None, stream=None):
+        import torch
+        pt = _i32(page_table)
+        if pt.ndim == 1:
+            pt = pt.reshape(len(doc_lens), -1)
+        dl, qt, ql = _i32(doc_lens), _i32(query_tokens), _i32(query_lens)
+        P = len(dl)
+        stride = pt.shape[1] if pt.ndim == 2 else 0
+        nbytes = int(lib.hr_rerank_workspace_bytes(self.handle, P, int(ql.sum()), stride))
+        ws = self._workspace(max(nbytes, 256))
+        scores = out if out is not None else torch.empty(max(P, 1), dtype=torch.float32, device=self.device)
+        st = lib.hr_rerank_score(self.handle, pool.handle, P, _i32p(pt), stride, _i32p(dl), _i32p(qt), _i32p(ql),
+                                 C.c_void_p(ws.data_ptr()), ws.numel(), C.c_void_p(scores.data_ptr()), _stream_ptr(stream))
+        check(st, "hr_rerank_score")
+        return scores[:P]
+
+    def score_full(self, doc_tokens: Sequence[np.ndarray], query_tokens: Sequence[np.ndarray], out=None, stream=None):
+        import torch
+        P = len(doc_tokens)
+        dl = _i32([len(d) for d in doc_tokens])
+        ql = _i32([len(q) for q in query_tokens])
+        dt = _i32(np.concatenate(doc_tokens)) if P and dl.sum() else np.zeros(1, np.int32)
+        qt = _i32(np.concatenate(query_tokens)) if P else np.zeros(1, np.int32)
+        total = int(dl.sum() + ql.sum())
+        nbytes = int(lib.hr_rerank_full_workspace_bytes(self.handle, P, total))
+        ws = self._workspace(max(nbytes, 256))
+        scores = out if out is not None else torch.empty(max(P, 1), dtype=torch.float32, device=self.device)
+        st = lib.hr_rerank_score_full(self.handle, P, _i32p(dt), _i32p(dl), _i32p(qt), _i32p(ql),
+                                      C.c_void_p(ws.data_ptr()), ws.numel(), C.c_void_p(scores.data_ptr()), _stream_ptr(stream))
+        check(st, "hr_rerank_score_full")
+        return scores[:P]
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib.hr_model_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,355 @@
+// Device-facing entry points of libhyperrerank: weight packing, pool writes and the layer loop of
+// the scoring pass (query suffix over cached document KV) and of the no-reuse reference pass.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "hr_internal.h"
+#include "hr_kernels.h"
+
+struct hr_model {
+    hr_model_cfg cfg;
+    hr::PackLayout pack;
+    const char* pack_base = nullptr;
+    const void* embedding = nullptr;
+    const float* final_norm = nullptr;
+    std::vector<const float*> norm1, norm2;
+    bool mfma_gemm = false;
+    // pinned staging for the per-call metadata upload
+    int32_t* stage = nullptr;
+    size_t stage_ints = 0;
+    hipEvent_t stage_ev = nullptr;
+    bool stage_pending = false;
+};
+
+namespace {
+
+using namespace hr;
+
+constexpr int64_t kGenericMaxKeys = 15000;     // scores of one row live in LDS in the generic attention
+constexpr int64_t kMfmaMaxKeys = 1 << 20;
+
+thread_local char g_last_error[256] = "";
+
+void note_hip_error(hipError_t e, const char* what) {
+    snprintf(g_last_error, sizeof(g_last_error), "%s: %s", what, hipGetErrorString(e));
+}
+
+#define HR_HIP(expr)                                   \
+    do {                                               \
+        hipError_t e__ = (expr);                       \
+        if (e__ != hipSuccess) {                       \
+            note_hip_error(e__, #expr);                \
+            return HR_ERR_DEVICE;                      \
+        }                                              \
+    } while (0)
+
+const void* layer_w(const hr_model* m, int l, size_t off) {
+    size_t esz = dtype_size(m->cfg.dtype);
+    return m->pack_base + ((size_t)l * m->pack.layer_elems + off) * esz;
+}
+
+int stage_reserve(hr_model* m, size_t ints) {
+    if (m->stage_pending) {
+        HR_HIP(hipEventSynchronize(m->stage_ev));
+        m->stage_pending = false;
+    }
+    if (ints > m->stage_ints) {
+        if (m->stage) (void)hipHostFree(m->stage);
+        m->stage = nullptr;
+        m->stage_ints = 0;
+        size_t want = std::max(ints, (size_t)1 << 16);
+        HR_HIP(hipHostMalloc((void**)&m->stage, want * sizeof(int32_t), hipHostMallocDefault));
+        m->stage_ints = want;
+    }
+    if (!m->stage_ev) HR_HIP(hipEventCreateWithFlags(&m->stage_ev, hipEventDisableTiming));
+    return HR_OK;
+}
+
+// One pass of all layers over the T new tokens described by `mv`, scores for every sequence.
+int run_layers(hr_model* m, const hr_pool* pool, const MetaView& mv, const Workspace& ws, char* wsb, int max_keys,
+               int max_new_len, float* scores, hipStream_t st) {
+    const hr_model_cfg& c = m->cfg;
+    const int dt = c.dtype;
+    const int H = c.hidden, d = c.head_dim, F = c.ffn;
+    const int nq = c.n_q_heads * d, nkv = c.n_kv_heads * d, nqkv = nq + 2 * nkv;
+    float* x = (float*)(wsb + ws.off_x);
+    void* y = wsb + ws.off_y;
+    void* q = wsb + ws.off_q;
+    void* k = wsb + ws.off_k;
+    void* v = wsb + ws.off_v;
+    void* o = wsb + ws.off_o;
+    void* mm = wsb + ws.off_m;
+    float* f32 = (float*)(wsb + ws.off_f32);
+    float2* rope = (float2*)(wsb + ws.off_rope);
+    const int64_t T = mv.T;
+
+    PoolView pv{};
+    pv.n_kv = c.n_kv_heads;
+    pv.d = d;
+    if (pool) {
+        pv.data = pool->base;
+        pv.scales = pool->cfg.kv_dtype == HR_FP8_E4M3 ? (const float*)(pool->base + pool->lay.data_bytes) : nullptr;
+        pv.num_pages = pool->cfg.num_pages;
+        pv.kv_dtype = pool->cfg.kv_dtype;
+        pv.esz = pool->lay.esz;
+    } else {
+        pv.kv_dtype = dt;
+        pv.esz = dtype_size(dt);
+        pv.num_pages = 1;
+    }
+    const bool mfma_attn = attn_mfma_supported(c, pv.kv_dtype, max_new_len);
+
+    HR_HIP(launch_embed(dt, m->embedding, mv, x, H, st));
+    HR_HIP(launch_rope_table(mv, rope, d, c.rope_base, st));
+    for (int l = 0; l < c.n_layers; ++l) {
+        HR_HIP(launch_rmsnorm(dt, x, m->norm1[l], y, T, H, c.rms_eps, st));
+        if (m->mfma_gemm) {
+            GemmArgs a{};
+            a.A = y; a.W = layer_w(m, l, m->pack.wqkv); a.M = T; a.N = nqkv; a.K = H;
+            a.out0 = q; a.out1 = k; a.out2 = v; a.rope = rope; a.n_q = c.n_q_heads; a.n_kv = c.n_kv_heads; a.d = d;
+            HR_HIP(launch_gemm_mfma(EPI_QKV_ROPE, a, st));
+        } else {
+            HR_HIP(launch_gemm_generic(dt, y, layer_w(m, l, m->pack.wqkv), f32, T, nqkv, H, false, st));
+            HR_HIP(launch_rope_split(dt, f32, rope, q, k, v, T, c.n_q_heads, c.n_kv_heads, d, st));
+        }
+        if (mfma_attn) HR_HIP(launch_attn_mfma(q, k, v, o, mv, pv, l, c.n_q_heads, max_new_len, st));
+        else HR_HIP(launch_attn_generic(dt, q, k, v, o, mv, pv, l, c.n_q_heads, max_keys, st));
+        if (m->mfma_gemm) {
+            GemmArgs a{};
+            a.A = o; a.W = layer_w(m, l, m->pack.wo); a.M = T; a.N = H; a.K = nq; a.x = x;
+            HR_HIP(launch_gemm_mfma(EPI_RESID_ADD, a, st));
+        } else {
+            HR_HIP(launch_gemm_generic(dt, o, layer_w(m, l, m->pack.wo), x, T, H, nq, true, st));
+        }
+        HR_HIP(launch_rmsnorm(dt, x, m->norm2[l], y, T, H, c.rms_eps, st));
+        if (m->mfma_gemm) {
+            GemmArgs a{};
+            a.A = y; a.W = layer_w(m, l, m->pack.wgu); a.M = T; a.N = 2 * F; a.K = H; a.out0 = mm;
+            HR_HIP(launch_gemm_mfma(EPI_SWIGLU, a, st));
+            GemmArgs b{};
+            b.A = mm; b.W = layer_w(m, l, m->pack.wd); b.M = T; b.N = H; b.K = F; b.x = x;
+            HR_HIP(launch_gemm_mfma(EPI_RESID_ADD, b, st));
+        } else {
+            HR_HIP(launch_gemm_generic(dt, y, layer_w(m, l, m->pack.wgu), f32, T, 2 * F, H, false, st));
+            HR_HIP(launch_swiglu(dt, f32, mm, T, F, m->pack.gu_interleave, st));
+            HR_HIP(launch_gemm_generic(dt, mm, layer_w(m, l, m->pack.wd), x, T, H, F, true, st));
+        }
+    }
+    HR_HIP(launch_score_head(dt, x, m->final_norm, m->embedding, mv, scores, H, c.rms_eps, c.yes_id, c.no_id, st));
+    return HR_OK;
+}
+
+MetaView make_meta_view(const int32_t* dev_meta, const MetaLayout& ml, int64_t n_seq, int64_t T, int64_t pt_stride) {
+    MetaView mv{};
+    mv.cu = dev_meta + ml.cu;
+    mv.tok_id = dev_meta + ml.tok_id;
+    mv.tok_pos = dev_meta + ml.tok_pos;
+    mv.tok_seq = dev_meta + ml.tok_seq;
+    mv.prefix_len = dev_meta + ml.prefix_len;
+    mv.page_table = dev_meta + ml.page_table;
+    mv.pt_stride = (int32_t)pt_stride;
+    mv.n_seq = (int32_t)n_seq;
+    mv.T = T;
+    return mv;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* w, void* pack_dev, size_t pack_bytes, void* stream,
+                    hr_model** out) {
+    if (!out) return HR_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!hr::model_cfg_valid(cfg) || !w || !pack_dev) return HR_ERR_INVALID_ARG;
+    if ((uintptr_t)pack_dev % hr::kAlign != 0) return HR_ERR_INVALID_ARG;
+    if (!w->embedding || !w->final_norm || !w->wq || !w->wk || !w->wv || !w->wo || !w->wg || !w->wu || !w->wd || !w->norm1 ||
+        !w->norm2)
+        return HR_ERR_INVALID_ARG;
+    for (int l = 0; l < cfg->n_layers; ++l)
+        if (!w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->wg[l] || !w->wu[l] || !w->wd[l] || !w->norm1[l] ||
+            !w->norm2[l])
+            return HR_ERR_INVALID_ARG;
+    hr::PackLayout pl = hr::make_pack_layout(*cfg);
+    if (pack_bytes < pl.total_bytes) return HR_ERR_WORKSPACE_SMALL;
+
+    hr_model* m = new (std::nothrow) hr_model();
+    if (!m) return HR_ERR_INVALID_ARG;
+    m->cfg = *cfg;
+    m->pack = pl;
+    m->pack_base = (const char*)pack_dev;
+    m->embedding = w->embedding;
+    m->final_norm = w->final_norm;
+    m->norm1.assign(w->norm1, w->norm1 + cfg->n_layers);
+    m->norm2.assign(w->norm2, w->norm2 + cfg->n_layers);
+    m->mfma_gemm = hr::gemm_mfma_supported(*cfg);
+
+    hipStream_t st = (hipStream_t)stream;
+    const int dt = cfg->dtype;
+    const size_t esz = hr::dtype_size(dt);
+    const int H = cfg->hidden, d = cfg->head_dim, F = cfg->ffn;
+    const int nq = cfg->n_q_heads * d, nkv = cfg->n_kv_heads * d;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        char* slab = (char*)pack_dev + (size_t)l * pl.layer_elems * esz;
+        char* wqkv = slab + pl.wqkv * esz;
+        hipError_t e = hr::launch_pack_rows(dt, w->wq[l], wqkv, nq, H, nq, 1, 0, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wk[l], wqkv + (size_t)nq * H * esz, nkv, H, nkv, 1, 0, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wv[l], wqkv + (size_t)(nq + nkv) * H * esz, nkv, H, nkv, 1, 0, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wo[l], slab + pl.wo * esz, H, nq, H, 1, 0, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wg[l], slab + pl.wgu * esz, F, H, pl.gu_interleave, 2, 0, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wu[l], slab + pl.wgu * esz, F, H, pl.gu_interleave, 2, 1, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wd[l], slab + pl.wd * esz, H, F, H, 1, 0, st);
+        if (e != hipSuccess) {
+            note_hip_error(e, "weight packing kernels");
+            delete m;
+            return HR_ERR_DEVICE;
+        }
+    }
+    *out = m;
+    return HR_OK;
+}
+
+void hr_model_destroy(hr_model* m) {
+    if (!m) return;
+    if (m->stage_pending) (void)hipEventSynchronize(m->stage_ev);
+    if (m->stage_ev) (void)hipEventDestroy(m->stage_ev);
+    if (m->stage) (void)hipHostFree(m->stage);
+    delete m;
+}
+
+int hr_doc_kv_write(hr_pool* pool, int32_t doc_len, const int32_t* page_ids, const void* k_dev, const void* v_dev,
+                    const float* ks, const float* vs, void* stream) {
+    int rc = hr::pool_check_write(pool, doc_len, page_ids);
+    if (rc != HR_OK) return rc;
+    if (!k_dev || !v_dev) return HR_ERR_INVALID_ARG;
+    bool fp8 = pool->cfg.kv_dtype == HR_FP8_E4M3;
+    if (fp8 && (!ks || !vs)) return HR_ERR_INVALID_ARG;
+    hipError_t e = hr::launch_kv_scatter(pool->lay, pool->base, page_ids, doc_len, k_dev, v_dev, ks, vs, (hipStream_t)stream);
+    if (e != hipSuccess) {
+        note_hip_error(e, "pool scatter kernel");
+        return HR_ERR_DEVICE;
+    }
+    hr::pool_mark(pool, page_ids, (doc_len + hr::kPageTokens - 1) / hr::kPageTokens, hr::PAGE_USED);
+    return HR_OK;
+}
+
+size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t total_q_tokens, int32_t pt_stride) {
+    if (!m || n_pairs < 0 || total_q_tokens < 0 || pt_stride < 0) return 0;
+    return hr::make_workspace(m->cfg, n_pairs, total_q_tokens, pt_stride, !m->mfma_gemm).total;
+}
+
+int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride,
+                    const int32_t* doc_lens, const int32_t* query_tokens, const int32_t* query_lens, void* workspace_dev,
+                    size_t workspace_bytes, float* scores_dev, void* stream) {
+    if (!m || !pool) return HR_ERR_INVALID_ARG;
+    int max_q = 0;
+    if (n_pairs > 0 && query_lens)
+        for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
+    const bool mfma_attn = hr::attn_mfma_supported(m->cfg, pool->cfg.kv_dtype, max_q);
+    int64_t T = 0;
+    int rc = hr::score_check_args(m->cfg, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens,
+                                  mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys, &T);
+    if (rc != HR_OK) return rc;
+    if (n_pairs == 0) return HR_OK;
+    if (!workspace_dev || !scores_dev) return HR_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace_dev % hr::kAlign != 0) return HR_ERR_INVALID_ARG;
+    hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm);
+    if (workspace_bytes < ws.total) return HR_ERR_WORKSPACE_SMALL;
+
+    hipStream_t st = (hipStream_t)stream;
+    hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, pt_stride);
+    rc = stage_reserve(m, ml.total);
+    if (rc != HR_OK) return rc;
+    hr::fill_meta(m->stage, ml, n_pairs, doc_lens, query_lens, query_tokens, page_table, pt_stride);
+    char* wsb = (char*)workspace_dev;
+    HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, m->stage, ml.total * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HR_HIP(hipEventRecord(m->stage_ev, st));
+    m->stage_pending = true;
+
+    int max_keys = 0;
+    for (int32_t p = 0; p < n_pairs; ++p) max_keys = std::max(max_keys, doc_lens[p] + query_lens[p]);
+    hr::MetaView mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, n_pairs, T, pt_stride);
+    return run_layers(m, pool, mv, ws, wsb, max_keys, max_q, scores_dev, st);
+}
+
+int hr_rerank_validate(const hr_model_cfg* cfg, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table,
+                       int32_t pt_stride, const int32_t* doc_lens, const int32_t* query_tokens, const int32_t* query_lens) {
+    if (!hr::model_cfg_valid(cfg) || !pool) return HR_ERR_INVALID_ARG;
+    int max_q = 0;
+    if (n_pairs > 0 && query_lens)
+        for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
+    const bool mfma_attn = hr::attn_mfma_supported(*cfg, pool->cfg.kv_dtype, max_q);
+    return hr::score_check_args(*cfg, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens,
+                                mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys, nullptr);
+}
+
+size_t hr_rerank_full_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t total_tokens) {
+    if (!m || n_pairs < 0 || total_tokens < 0) return 0;
+    return hr::make_workspace(m->cfg, n_pairs, total_tokens, 0, !m->mfma_gemm).total;
+}
+
+int hr_rerank_score_full(hr_model* m, int32_t n_pairs, const int32_t* doc_tokens, const int32_t* doc_lens,
+                         const int32_t* query_tokens, const int32_t* query_lens, void* workspace_dev, size_t workspace_bytes,
+                         float* scores_dev, void* stream) {
+    if (!m || n_pairs < 0) return HR_ERR_INVALID_ARG;
+    if (n_pairs == 0) return HR_OK;
+    if (!doc_lens || !query_lens || !query_tokens || !workspace_dev || !scores_dev) return HR_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace_dev % hr::kAlign != 0) return HR_ERR_INVALID_ARG;
+    int64_t T = 0, Td = 0;
+    int max_len = 0;
+    for (int32_t p = 0; p < n_pairs; ++p) {
+        if (doc_lens[p] < 0 || query_lens[p] <= 0) return HR_ERR_LEN_RANGE;
+        int64_t n = (int64_t)doc_lens[p] + query_lens[p];
+        if (n > kGenericMaxKeys) return HR_ERR_LEN_RANGE;
+        max_len = std::max(max_len, (int)n);
+        T += n;
+        Td += doc_lens[p];
+    }
+    if (T > (int64_t)1 << 30) return HR_ERR_LEN_RANGE;
+    if (Td > 0 && !doc_tokens) return HR_ERR_INVALID_ARG;
+    hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, 0, !m->mfma_gemm);
+    if (workspace_bytes < ws.total) return HR_ERR_WORKSPACE_SMALL;
+    // concatenated [doc ; query] token stream and its lengths
+    std::vector<int32_t> toks((size_t)T), lens((size_t)n_pairs);
+    {
+        int64_t t = 0, td = 0, tq = 0;
+        for (int32_t p = 0; p < n_pairs; ++p) {
+            for (int32_t i = 0; i < doc_lens[p]; ++i) toks[t++] = doc_tokens[td++];
+            for (int32_t i = 0; i < query_lens[p]; ++i) toks[t++] = query_tokens[tq++];
+            lens[p] = doc_lens[p] + query_lens[p];
+        }
+    }
+    for (int64_t t = 0; t < T; ++t)
+        if (toks[t] < 0 || toks[t] >= m->cfg.vocab) return HR_ERR_TOKEN_RANGE;
+
+    hipStream_t st = (hipStream_t)stream;
+    hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, 0);
+    int rc = stage_reserve(m, ml.total);
+    if (rc != HR_OK) return rc;
+    hr::fill_meta(m->stage, ml, n_pairs, nullptr, lens.data(), toks.data(), nullptr, 0);
+    char* wsb = (char*)workspace_dev;
+    HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, m->stage, ml.total * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HR_HIP(hipEventRecord(m->stage_ev, st));
+    m->stage_pending = true;
+    hr::MetaView mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, n_pairs, T, 0);
+    return run_layers(m, nullptr, mv, ws, wsb, max_len, max_len, scores_dev, st);
+}
+
+const char* hr_last_error(void) { return g_last_error; }
+
+const char* hr_attention_path(const hr_model* m, const hr_pool* pool) {
+    if (!m || !pool) return "none";
+    return hr::attn_mfma_supported(m->cfg, pool->cfg.kv_dtype, 1) ? "mfma" : "generic";
+}
+
+const char* hr_gemm_path(const hr_model* m) {
+    if (!m) return "none";
+    return m->mfma_gemm ? "mfma" : "generic";
+}
+
+}  // extern "C"

@@ -1,0 +1,263 @@
+// Host-only part of libhyperrerank: configuration checks, pool layout and page bookkeeping,
+// argument validation of the scoring call and the per-call metadata (schedule) builder.
+// No HIP calls here, so every error path can be exercised on a machine without a GPU.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "hr_internal.h"
+
+namespace hr {
+
+bool pool_cfg_valid(const hr_pool_cfg* c) {
+    if (!c) return false;
+    if (c->n_layers <= 0 || c->n_kv_heads <= 0 || c->num_pages <= 0) return false;
+    if (c->head_dim <= 0 || c->head_dim % 16 != 0 || c->head_dim > 256) return false;
+    if (c->page_tokens != kPageTokens) return false;
+    if (c->kv_dtype != HR_F32 && c->kv_dtype != HR_BF16 && c->kv_dtype != HR_FP8_E4M3) return false;
+    return true;
+}
+
+bool model_cfg_valid(const hr_model_cfg* c) {
+    if (!c) return false;
+    if (c->n_layers <= 0 || c->hidden <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0) return false;
+    if (c->n_q_heads % c->n_kv_heads != 0) return false;
+    if (c->head_dim <= 0 || c->head_dim % 16 != 0 || c->head_dim > 256) return false;
+    if (c->ffn <= 0 || c->vocab <= 0) return false;
+    if (c->hidden % 8 != 0 || c->ffn % 8 != 0) return false;
+    if (c->yes_id < 0 || c->yes_id >= c->vocab || c->no_id < 0 || c->no_id >= c->vocab) return false;
+    if (c->dtype != HR_F32 && c->dtype != HR_BF16) return false;
+    if (!(c->rope_base > 1.0f) || !(c->rms_eps >= 0.0f)) return false;
+    return true;
+}
+
+PoolLayout make_layout(const hr_pool_cfg& c) {
+    PoolLayout l;
+    l.n_layers = c.n_layers; l.n_kv = c.n_kv_heads; l.d = c.head_dim; l.num_pages = c.num_pages; l.kv_dtype = c.kv_dtype;
+    l.esz = dtype_size(c.kv_dtype);
+    l.block_elems = (size_t)kPageTokens * c.head_dim;
+    size_t blocks = (size_t)c.n_layers * c.num_pages * c.n_kv_heads * 2;
+    l.data_bytes = align_up(blocks * l.block_elems * l.esz);
+    l.scale_bytes = c.kv_dtype == HR_FP8_E4M3 ? align_up(blocks * sizeof(float)) : 0;
+    l.total_bytes = l.data_bytes + l.scale_bytes;
+    return l;
+}
+
+PackLayout make_pack_layout(const hr_model_cfg& c) {
+    PackLayout p;
+    size_t H = c.hidden, d = c.head_dim, F = c.ffn;
+    size_t nqkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * d;
+    // every slab starts on a 256-byte boundary for either element size
+    auto up = [](size_t e) { return (e + 127) / 128 * 128; };
+    p.wqkv = 0;
+    p.wo = up(p.wqkv + nqkv * H);
+    p.wgu = up(p.wo + H * (size_t)c.n_q_heads * d);
+    p.wd = up(p.wgu + 2 * F * H);
+    p.layer_elems = up(p.wd + H * F);
+    p.total_bytes = align_up(p.layer_elems * (size_t)c.n_layers * dtype_size(c.dtype));
+    p.gu_interleave = (c.ffn % 32 == 0) ? 32 : 1;
+    return p;
+}
+
+MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride) {
+    MetaLayout m;
+    auto up = [](size_t e) { return (e + 63) / 64 * 64; };
+    size_t o = 0;
+    m.cu = o;          o = up(o + (size_t)n_seq + 1);
+    m.tok_id = o;      o = up(o + (size_t)T);
+    m.tok_pos = o;     o = up(o + (size_t)T);
+    m.tok_seq = o;     o = up(o + (size_t)T);
+    m.prefix_len = o;  o = up(o + (size_t)n_seq);
+    m.page_table = o;  o = up(o + (size_t)n_seq * (size_t)pt_stride);
+    m.total = o;
+    return m;
+}
+
+Workspace make_workspace(const hr_model_cfg& c, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch) {
+    Workspace w;
+    size_t asz = dtype_size(c.dtype);
+    size_t H = c.hidden, d = c.head_dim, F = c.ffn;
+    size_t nq = (size_t)c.n_q_heads * d, nkv = (size_t)c.n_kv_heads * d;
+    size_t t = (size_t)T;
+    MetaLayout ml = make_meta_layout(n_seq, T, pt_stride);
+    w.meta_ints = ml.total;
+    size_t o = 0;
+    w.off_meta = o; o = align_up(o + ml.total * sizeof(int32_t));
+    w.off_rope = o; o = align_up(o + t * (d / 2) * 2 * sizeof(float));
+    w.off_x = o;    o = align_up(o + t * H * sizeof(float));
+    w.off_y = o;    o = align_up(o + t * H * asz);
+    w.off_q = o;    o = align_up(o + t * nq * asz);
+    w.off_k = o;    o = align_up(o + t * nkv * asz);
+    w.off_v = o;    o = align_up(o + t * nkv * asz);
+    w.off_o = o;    o = align_up(o + t * nq * asz);
+    w.off_m = o;    o = align_up(o + t * F * asz);
+    w.off_f32 = o;
+    if (need_f32_scratch) o = align_up(o + t * std::max(nq + 2 * nkv, 2 * F) * sizeof(float));
+    w.total = o;
+    return w;
+}
+
+int pool_check_write(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids) {
+    if (!pool || !page_ids) return HR_ERR_INVALID_ARG;
+    if (doc_len <= 0) return HR_ERR_LEN_RANGE;
+    int64_t n = ((int64_t)doc_len + kPageTokens - 1) / kPageTokens;
+    if (n > pool->cfg.num_pages) return HR_ERR_LEN_RANGE;
+    for (int64_t i = 0; i < n; ++i) {
+        int32_t p = page_ids[i];
+        if (p < 0 || p >= pool->cfg.num_pages) return HR_ERR_PAGE_RANGE;
+    }
+    for (int64_t i = 0; i < n; ++i)
+        if (pool->state[page_ids[i]] == PAGE_USED) return HR_ERR_PAGE_IN_USE;
+    // duplicates: sort a copy (documents have at most a few thousand pages)
+    std::vector<int32_t> s(page_ids, page_ids + n);
+    std::sort(s.begin(), s.end());
+    if (std::adjacent_find(s.begin(), s.end()) != s.end()) return HR_ERR_PAGE_DUP;
+    return HR_OK;
+}
+
+void pool_mark(hr_pool* pool, const int32_t* page_ids, int n, PageState st) {
+    for (int i = 0; i < n; ++i) {
+        uint8_t& cur = pool->state[page_ids[i]];
+        if (cur == PAGE_FREE && st != PAGE_FREE) pool->n_free--;
+        if (cur != PAGE_FREE && st == PAGE_FREE) pool->n_free++;
+        cur = st;
+    }
+}
+
+int score_check_args(const hr_model_cfg& mc, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table,
+                     int32_t pt_stride, const int32_t* doc_lens, const int32_t* query_tokens,
+                     const int32_t* query_lens, int64_t max_keys, int64_t* total_q_out) {
+    if (!pool || n_pairs < 0 || pt_stride < 0) return HR_ERR_INVALID_ARG;
+    if (n_pairs > 0 && (!doc_lens || !query_lens || !query_tokens)) return HR_ERR_INVALID_ARG;
+    if (pool->cfg.n_layers != mc.n_layers || pool->cfg.n_kv_heads != mc.n_kv_heads || pool->cfg.head_dim != mc.head_dim)
+        return HR_ERR_MISMATCH;
+    if (mc.dtype == HR_F32 && pool->cfg.kv_dtype != HR_F32) return HR_ERR_MISMATCH;
+    if (mc.dtype == HR_BF16 && pool->cfg.kv_dtype == HR_F32) return HR_ERR_MISMATCH;
+    int64_t T = 0;
+    for (int32_t p = 0; p < n_pairs; ++p) {
+        int32_t D = doc_lens[p], q = query_lens[p];
+        if (D < 0 || q <= 0) return HR_ERR_LEN_RANGE;
+        if ((int64_t)D + q > max_keys) return HR_ERR_LEN_RANGE;
+        int64_t np = ((int64_t)D + kPageTokens - 1) / kPageTokens;
+        if (np > pt_stride) return HR_ERR_TABLE_SHORT;
+        if (np > 0 && !page_table) return HR_ERR_INVALID_ARG;
+        const int32_t* row = page_table + (size_t)p * pt_stride;
+        for (int64_t i = 0; i < np; ++i) {
+            int32_t pg = row[i];
+            if (pg == -1) return HR_ERR_TABLE_SHORT;
+            if (pg < 0 || pg >= pool->cfg.num_pages) return HR_ERR_PAGE_RANGE;
+            if (pool->state[pg] != PAGE_USED) return HR_ERR_TABLE_SHORT;
+        }
+        T += q;
+    }
+    if (T > (int64_t)1 << 30) return HR_ERR_LEN_RANGE;
+    for (int64_t t = 0; t < T; ++t)
+        if (query_tokens[t] < 0 || query_tokens[t] >= mc.vocab) return HR_ERR_TOKEN_RANGE;
+    if (total_q_out) *total_q_out = T;
+    return HR_OK;
+}
+
+void fill_meta(int32_t* meta, const MetaLayout& ml, int64_t n_seq, const int32_t* prefix_lens,
+               const int32_t* new_lens, const int32_t* tokens, const int32_t* page_table, int64_t pt_stride) {
+    int32_t* cu = meta + ml.cu;
+    int32_t* tok_id = meta + ml.tok_id;
+    int32_t* tok_pos = meta + ml.tok_pos;
+    int32_t* tok_seq = meta + ml.tok_seq;
+    int32_t* pre = meta + ml.prefix_len;
+    int64_t t = 0;
+    cu[0] = 0;
+    for (int64_t p = 0; p < n_seq; ++p) {
+        int32_t D = prefix_lens ? prefix_lens[p] : 0;
+        pre[p] = D;
+        for (int32_t i = 0; i < new_lens[p]; ++i, ++t) {
+            tok_id[t] = tokens[t];
+            tok_pos[t] = D + i;       // positions continue right after the document
+            tok_seq[t] = (int32_t)p;
+        }
+        cu[p + 1] = (int32_t)t;
+    }
+    if (page_table && pt_stride > 0)
+        std::memcpy(meta + ml.page_table, page_table, sizeof(int32_t) * (size_t)n_seq * (size_t)pt_stride);
+}
+
+}  // namespace hr
+
+// ------------------------------------------------------------------------------------------------
+// C ABI: the calls that need no device work
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+const char* hr_status_str(int s) {
+    switch (s) {
+        case HR_OK: return "ok";
+        case HR_ERR_INVALID_ARG: return "invalid argument";
+        case HR_ERR_POOL_TOO_SMALL: return "pool buffer too small";
+        case HR_ERR_PAGE_RANGE: return "page id out of range";
+        case HR_ERR_PAGE_IN_USE: return "page already in use";
+        case HR_ERR_PAGE_DUP: return "duplicate page id";
+        case HR_ERR_LEN_RANGE: return "length out of range";
+        case HR_ERR_TABLE_SHORT: return "page table row too short or names an unwritten page";
+        case HR_ERR_TOKEN_RANGE: return "token id out of range";
+        case HR_ERR_WORKSPACE_SMALL: return "workspace too small";
+        case HR_ERR_UNSUPPORTED_SHAPE: return "unsupported shape";
+        case HR_ERR_DEVICE: return "device error";
+        case HR_ERR_POOL_FULL: return "not enough free pages";
+        case HR_ERR_MISMATCH: return "pool and model do not match";
+        default: return "unknown status";
+    }
+}
+
+size_t hr_kv_pool_bytes(const hr_pool_cfg* cfg) {
+    if (!hr::pool_cfg_valid(cfg)) return 0;
+    return hr::make_layout(*cfg).total_bytes;
+}
+
+int hr_kv_pool_create(const hr_pool_cfg* cfg, void* dev_mem, size_t bytes, hr_pool** out) {
+    if (!out) return HR_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!hr::pool_cfg_valid(cfg) || !dev_mem) return HR_ERR_INVALID_ARG;
+    if ((uintptr_t)dev_mem % hr::kAlign != 0) return HR_ERR_INVALID_ARG;
+    hr::PoolLayout lay = hr::make_layout(*cfg);
+    if (bytes < lay.total_bytes) return HR_ERR_POOL_TOO_SMALL;
+    hr_pool* p = new (std::nothrow) hr_pool();
+    if (!p) return HR_ERR_INVALID_ARG;
+    p->cfg = *cfg;
+    p->lay = lay;
+    p->base = (char*)dev_mem;
+    p->state.assign((size_t)cfg->num_pages, hr::PAGE_FREE);
+    p->n_free = cfg->num_pages;
+    *out = p;
+    return HR_OK;
+}
+
+void hr_kv_pool_destroy(hr_pool* pool) { delete pool; }
+
+int64_t hr_kv_pool_free_pages(const hr_pool* pool) {
+    if (!pool) return HR_ERR_INVALID_ARG;
+    return pool->n_free;
+}
+
+int hr_kv_pool_alloc_pages(hr_pool* pool, int32_t n, int32_t* out) {
+    if (!pool || !out || n <= 0) return HR_ERR_INVALID_ARG;
+    if (n > pool->n_free) return HR_ERR_POOL_FULL;
+    int32_t got = 0;
+    for (int32_t pg = 0; pg < pool->cfg.num_pages && got < n; ++pg)
+        if (pool->state[pg] == hr::PAGE_FREE) out[got++] = pg;
+    hr::pool_mark(pool, out, n, hr::PAGE_RESERVED);
+    return HR_OK;
+}
+
+int hr_doc_kv_free(hr_pool* pool, const int32_t* page_ids, int32_t n) {
+    if (!pool || n < 0 || (n > 0 && !page_ids)) return HR_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i)
+        if (page_ids[i] < 0 || page_ids[i] >= pool->cfg.num_pages) return HR_ERR_PAGE_RANGE;
+    hr::pool_mark(pool, page_ids, n, hr::PAGE_FREE);
+    return HR_OK;
+}
+
+size_t hr_weights_pack_bytes(const hr_model_cfg* cfg) {
+    if (!hr::model_cfg_valid(cfg)) return 0;
+    return hr::make_pack_layout(*cfg).total_bytes;
+}
+
+}  // extern "C"

@@ -1,0 +1,92 @@
+// Internal definitions shared by the host logic and the HIP engine of libhyperrerank.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "hyperrerank.h"
+
+namespace hr {
+
+constexpr int kPageTokens = HR_PAGE_TOKENS;
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+inline size_t dtype_size(int dt) { return dt == HR_F32 ? 4 : dt == HR_BF16 ? 2 : dt == HR_FP8_E4M3 ? 1 : 0; }
+
+enum PageState : uint8_t { PAGE_FREE = 0, PAGE_RESERVED = 1, PAGE_USED = 2 };
+
+// Physical arrangement of the pool (private to the library):
+//   data:   [layer][page][kv_head][K | V] blocks of 16 * head_dim elements.
+//           K block: [16 tokens][head_dim].
+//           V block: [head_dim][16 slots]; token t of the page sits in slot v_slot(t)
+//           (bits 2 and 3 of t swapped), which puts the 8 keys one MFMA lane consumes next to
+//           each other.
+//   scales: fp8 pools only, after the data: [layer][page][kv_head][2] fp32 (K scale, V scale).
+struct PoolLayout {
+    int n_layers = 0, n_kv = 0, d = 0, num_pages = 0, kv_dtype = 0;
+    size_t esz = 0;          // bytes per element
+    size_t block_elems = 0;  // 16 * d
+    size_t data_bytes = 0;   // aligned
+    size_t scale_bytes = 0;  // aligned, 0 unless fp8
+    size_t total_bytes = 0;
+
+    size_t block_index(int layer, int page, int kvh, int which) const {
+        return ((((size_t)layer * num_pages + page) * n_kv + kvh) * 2 + which);
+    }
+    size_t scale_index(int layer, int page, int kvh, int which) const { return block_index(layer, page, kvh, which); }
+};
+
+inline int v_slot(int t) { return (t & 3) | ((t & 4) << 1) | ((t & 8) >> 1); }
+
+bool pool_cfg_valid(const hr_pool_cfg* cfg);
+bool model_cfg_valid(const hr_model_cfg* cfg);
+PoolLayout make_layout(const hr_pool_cfg& cfg);
+
+// Packed weights of one layer (element offsets into the pack buffer).
+struct PackLayout {
+    size_t wqkv = 0, wo = 0, wgu = 0, wd = 0;   // element offsets within one layer's slab
+    size_t layer_elems = 0;
+    size_t total_bytes = 0;
+    int gu_interleave = 1;   // rows of gate / up alternate in blocks of this many
+};
+PackLayout make_pack_layout(const hr_model_cfg& cfg);
+
+// Workspace carving for one call over `n_seq` sequences and `T` new tokens.
+struct Workspace {
+    size_t meta_ints = 0;      // int32 count of the metadata block
+    size_t off_meta = 0, off_rope = 0, off_x = 0, off_y = 0, off_q = 0, off_k = 0, off_v = 0, off_o = 0,
+           off_m = 0, off_f32 = 0;
+    size_t total = 0;
+};
+// full_path: sequences carry their own document tokens (no page table).
+Workspace make_workspace(const hr_model_cfg& cfg, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch);
+
+// Metadata block layout (int32 offsets inside the block), uploaded once per call.
+struct MetaLayout {
+    size_t cu = 0, tok_id = 0, tok_pos = 0, tok_seq = 0, prefix_len = 0, page_table = 0, total = 0;
+};
+MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride);
+
+}  // namespace hr
+
+struct hr_pool {
+    hr_pool_cfg cfg;
+    hr::PoolLayout lay;
+    char* base = nullptr;
+    std::vector<uint8_t> state;
+    int64_t n_free = 0;
+};
+
+// Host-side validation / bookkeeping (no HIP calls), used by the engine and testable on a CPU.
+namespace hr {
+int pool_check_write(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids);
+void pool_mark(hr_pool* pool, const int32_t* page_ids, int n, PageState st);
+int score_check_args(const hr_model_cfg& mc, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table,
+                     int32_t pt_stride, const int32_t* doc_lens, const int32_t* query_tokens,
+                     const int32_t* query_lens, int64_t max_keys, int64_t* total_q_out);
+// Fills the metadata block for a call.  new_lens[p] tokens at positions prefix_lens[p]..; tokens flat.
+void fill_meta(int32_t* meta, const MetaLayout& ml, int64_t n_seq, const int32_t* prefix_lens,
+               const int32_t* new_lens, const int32_t* tokens, const int32_t* page_table, int64_t pt_stride);
+}  // namespace hr

@@ -1,0 +1,74 @@
+// Launchers of the HIP kernels (gfx950).  Every launcher enqueues on `st` and returns the HIP status
+// of the launch; none of them synchronises.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "hr_internal.h"
+
+namespace hr {
+
+// Per-layer view of the document-KV pool handed to attention kernels.
+struct PoolView {
+    const char* data;      // pool base
+    const float* scales;   // fp8 only, else nullptr
+    int num_pages, n_kv, d, kv_dtype;
+    size_t esz;
+};
+
+// Device-side view of the per-call metadata.
+struct MetaView {
+    const int32_t* cu;          // [n_seq + 1] start of each sequence's new tokens
+    const int32_t* tok_id;      // [T]
+    const int32_t* tok_pos;     // [T] RoPE position
+    const int32_t* tok_seq;     // [T] sequence of each token
+    const int32_t* prefix_len;  // [n_seq] cached-document length
+    const int32_t* page_table;  // [n_seq][pt_stride]
+    int32_t pt_stride;
+    int32_t n_seq;
+    int64_t T;
+};
+
+// ---- generic (any shape, VALU arithmetic in fp32) ----
+hipError_t launch_embed(int dtype, const void* E, const MetaView& mv, float* x, int H, hipStream_t st);
+hipError_t launch_rope_table(const MetaView& mv, float2* tab, int head_dim, float base, hipStream_t st);
+hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st);
+// C[M][N] (+)= A[M][K] * W[N][K]^T, C fp32
+hipError_t launch_gemm_generic(int dtype, const void* A, const void* W, float* C, int64_t M, int N, int K,
+                               bool accumulate, hipStream_t st);
+hipError_t launch_rope_split(int dtype, const float* qkv, const float2* tab, void* q, void* k, void* v, int64_t T,
+                             int n_q, int n_kv, int d, hipStream_t st);
+hipError_t launch_swiglu(int dtype, const float* gu, void* m, int64_t T, int F, int interleave, hipStream_t st);
+hipError_t launch_attn_generic(int dtype, const void* q, const void* k_new, const void* v_new, void* o,
+                               const MetaView& mv, const PoolView& pv, int layer, int n_q, int max_keys, hipStream_t st);
+hipError_t launch_score_head(int dtype, const float* x, const float* gain, const void* E, const MetaView& mv,
+                             float* scores, int H, float eps, int yes_id, int no_id, hipStream_t st);
+hipError_t launch_kv_scatter(const PoolLayout& lay, char* pool_base, const int32_t* page_ids_host, int doc_len,
+                             const void* k, const void* v, const float* ks, const float* vs, hipStream_t st);
+// dst row ((r / ib) * mul + sel) * ib + r % ib  <-  src row r   (rows of `cols` elements)
+hipError_t launch_pack_rows(int dtype, const void* src, void* dst, int rows, int cols, int ib, int mul, int sel,
+                            hipStream_t st);
+
+// ---- MFMA paths (bf16) ----
+bool gemm_mfma_supported(const hr_model_cfg& c);
+enum GemmEpilogue { EPI_QKV_ROPE = 0, EPI_RESID_ADD = 1, EPI_SWIGLU = 2 };
+struct GemmArgs {
+    const void* A;      // [M][K] bf16
+    const void* W;      // [N][K] bf16 (packed)
+    int64_t M;
+    int N, K;
+    // epilogue operands
+    float* x;           // EPI_RESID_ADD: fp32 [M][N], x += acc
+    void* out0;         // EPI_QKV_ROPE: q ; EPI_SWIGLU: m [M][N/2]
+    void* out1;         // EPI_QKV_ROPE: k
+    void* out2;         // EPI_QKV_ROPE: v
+    const float2* rope; // [M][d/2]
+    int n_q, n_kv, d;
+};
+hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st);
+
+bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len);
+hipError_t launch_attn_mfma(const void* q, const void* k_new, const void* v_new, void* o, const MetaView& mv,
+                            const PoolView& pv, int layer, int n_q, int max_q_len, hipStream_t st);
+
+}  // namespace hr

@@ -1,0 +1,416 @@
+// Shape-agnostic kernels of the scoring pass: fp32 VALU arithmetic, storage type templated.
+// They are the whole path for fp32 models and the fallback for shapes the MFMA kernels do not
+// cover; the elementwise ones (embedding gather, RMSNorm, RoPE table, scoring head, pool scatter,
+// weight packing) serve every path.
+#include <hip/hip_runtime.h>
+
+#include "hr_device_types.h"
+#include "hr_kernels.h"
+
+namespace hr {
+
+// ------------------------------------------------------------------------------------------------
+// embedding gather: x[t][:] = E[token[t]][:]   (fp32 residual stream)
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tok_id, float* __restrict__ x, int H) {
+    size_t t = blockIdx.x;
+    const T* src = E + (size_t)tok_id[t] * H;
+    float* dst = x + t * H;
+    for (int c = threadIdx.x; c < H; c += blockDim.x) dst[c] = to_float(src[c]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// RoPE table: tab[t][j] = (cos, sin)(pos[t] * base^(-2j/d)), angles in fp64, once per call
+// ------------------------------------------------------------------------------------------------
+__global__ void rope_table_kernel(const int32_t* __restrict__ tok_pos, float2* __restrict__ tab, int64_t T, int half,
+                                  double base) {
+    int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= T * half) return;
+    int64_t t = idx / half;
+    int j = (int)(idx - t * half);
+    double inv_freq = pow(base, -(double)j / (double)half);
+    double ang = (double)tok_pos[t] * inv_freq;
+    double s, c;
+    sincos(ang, &s, &c);
+    tab[idx] = make_float2((float)c, (float)s);
+}
+
+// ------------------------------------------------------------------------------------------------
+// RMSNorm: y = x * rsqrt(mean(x^2) + eps) * gain ; one 256-thread block per row
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+    v = wave_sum(v);
+    int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float r = red[0] + red[1] + red[2] + red[3];
+    __syncthreads();
+    return r;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                      T* __restrict__ y, int H, float eps) {
+    __shared__ float red[4];
+    size_t t = blockIdx.x;
+    const float* xr = x + t * H;
+    float ss = 0.f;
+    for (int c = threadIdx.x; c < H; c += 256) { float v = xr[c]; ss += v * v; }
+    ss = block_sum_256(ss, red);
+    float rs = 1.0f / sqrtf(ss / (float)H + eps);
+    T* yr = y + t * H;
+    for (int c = threadIdx.x; c < H; c += 256) yr[c] = from_float<T>(xr[c] * rs * gain[c]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// generic GEMM: C[M][N] (+)= A[M][K] W[N][K]^T, 64x64 tile, 256 threads x (4x4), fp32 FMA
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) gemm_generic_kernel(const T* __restrict__ A, const T* __restrict__ W,
+                                                           float* __restrict__ C, int64_t M, int N, int K, int accumulate) {
+    constexpr int BM = 64, BN = 64, BK = 16;
+    __shared__ float sA[BK][BM + 4];
+    __shared__ float sW[BK][BN + 4];
+    int64_t m0 = (int64_t)blockIdx.x * BM;
+    int n0 = blockIdx.y * BN;
+    int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    float acc[4][4] = {};
+    int lr = threadIdx.x >> 2;         // 0..63 tile row loaded by this thread
+    int lc = (threadIdx.x & 3) * 4;    // 0,4,8,12 first of 4 k's
+    for (int k0 = 0; k0 < K; k0 += BK) {
+        for (int u = 0; u < 4; ++u) {
+            int kk = k0 + lc + u;
+            int64_t am = m0 + lr;
+            int wn = n0 + lr;
+            sA[lc + u][lr] = (am < M && kk < K) ? to_float(A[am * K + kk]) : 0.f;
+            sW[lc + u][lr] = (wn < N && kk < K) ? to_float(W[(size_t)wn * K + kk]) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < BK; ++kk) {
+            float a[4], w[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = sA[kk][ty * 4 + i]; w[i] = sW[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+    for (int i = 0; i < 4; ++i) {
+        int64_t m = m0 + ty * 4 + i;
+        if (m >= M) continue;
+        for (int j = 0; j < 4; ++j) {
+            int n = n0 + tx * 4 + j;
+            if (n >= N) continue;
+            float* c = C + m * N + n;
+            *c = accumulate ? (*c + acc[i][j]) : acc[i][j];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// RoPE + split of the fused projection: qkv fp32 [T][(n_q + 2 n_kv) d] -> q, k (rotated), v
+// rotate-half pairing (j, j + d/2); one block per token
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void rope_split_kernel(const float* __restrict__ qkv, const float2* __restrict__ tab, T* __restrict__ q,
+                                  T* __restrict__ k, T* __restrict__ v, int n_q, int n_kv, int d) {
+    size_t t = blockIdx.x;
+    int half = d / 2;
+    int nqkv = (n_q + 2 * n_kv) * d;
+    const float* row = qkv + t * nqkv;
+    const float2* tr = tab + t * half;
+    int rot_heads = n_q + n_kv;
+    for (int idx = threadIdx.x; idx < rot_heads * half; idx += blockDim.x) {
+        int hd = idx / half, j = idx - hd * half;
+        float x1 = row[hd * d + j], x2 = row[hd * d + j + half];
+        float2 cs = tr[j];
+        float o1 = x1 * cs.x - x2 * cs.y;
+        float o2 = x2 * cs.x + x1 * cs.y;
+        T* dst = hd < n_q ? q + (t * n_q + hd) * d : k + (t * n_kv + (hd - n_q)) * d;
+        dst[j] = from_float<T>(o1);
+        dst[j + half] = from_float<T>(o2);
+    }
+    const float* vr = row + (size_t)rot_heads * d;
+    for (int idx = threadIdx.x; idx < n_kv * d; idx += blockDim.x) v[t * n_kv * d + idx] = from_float<T>(vr[idx]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// SwiGLU on the fused gate/up projection (rows interleaved in blocks of `ib`)
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void swiglu_kernel(const float* __restrict__ gu, T* __restrict__ m, int F, int ib) {
+    size_t t = blockIdx.x;
+    const float* row = gu + t * 2 * F;
+    for (int f = threadIdx.x; f < F; f += blockDim.x) {
+        int base = (f / ib) * 2 * ib + f % ib;
+        float g = row[base], u = row[base + ib];
+        m[t * F + f] = from_float<T>(g / (1.0f + expf(-g)) * u);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// generic prefix + causal attention: one wave per (new token, q head)
+//   pass 1: lanes split the keys, scores to LDS; pass 2: lanes split head_dim
+// ------------------------------------------------------------------------------------------------
+template <typename KVT>
+__device__ __forceinline__ float kv_load(const KVT* p, size_t i) { return to_float(p[i]); }
+template <>
+__device__ __forceinline__ float kv_load<uint8_t>(const uint8_t* p, size_t i) { return e4m3_to_float(p[i]); }
+
+template <typename T, typename KVT>
+__global__ void __launch_bounds__(64) attn_generic_kernel(const T* __restrict__ q, const T* __restrict__ k_new,
+                                                         const T* __restrict__ v_new, T* __restrict__ o, MetaView mv,
+                                                         PoolView pv, int layer, int n_q) {
+    extern __shared__ float sm[];
+    const int d = pv.d, n_kv = pv.n_kv, g = n_q / n_kv;
+    float* sq = sm;
+    float* ss = sm + d;
+    const int lane = threadIdx.x;
+    const size_t t = blockIdx.x;
+    const int a = blockIdx.y, h = a / g;
+    const int p = mv.tok_seq[t];
+    const int t0 = mv.cu[p];
+    const int i = (int)t - t0;
+    const int D = mv.prefix_len[p];
+    const int nkeys = D + i + 1;
+    const float scale = 1.0f / sqrtf((float)d);
+    const int32_t* pt = mv.page_table + (size_t)p * mv.pt_stride;
+    const KVT* pool = (const KVT*)pv.data;
+    const size_t blk = (size_t)kPageTokens * d;
+
+    for (int c = lane; c < d; c += 64) sq[c] = to_float(q[(t * n_q + a) * d + c]);
+    __syncthreads();
+
+    float mx = -INFINITY;
+    for (int j = lane; j < nkeys; j += 64) {
+        float s = 0.f;
+        if (j < D) {
+            int page = pt[j >> 4], slot = j & 15;
+            size_t bi = ((((size_t)layer * pv.num_pages + page) * n_kv + h) * 2 + 0);
+            const KVT* kr = pool + bi * blk + (size_t)slot * d;
+            for (int c = 0; c < d; ++c) s = fmaf(sq[c], kv_load<KVT>(kr, c), s);
+            if (pv.scales) s *= pv.scales[bi];
+        } else {
+            const T* kr = k_new + ((size_t)(t0 + j - D) * n_kv + h) * d;
+            for (int c = 0; c < d; ++c) s = fmaf(sq[c], to_float(kr[c]), s);
+        }
+        s *= scale;
+        ss[j] = s;
+        mx = fmaxf(mx, s);
+    }
+    mx = wave_max(mx);
+    float sum = 0.f;
+    for (int j = lane; j < nkeys; j += 64) {
+        float e = expf(ss[j] - mx);
+        ss[j] = e;
+        sum += e;
+    }
+    sum = wave_sum(sum);
+    __syncthreads();
+    const float inv = 1.0f / sum;
+    const int n_pages = (D + kPageTokens - 1) / kPageTokens;
+    for (int c = lane; c < d; c += 64) {
+        float acc = 0.f;
+        for (int pg = 0; pg < n_pages; ++pg) {
+            int page = pt[pg];
+            size_t bi = ((((size_t)layer * pv.num_pages + page) * n_kv + h) * 2 + 1);
+            const KVT* vb = pool + bi * blk + (size_t)c * kPageTokens;
+            float part = 0.f;
+            int lim = min(kPageTokens, D - pg * kPageTokens);
+            for (int tk = 0; tk < lim; ++tk) {
+                int slot = (tk & 3) | ((tk & 4) << 1) | ((tk & 8) >> 1);
+                part = fmaf(ss[pg * kPageTokens + tk], kv_load<KVT>(vb, slot), part);
+            }
+            acc += pv.scales ? part * pv.scales[bi] : part;
+        }
+        for (int j = 0; j <= i; ++j) acc = fmaf(ss[D + j], to_float(v_new[((size_t)(t0 + j) * n_kv + h) * d + c]), acc);
+        o[(t * n_q + a) * d + c] = from_float<T>(acc * inv);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// scoring head: final RMSNorm on each sequence's last token, then <y, E[yes]> - <y, E[no]>
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) score_head_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                         const T* __restrict__ E, const int32_t* __restrict__ cu,
+                                                         float* __restrict__ scores, int H, float eps, int yes_id, int no_id) {
+    __shared__ float red[4];
+    int p = blockIdx.x;
+    const float* xr = x + (size_t)(cu[p + 1] - 1) * H;
+    float ssq = 0.f;
+    for (int c = threadIdx.x; c < H; c += 256) { float v = xr[c]; ssq += v * v; }
+    ssq = block_sum_256(ssq, red);
+    float rs = 1.0f / sqrtf(ssq / (float)H + eps);
+    const T* ey = E + (size_t)yes_id * H;
+    const T* en = E + (size_t)no_id * H;
+    float acc = 0.f;
+    for (int c = threadIdx.x; c < H; c += 256) acc += xr[c] * rs * gain[c] * (to_float(ey[c]) - to_float(en[c]));
+    acc = block_sum_256(acc, red);
+    if (threadIdx.x == 0) scores[p] = acc;
+}
+
+// ------------------------------------------------------------------------------------------------
+struct PageIdChunk { int32_t ids[256]; };   // page ids travel as kernel arguments: no device staging
+
+// pool write: logical [L][D][n_kv][d] -> pages (K row-major, V transposed with slot swizzle), tail zeroed
+// grid: (n_pages, n_layers * n_kv); 256 threads
+// ------------------------------------------------------------------------------------------------
+template <typename KVT>
+__global__ void __launch_bounds__(256) kv_scatter_kernel(KVT* __restrict__ pool, float* __restrict__ scales,
+                                                         PageIdChunk page_ids, int pg0, int doc_len, int n_pages,
+                                                         const KVT* __restrict__ k, const KVT* __restrict__ v,
+                                                         const float* __restrict__ ks, const float* __restrict__ vs,
+                                                         int num_pages, int n_kv, int d) {
+    int pg = pg0 + blockIdx.x;
+    int layer = blockIdx.y / n_kv, h = blockIdx.y % n_kv;
+    int page = page_ids.ids[blockIdx.x];
+    size_t blk = (size_t)kPageTokens * d;
+    size_t bi = (((size_t)layer * num_pages + page) * n_kv + h) * 2;
+    KVT* kb = pool + bi * blk;
+    KVT* vb = kb + blk;
+    for (int e = threadIdx.x; e < (int)blk; e += 256) {
+        int tk = e / d, c = e - tk * d;
+        int tok = pg * kPageTokens + tk;
+        KVT kvl = KVT(0), vvl = KVT(0);
+        if (tok < doc_len) {
+            size_t src = (((size_t)layer * doc_len + tok) * n_kv + h) * d + c;
+            kvl = k[src];
+            vvl = v[src];
+        }
+        kb[e] = kvl;
+        int slot = (tk & 3) | ((tk & 4) << 1) | ((tk & 8) >> 1);
+        vb[c * kPageTokens + slot] = vvl;
+    }
+    if (scales && threadIdx.x == 0) {
+        size_t si = ((size_t)layer * n_pages + pg) * n_kv + h;
+        scales[bi] = ks[si];
+        scales[bi + 1] = vs[si];
+    }
+}
+
+template <typename T>
+__global__ void pack_rows_kernel(const T* __restrict__ src, T* __restrict__ dst, int rows, int cols, int ib, int mul, int sel) {
+    int r = blockIdx.x;
+    size_t drow = ((size_t)(r / ib) * mul + sel) * ib + r % ib;
+    for (int c = threadIdx.x; c < cols; c += blockDim.x) dst[drow * cols + c] = src[(size_t)r * cols + c];
+}
+
+// ------------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------------
+#define HR_DISPATCH_ACT(dtype, ...)                                   \
+    do {                                                              \
+        if ((dtype) == HR_F32) { using AT = float; __VA_ARGS__; }      \
+        else { using AT = bf16_t; __VA_ARGS__; }                       \
+    } while (0)
+
+hipError_t launch_embed(int dtype, const void* E, const MetaView& mv, float* x, int H, hipStream_t st) {
+    if (mv.T == 0) return hipSuccess;
+    HR_DISPATCH_ACT(dtype, embed_kernel<AT><<<dim3((unsigned)mv.T), 256, 0, st>>>((const AT*)E, mv.tok_id, x, H));
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_table(const MetaView& mv, float2* tab, int head_dim, float base, hipStream_t st) {
+    if (mv.T == 0) return hipSuccess;
+    int half = head_dim / 2;
+    int64_t n = mv.T * half;
+    rope_table_kernel<<<dim3((unsigned)((n + 255) / 256)), 256, 0, st>>>(mv.tok_pos, tab, mv.T, half, (double)base);
+    return hipGetLastError();
+}
+
+hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st) {
+    if (T == 0) return hipSuccess;
+    HR_DISPATCH_ACT(dtype, rmsnorm_kernel<AT><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (AT*)y, H, eps));
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_generic(int dtype, const void* A, const void* W, float* C, int64_t M, int N, int K, bool accumulate,
+                               hipStream_t st) {
+    if (M == 0) return hipSuccess;
+    dim3 grid((unsigned)((M + 63) / 64), (unsigned)((N + 63) / 64));
+    HR_DISPATCH_ACT(dtype, gemm_generic_kernel<AT><<<grid, 256, 0, st>>>((const AT*)A, (const AT*)W, C, M, N, K, accumulate ? 1 : 0));
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_split(int dtype, const float* qkv, const float2* tab, void* q, void* k, void* v, int64_t T, int n_q,
+                             int n_kv, int d, hipStream_t st) {
+    if (T == 0) return hipSuccess;
+    HR_DISPATCH_ACT(dtype, rope_split_kernel<AT><<<dim3((unsigned)T), 256, 0, st>>>(qkv, tab, (AT*)q, (AT*)k, (AT*)v, n_q, n_kv, d));
+    return hipGetLastError();
+}
+
+hipError_t launch_swiglu(int dtype, const float* gu, void* m, int64_t T, int F, int interleave, hipStream_t st) {
+    if (T == 0) return hipSuccess;
+    HR_DISPATCH_ACT(dtype, swiglu_kernel<AT><<<dim3((unsigned)T), 256, 0, st>>>(gu, (AT*)m, F, interleave));
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_generic(int dtype, const void* q, const void* k_new, const void* v_new, void* o, const MetaView& mv,
+                               const PoolView& pv, int layer, int n_q, int max_keys, hipStream_t st) {
+    if (mv.T == 0) return hipSuccess;
+    dim3 grid((unsigned)mv.T, (unsigned)n_q);
+    size_t lds = (size_t)(pv.d + max_keys) * sizeof(float);
+    if (dtype == HR_F32) {
+        attn_generic_kernel<float, float><<<grid, 64, lds, st>>>((const float*)q, (const float*)k_new, (const float*)v_new,
+                                                                 (float*)o, mv, pv, layer, n_q);
+    } else if (pv.kv_dtype == HR_FP8_E4M3) {
+        attn_generic_kernel<bf16_t, uint8_t><<<grid, 64, lds, st>>>((const bf16_t*)q, (const bf16_t*)k_new,
+                                                                    (const bf16_t*)v_new, (bf16_t*)o, mv, pv, layer, n_q);
+    } else {
+        attn_generic_kernel<bf16_t, bf16_t><<<grid, 64, lds, st>>>((const bf16_t*)q, (const bf16_t*)k_new,
+                                                                   (const bf16_t*)v_new, (bf16_t*)o, mv, pv, layer, n_q);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_score_head(int dtype, const float* x, const float* gain, const void* E, const MetaView& mv, float* scores,
+                             int H, float eps, int yes_id, int no_id, hipStream_t st) {
+    if (mv.n_seq == 0) return hipSuccess;
+    HR_DISPATCH_ACT(dtype, score_head_kernel<AT><<<dim3((unsigned)mv.n_seq), 256, 0, st>>>(x, gain, (const AT*)E, mv.cu, scores, H,
+                                                                                        eps, yes_id, no_id));
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_scatter(const PoolLayout& lay, char* pool_base, const int32_t* page_ids_host, int doc_len, const void* k,
+                             const void* v, const float* ks, const float* vs, hipStream_t st) {
+    int n_pages = (doc_len + kPageTokens - 1) / kPageTokens;
+    float* scales = lay.kv_dtype == HR_FP8_E4M3 ? (float*)(pool_base + lay.data_bytes) : nullptr;
+    for (int pg0 = 0; pg0 < n_pages; pg0 += 256) {
+        int n = n_pages - pg0 < 256 ? n_pages - pg0 : 256;
+        PageIdChunk ids;
+        for (int i = 0; i < 256; ++i) ids.ids[i] = i < n ? page_ids_host[pg0 + i] : 0;
+        dim3 grid((unsigned)n, (unsigned)(lay.n_layers * lay.n_kv));
+        if (lay.kv_dtype == HR_F32)
+            kv_scatter_kernel<float><<<grid, 256, 0, st>>>((float*)pool_base, nullptr, ids, pg0, doc_len, n_pages,
+                                                           (const float*)k, (const float*)v, nullptr, nullptr, lay.num_pages,
+                                                           lay.n_kv, lay.d);
+        else if (lay.kv_dtype == HR_BF16)
+            kv_scatter_kernel<uint16_t><<<grid, 256, 0, st>>>((uint16_t*)pool_base, nullptr, ids, pg0, doc_len, n_pages,
+                                                              (const uint16_t*)k, (const uint16_t*)v, nullptr, nullptr,
+                                                              lay.num_pages, lay.n_kv, lay.d);
+        else
+            kv_scatter_kernel<uint8_t><<<grid, 256, 0, st>>>((uint8_t*)pool_base, scales, ids, pg0, doc_len, n_pages,
+                                                             (const uint8_t*)k, (const uint8_t*)v, ks, vs, lay.num_pages,
+                                                             lay.n_kv, lay.d);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_pack_rows(int dtype, const void* src, void* dst, int rows, int cols, int ib, int mul, int sel,
+                            hipStream_t st) {
+    if (dtype == HR_F32)
+        pack_rows_kernel<float><<<dim3((unsigned)rows), 256, 0, st>>>((const float*)src, (float*)dst, rows, cols, ib, mul, sel);
+    else
+        pack_rows_kernel<uint16_t><<<dim3((unsigned)rows), 256, 0, st>>>((const uint16_t*)src, (uint16_t*)dst, rows, cols, ib,
+                                                                         mul, sel);
+    return hipGetLastError();
+}
+
+}  // namespace hr
