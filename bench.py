@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the reranker scoring pass (query suffix over cached document KV) on one MI355X.
+
+One "step" = one hr_rerank_score call over the whole workload (all pairs, all layers), inputs
+(weights, document-KV pool) resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_qwen0p5b]
+
+Besides the headline pairs/s the line carries
+  roofline            the kernel class with the largest share of the step (per-kernel HIP events,
+                      recorded by the library on the stream it launches on, during the timed steps)
+  roofline_attention  the KV-streaming attention kernel against HBM peak
+  cpu_baseline        the CPU oracle timed on a bounded sample of the same pairs
+  no_reuse            the same GPU running the full [doc ; query] prefill on a few pairs
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2_qwen0p5b")
+    ap.add_argument("--cpu-pairs", type=int, default=0, help="pairs for the CPU-oracle leg (0 = pick for ~15 s)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-reuse-pairs", type=int, default=16, help="pairs for the no-reuse reference (0 = skip)")
+    ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events during the timed steps")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build measures ONE GPU only (pairs shard over GPUs with no collective; see DESIGN.md). "
+            "Run with --gpus 1.")
+        sys.exit(2)
+
+    import torch
+    from paper_2504_02921_amd import binding as hb
+    from paper_2504_02921_amd import workloads as wlmod
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    cfg = wlmod.CONFIGS[args.workload]
+    m = cfg.model
+    t0 = time.time()
+    wl = wlmod.make_workload(cfg)
+    weights = wlmod.SeededWeights(m, seed=cfg.seed)
+    model = hb.Model(m, weights, dev)
+    pool = hb.KVPool(m.n_layers, m.n_kv_heads, m.head_dim, wl.num_pages, cfg.kv_dtype, dev)
+    for d in range(wl.n_docs):
+        kv = wlmod.synthetic_doc_kv(wl, d, dev)
+        if cfg.kv_dtype == "fp8":
+            pool.write(int(wl.pool_doc_lens[d]), wl.pool_doc_pages[d], kv["k"], kv["v"], kv["k_scale"], kv["v_scale"])
+        else:
+            pool.write(int(wl.pool_doc_lens[d]), wl.pool_doc_pages[d], kv["k"], kv["v"])
+        torch.cuda.synchronize()
+    log(f"setup {time.time() - t0:.1f}s: {wl.n_pairs} pairs, {wl.total_q_tokens} query tokens, pool {pool.mem.numel() / 1e9:.2f} GB, "
+        f"gemm={model.gemm_path()} attention={model.attention_path(pool)}")
+
+    scores = torch.empty(wl.n_pairs, dtype=torch.float32, device=dev)
+
+    def step():
+        model.score(pool, wl.page_table, wl.doc_lens, wl.query_tokens, wl.query_lens, out=scores)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    model.profile_enable(not args.no_events)
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t1
+    prof = model.profile_read() if not args.no_events else {}
+    model.profile_enable(False)
+    ms_per_step = dt / args.steps * 1e3
+    pairs_per_s = wl.n_pairs / (dt / args.steps)
+    assert bool(torch.isfinite(scores).all()), "non-finite scores"
+
+    # ---- rooflines from the per-kernel events ------------------------------------------------
+    T = wl.total_q_tokens
+    H, d, F = m.hidden, m.head_dim, m.ffn
+    nq = m.n_q_heads * d
+    flop_per_launch = {
+        "gemm_qkv": 2.0 * T * H * m.qkv_out, "gemm_o": 2.0 * T * nq * H,
+        "gemm_gate_up": 2.0 * T * H * 2 * F, "gemm_down": 2.0 * T * F * H,
+    }
+    kv_bytes_per_launch = wl.kv_stream_bytes() / m.n_layers
+    roofline = None
+    roof_attn = None
+    breakdown = {}
+    if prof:
+        total_ms = sum(v["ms"] for v in prof.values()) or 1.0
+        for name, v in prof.items():
+            if v["launches"]:
+                breakdown[name] = {"ms_per_step": round(v["ms"] / args.steps, 4), "launches_per_step": v["launches"] // args.steps,
+                                   "share": round(v["ms"] / total_ms, 4)}
+        dominant = max(prof, key=lambda k: prof[k]["ms"])
+
+        def gemm_roof(name):
+            avg_s = prof[name]["ms"] / prof[name]["launches"] * 1e-3
+            if model.gemm_path() == "mfma":
+                ach = flop_per_launch[name] / avg_s / 1e12
+                return {"kernel": name, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "avg_launch_ms": round(avg_s * 1e3, 4)}
+            ach = flop_per_launch[name] / avg_s / 1e12
+            return {"kernel": name, "bound": "alu", "achieved": round(ach, 3), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": None, "avg_launch_ms": round(avg_s * 1e3, 4)}
+
+        def attn_roof():
+            avg_s = prof["attention"]["ms"] / prof["attention"]["launches"] * 1e-3
+            ach = kv_bytes_per_launch / avg_s / 1e9
+            return {"kernel": "attention", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "avg_launch_ms": round(avg_s * 1e3, 4),
+                    "algorithmic_bytes_per_launch": int(kv_bytes_per_launch)}
+
+        roof_attn = attn_roof()
+        roofline = roof_attn if dominant == "attention" else gemm_roof(dominant if dominant in flop_per_launch else "gemm_gate_up")
+        gemm_ms = sum(prof[k]["ms"] for k in flop_per_launch)
+        gemm_all = {"achieved_tflops": round(sum(flop_per_launch.values()) * m.n_layers * args.steps / (gemm_ms * 1e-3) / 1e12, 2)}
+    else:
+        gemm_all = None
+
+    # ---- same-GPU no-reuse reference on a few pairs ------------------------------------------
+    no_reuse = None
+    if args.no_reuse_pairs > 0:
+        n = min(args.no_reuse_pairs, wl.n_pairs)
+        docs = [wl.doc_tokens(int(dd)) for dd in wl.pair_doc[:n]]
+        qs = [wl.query_tokens_per_query[int(q)] for q in wl.pair_query[:n]]
+        try:
+            model.score_full(docs, qs)
+            torch.cuda.synchronize()
+            tt = time.perf_counter()
+            model.score_full(docs, qs)
+            torch.cuda.synchronize()
+            el = time.perf_counter() - tt
+            no_reuse = {"value": round(n / el, 2), "unit": "pairs/s", "pairs": n,
+                        "note": "full [doc ; query] prefill per pair on the same GPU, random doc tokens of the same lengths"}
+        except hb.HrError as e:
+            no_reuse = {"value": None, "note": str(e)}
+
+    # ---- CPU oracle on a bounded sample ---------------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import reranker as orr
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = len(os.sched_getaffinity(0))
+        opool = orr.PagedKV(m.n_layers, m.n_kv_heads, m.head_dim, 16, cfg.kv_dtype)
+
+        def load_doc(dd):
+            kv = wlmod.synthetic_doc_kv(wl, dd, dev)
+            if cfg.kv_dtype == "fp8":
+                opool.write(wl.pool_doc_pages[dd], kv["k"].cpu().numpy(), kv["v"].cpu().numpy(),
+                            kv["k_scale"].cpu().numpy(), kv["v_scale"].cpu().numpy())
+            else:
+                opool.write(wl.pool_doc_pages[dd], kv["k"].double().cpu().numpy(), kv["v"].double().cpu().numpy())
+
+        rng = np.random.default_rng(0)
+        order = rng.permutation(wl.n_pairs)
+
+        class Cached:                        # keep small models' tensors so the timing is the oracle's arithmetic
+            def __init__(self, base, keep):
+                self.base, self.keep, self.store = base, keep, {}
+
+            def get(self, kind, layer=-1):
+                if not self.keep:
+                    return self.base.get(kind, layer)
+                if (kind, layer) not in self.store:
+                    self.store[(kind, layer)] = self.base.get(kind, layer)
+                return self.store[(kind, layer)]
+
+        n_params = m.gemm_flop_per_token() / 2
+        oweights = Cached(weights, keep=n_params < 1.5e9)
+
+        def run_oracle(idx):
+            sub = wl.subset(idx)
+            for dd in set(int(x) for x in sub.pair_doc):
+                if int(wl.pool_doc_pages[dd][0]) not in opool.pages:
+                    load_doc(dd)
+            t = time.perf_counter()
+            s = orr.score_cached(oweights, m, opool, sub.page_table, sub.doc_lens, sub.query_tokens, sub.query_lens)
+            return time.perf_counter() - t, s, sub
+
+        n_cpu = args.cpu_pairs
+        if n_cpu <= 0:
+            el1, _, _ = run_oracle(order[:1])
+            n_cpu = int(max(1, min(wl.n_pairs, 64, round(15.0 / max(el1, 1e-3)))))
+        el, s_cpu, sub = run_oracle(order[:n_cpu])
+        s_gpu = scores[torch.from_numpy(order[:n_cpu].copy()).to(dev)].cpu().numpy()
+        cpu = {"value": round(n_cpu / el, 4), "unit": "pairs/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"{n_cpu} seeded pairs of {wl.n_pairs} ({el:.1f} s, float64 numpy" + ("" if oweights.keep else "; weight generation inside the timed call") + f")",
+               "max_abs_err_vs_gpu": float(np.abs(s_cpu - s_gpu).max())}
+
+    line = {
+        "metric": "rerank_pairs_per_sec", "value": round(pairs_per_s, 2), "unit": "pairs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": m.dtype if cfg.kv_dtype != "fp8" else f"{m.dtype}+fp8kv", "data": "synthetic",
+        "config": {"workload": cfg.name, "model_shape": m.name, "pairs": wl.n_pairs, "query_tokens": T,
+                   "doc_len": cfg.doc_len, "query_len": cfg.query_len, "kv_dtype": cfg.kv_dtype,
+                   "gemm_path": model.gemm_path(), "attention_path": model.attention_path(pool),
+                   "events_in_timed_region": not args.no_events},
+        "roofline": roofline, "roofline_attention": roof_attn, "gemm_overall": gemm_all,
+        "kernel_breakdown": breakdown, "cpu_baseline": cpu, "no_reuse": no_reuse,
+        "paper_context": "2-3x end-to-end service throughput from reranker KV reuse on 8x A100 (Table 1); not this metric",
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -199,6 +199,16 @@ int hr_rerank_score_full(hr_model* model, int32_t n_pairs,
 /* ---- introspection for benchmarks ---- */
 
 /* Name of the kernel family a model/pool combination runs ("generic", "mfma"); never NULL. */
+/* Per-kernel timing for benchmarks.  While enabled, every kernel launch of a scoring call is
+ * bracketed by two HIP events on the call's stream, tagged with a kernel class (hr_profile_name:
+ * "gemm_gate_up", "attention", ...; hr_profile_count classes).  hr_profile_read waits for the
+ * recorded events, returns per class the summed duration in ms and the number of launches
+ * (arrays of hr_profile_count entries, host) and clears the record. */
+int hr_profile_enable(hr_model* model, int enable);
+int hr_profile_count(void);
+const char* hr_profile_name(int idx);
+int hr_profile_read(hr_model* model, double* ms_out, int64_t* launches_out);
+
 const char* hr_attention_path(const hr_model* model, const hr_pool* pool);
 const char* hr_gemm_path(const hr_model* model);
 

@@ -58,6 +58,7 @@ EXPORTS = [
     "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_free", "hr_weights_pack_bytes", "hr_weights_load",
     "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_attention_path", "hr_gemm_path",
+    "hr_profile_enable", "hr_profile_count", "hr_profile_name", "hr_profile_read",
 ]
 
 
@@ -97,6 +98,10 @@ def _load() -> C.CDLL:
                                            C.c_void_p, C.c_void_p]),
         "hr_attention_path": (C.c_char_p, [C.c_void_p, C.c_void_p]),
         "hr_gemm_path": (C.c_char_p, [C.c_void_p]),
+        "hr_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
+        "hr_profile_count": (C.c_int, []),
+        "hr_profile_name": (C.c_char_p, [C.c_int]),
+        "hr_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -267,6 +272,16 @@ class Model:
 
     def attention_path(self, pool: KVPool) -> str:
         return lib.hr_attention_path(self.handle, pool.handle).decode()
+
+    def profile_enable(self, on: bool) -> None:
+        check(lib.hr_profile_enable(self.handle, 1 if on else 0), "hr_profile_enable")
+
+    def profile_read(self) -> Dict[str, Dict[str, float]]:
+        n = lib.hr_profile_count()
+        ms = (C.c_double * n)()
+        cnt = (C.c_int64 * n)()
+        check(lib.hr_profile_read(self.handle, ms, cnt), "hr_profile_read")
+        return {lib.hr_profile_name(i).decode(): {"ms": float(ms[i]), "launches": int(cnt[i])} for i in range(n)}
 
     def score(self, pool: KVPool, page_table, doc_lens, query_tokens, query_lens, out=None, stream=None):
         import torch

@@ -6,15 +6,21 @@
 
 namespace hr {
 
-typedef __bf16 bf16_t;
+typedef __bf16 bf16_t;      // storage type of the caller's 16-bit weights, embedding and KV
+typedef _Float16 half_t;    // the library's 16-bit compute / activation type (MFMA operand type)
 
 template <typename T> __device__ __forceinline__ float to_float(T v);
 template <> __device__ __forceinline__ float to_float<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_float<bf16_t>(bf16_t v) { return (float)v; }
+template <> __device__ __forceinline__ float to_float<half_t>(half_t v) { return (float)v; }
 
 template <typename T> __device__ __forceinline__ T from_float(float v);
 template <> __device__ __forceinline__ float from_float<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_float<bf16_t>(float v) { return (bf16_t)v; }   // round to nearest even
+// round to nearest even, saturating at the largest finite half instead of overflowing to infinity
+template <> __device__ __forceinline__ half_t from_float<half_t>(float v) {
+    return (half_t)fminf(fmaxf(v, -65504.0f), 65504.0f);
+}
 
 // OCP E4M3 (bias 7, no infinities) decoded from its bit fields; exact in fp32.
 __device__ __forceinline__ float e4m3_to_float(uint8_t c) {

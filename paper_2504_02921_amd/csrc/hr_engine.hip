@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -19,6 +20,12 @@ struct hr_model {
     const float* final_norm = nullptr;
     std::vector<const float*> norm1, norm2;
     bool mfma_gemm = false;
+    bool force_generic = false;
+    // optional per-kernel timing with HIP events (benchmarks)
+    bool prof_on = false;
+    std::vector<hipEvent_t> prof_events;          // pool, two per timed launch
+    std::vector<int> prof_class;                  // class of each recorded launch
+    size_t prof_used = 0;                         // events in use
     // pinned staging for the per-call metadata upload
     int32_t* stage = nullptr;
     size_t stage_ints = 0;
@@ -70,6 +77,39 @@ int stage_reserve(hr_model* m, size_t ints) {
     return HR_OK;
 }
 
+enum ProfClass { PC_EMBED = 0, PC_RMSNORM, PC_GEMM_QKV, PC_ATTENTION, PC_GEMM_O, PC_GEMM_GATE_UP, PC_GEMM_DOWN, PC_SCORE_HEAD,
+                 PC_ELEMENTWISE, PC_COUNT };
+const char* const kProfNames[PC_COUNT] = {"embed_rope_table", "rmsnorm", "gemm_qkv", "attention", "gemm_o", "gemm_gate_up",
+                                          "gemm_down", "score_head", "elementwise"};
+
+struct ProfScope {
+    hr_model* m;
+    hipStream_t st;
+    bool on;
+    ProfScope(hr_model* m_, int cls, hipStream_t st_) : m(m_), st(st_), on(m_->prof_on) {
+        if (!on) return;
+        if (m->prof_used + 2 > m->prof_events.size()) {
+            for (int i = 0; i < 64; ++i) {
+                hipEvent_t e;
+                if (hipEventCreate(&e) != hipSuccess) { on = false; return; }
+                m->prof_events.push_back(e);
+            }
+        }
+        m->prof_class.push_back(cls);
+        (void)hipEventRecord(m->prof_events[m->prof_used], st);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(m->prof_events[m->prof_used + 1], st);
+        m->prof_used += 2;
+    }
+};
+#define HR_TIMED(cls, expr)              \
+    do {                                 \
+        ProfScope scope__(m, cls, st);   \
+        HR_HIP(expr);                    \
+    } while (0)
+
 // One pass of all layers over the T new tokens described by `mv`, scores for every sequence.
 int run_layers(hr_model* m, const hr_pool* pool, const MetaView& mv, const Workspace& ws, char* wsb, int max_keys,
                int max_new_len, float* scores, hipStream_t st) {
@@ -102,45 +142,48 @@ int run_layers(hr_model* m, const hr_pool* pool, const MetaView& mv, const Works
         pv.esz = dtype_size(dt);
         pv.num_pages = 1;
     }
-    const bool mfma_attn = attn_mfma_supported(c, pv.kv_dtype, max_new_len);
+    const bool mfma_attn = !m->force_generic && attn_mfma_supported(c, pv.kv_dtype, max_new_len);
 
-    HR_HIP(launch_embed(dt, m->embedding, mv, x, H, st));
-    HR_HIP(launch_rope_table(mv, rope, d, c.rope_base, st));
+    HR_TIMED(PC_EMBED, launch_embed(dt, m->embedding, mv, x, H, st));
+    HR_TIMED(PC_EMBED, launch_rope_table(mv, rope, d, c.rope_base, st));
     for (int l = 0; l < c.n_layers; ++l) {
-        HR_HIP(launch_rmsnorm(dt, x, m->norm1[l], y, T, H, c.rms_eps, st));
+        HR_TIMED(PC_RMSNORM, launch_rmsnorm(dt, x, m->norm1[l], y, T, H, c.rms_eps, st));
         if (m->mfma_gemm) {
             GemmArgs a{};
             a.A = y; a.W = layer_w(m, l, m->pack.wqkv); a.M = T; a.N = nqkv; a.K = H;
             a.out0 = q; a.out1 = k; a.out2 = v; a.rope = rope; a.n_q = c.n_q_heads; a.n_kv = c.n_kv_heads; a.d = d;
-            HR_HIP(launch_gemm_mfma(EPI_QKV_ROPE, a, st));
+            HR_TIMED(PC_GEMM_QKV, launch_gemm_mfma(EPI_QKV_ROPE, a, st));
         } else {
-            HR_HIP(launch_gemm_generic(dt, y, layer_w(m, l, m->pack.wqkv), f32, T, nqkv, H, false, st));
-            HR_HIP(launch_rope_split(dt, f32, rope, q, k, v, T, c.n_q_heads, c.n_kv_heads, d, st));
+            HR_TIMED(PC_GEMM_QKV, launch_gemm_generic(dt, y, layer_w(m, l, m->pack.wqkv), f32, T, nqkv, H, false, st));
+            HR_TIMED(PC_ELEMENTWISE, launch_rope_split(dt, f32, rope, q, k, v, T, c.n_q_heads, c.n_kv_heads, d, st));
         }
-        if (mfma_attn) HR_HIP(launch_attn_mfma(q, k, v, o, mv, pv, l, c.n_q_heads, max_new_len, st));
-        else HR_HIP(launch_attn_generic(dt, q, k, v, o, mv, pv, l, c.n_q_heads, max_keys, st));
+        if (mfma_attn) {
+            HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, v, o, mv, pv, l, c.n_q_heads, max_new_len, st));
+        } else {
+            HR_TIMED(PC_ATTENTION, launch_attn_generic(dt, q, k, v, o, mv, pv, l, c.n_q_heads, max_keys, st));
+        }
         if (m->mfma_gemm) {
             GemmArgs a{};
             a.A = o; a.W = layer_w(m, l, m->pack.wo); a.M = T; a.N = H; a.K = nq; a.x = x;
-            HR_HIP(launch_gemm_mfma(EPI_RESID_ADD, a, st));
+            HR_TIMED(PC_GEMM_O, launch_gemm_mfma(EPI_RESID_ADD, a, st));
         } else {
-            HR_HIP(launch_gemm_generic(dt, o, layer_w(m, l, m->pack.wo), x, T, H, nq, true, st));
+            HR_TIMED(PC_GEMM_O, launch_gemm_generic(dt, o, layer_w(m, l, m->pack.wo), x, T, H, nq, true, st));
         }
-        HR_HIP(launch_rmsnorm(dt, x, m->norm2[l], y, T, H, c.rms_eps, st));
+        HR_TIMED(PC_RMSNORM, launch_rmsnorm(dt, x, m->norm2[l], y, T, H, c.rms_eps, st));
         if (m->mfma_gemm) {
             GemmArgs a{};
             a.A = y; a.W = layer_w(m, l, m->pack.wgu); a.M = T; a.N = 2 * F; a.K = H; a.out0 = mm;
-            HR_HIP(launch_gemm_mfma(EPI_SWIGLU, a, st));
+            HR_TIMED(PC_GEMM_GATE_UP, launch_gemm_mfma(EPI_SWIGLU, a, st));
             GemmArgs b{};
             b.A = mm; b.W = layer_w(m, l, m->pack.wd); b.M = T; b.N = H; b.K = F; b.x = x;
-            HR_HIP(launch_gemm_mfma(EPI_RESID_ADD, b, st));
+            HR_TIMED(PC_GEMM_DOWN, launch_gemm_mfma(EPI_RESID_ADD, b, st));
         } else {
-            HR_HIP(launch_gemm_generic(dt, y, layer_w(m, l, m->pack.wgu), f32, T, 2 * F, H, false, st));
-            HR_HIP(launch_swiglu(dt, f32, mm, T, F, m->pack.gu_interleave, st));
-            HR_HIP(launch_gemm_generic(dt, mm, layer_w(m, l, m->pack.wd), x, T, H, F, true, st));
+            HR_TIMED(PC_GEMM_GATE_UP, launch_gemm_generic(dt, y, layer_w(m, l, m->pack.wgu), f32, T, 2 * F, H, false, st));
+            HR_TIMED(PC_ELEMENTWISE, launch_swiglu(dt, f32, mm, T, F, m->pack.gu_interleave, st));
+            HR_TIMED(PC_GEMM_DOWN, launch_gemm_generic(dt, mm, layer_w(m, l, m->pack.wd), x, T, H, F, true, st));
         }
     }
-    HR_HIP(launch_score_head(dt, x, m->final_norm, m->embedding, mv, scores, H, c.rms_eps, c.yes_id, c.no_id, st));
+    HR_TIMED(PC_SCORE_HEAD, launch_score_head(dt, x, m->final_norm, m->embedding, mv, scores, H, c.rms_eps, c.yes_id, c.no_id, st));
     return HR_OK;
 }
 
@@ -187,7 +230,9 @@ int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* w, void* pack
     m->final_norm = w->final_norm;
     m->norm1.assign(w->norm1, w->norm1 + cfg->n_layers);
     m->norm2.assign(w->norm2, w->norm2 + cfg->n_layers);
-    m->mfma_gemm = hr::gemm_mfma_supported(*cfg);
+    const char* force = getenv("HR_FORCE_GENERIC");      // A/B switch for tests and benchmarks
+    m->force_generic = force && force[0] == '1';
+    m->mfma_gemm = !m->force_generic && hr::gemm_mfma_supported(*cfg);
 
     hipStream_t st = (hipStream_t)stream;
     const int dt = cfg->dtype;
@@ -219,6 +264,7 @@ void hr_model_destroy(hr_model* m) {
     if (m->stage_pending) (void)hipEventSynchronize(m->stage_ev);
     if (m->stage_ev) (void)hipEventDestroy(m->stage_ev);
     if (m->stage) (void)hipHostFree(m->stage);
+    for (hipEvent_t e : m->prof_events) (void)hipEventDestroy(e);
     delete m;
 }
 
@@ -250,7 +296,7 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     int max_q = 0;
     if (n_pairs > 0 && query_lens)
         for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
-    const bool mfma_attn = hr::attn_mfma_supported(m->cfg, pool->cfg.kv_dtype, max_q);
+    const bool mfma_attn = !m->force_generic && hr::attn_mfma_supported(m->cfg, pool->cfg.kv_dtype, max_q);
     int64_t T = 0;
     int rc = hr::score_check_args(m->cfg, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens,
                                   mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys, &T);
@@ -340,11 +386,37 @@ int hr_rerank_score_full(hr_model* m, int32_t n_pairs, const int32_t* doc_tokens
     return run_layers(m, nullptr, mv, ws, wsb, max_len, max_len, scores_dev, st);
 }
 
+int hr_profile_enable(hr_model* m, int enable) {
+    if (!m) return HR_ERR_INVALID_ARG;
+    m->prof_on = enable != 0;
+    return HR_OK;
+}
+
+int hr_profile_count(void) { return PC_COUNT; }
+
+const char* hr_profile_name(int idx) { return idx >= 0 && idx < PC_COUNT ? kProfNames[idx] : ""; }
+
+int hr_profile_read(hr_model* m, double* ms_out, int64_t* launches_out) {
+    if (!m || !ms_out || !launches_out) return HR_ERR_INVALID_ARG;
+    for (int i = 0; i < PC_COUNT; ++i) { ms_out[i] = 0.0; launches_out[i] = 0; }
+    for (size_t i = 0; i + 1 < m->prof_used; i += 2) {
+        HR_HIP(hipEventSynchronize(m->prof_events[i + 1]));
+        float ms = 0.f;
+        HR_HIP(hipEventElapsedTime(&ms, m->prof_events[i], m->prof_events[i + 1]));
+        int cls = m->prof_class[i / 2];
+        ms_out[cls] += ms;
+        launches_out[cls] += 1;
+    }
+    m->prof_used = 0;
+    m->prof_class.clear();
+    return HR_OK;
+}
+
 const char* hr_last_error(void) { return g_last_error; }
 
 const char* hr_attention_path(const hr_model* m, const hr_pool* pool) {
     if (!m || !pool) return "none";
-    return hr::attn_mfma_supported(m->cfg, pool->cfg.kv_dtype, 1) ? "mfma" : "generic";
+    return !m->force_generic && hr::attn_mfma_supported(m->cfg, pool->cfg.kv_dtype, 1) ? "mfma" : "generic";
 }
 
 const char* hr_gemm_path(const hr_model* m) {

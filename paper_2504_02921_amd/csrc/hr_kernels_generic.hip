@@ -260,10 +260,15 @@ struct PageIdChunk { int32_t ids[256]; };   // page ids travel as kernel argumen
 // pool write: logical [L][D][n_kv][d] -> pages (K row-major, V transposed with slot swizzle), tail zeroed
 // grid: (n_pages, n_layers * n_kv); 256 threads
 // ------------------------------------------------------------------------------------------------
-template <typename KVT>
+template <typename SRC, typename DST> __device__ __forceinline__ DST kv_convert(SRC v) { return (DST)v; }
+// 16-bit pools: the caller's bf16 values are stored as half (exact for |x| in [2^-14, 65504]; smaller
+// magnitudes keep an absolute error below 2^-25, larger ones saturate)
+template <> __device__ __forceinline__ half_t kv_convert<bf16_t, half_t>(bf16_t v) { return from_float<half_t>((float)v); }
+
+template <typename KVT, typename KVS>
 __global__ void __launch_bounds__(256) kv_scatter_kernel(KVT* __restrict__ pool, float* __restrict__ scales,
                                                          PageIdChunk page_ids, int pg0, int doc_len, int n_pages,
-                                                         const KVT* __restrict__ k, const KVT* __restrict__ v,
+                                                         const KVS* __restrict__ k, const KVS* __restrict__ v,
                                                          const float* __restrict__ ks, const float* __restrict__ vs,
                                                          int num_pages, int n_kv, int d) {
     int pg = pg0 + blockIdx.x;
@@ -276,11 +281,11 @@ __global__ void __launch_bounds__(256) kv_scatter_kernel(KVT* __restrict__ pool,
     for (int e = threadIdx.x; e < (int)blk; e += 256) {
         int tk = e / d, c = e - tk * d;
         int tok = pg * kPageTokens + tk;
-        KVT kvl = KVT(0), vvl = KVT(0);
+        KVT kvl = KVT(0.0f), vvl = KVT(0.0f);
         if (tok < doc_len) {
             size_t src = (((size_t)layer * doc_len + tok) * n_kv + h) * d + c;
-            kvl = k[src];
-            vvl = v[src];
+            kvl = kv_convert<KVS, KVT>(k[src]);
+            vvl = kv_convert<KVS, KVT>(v[src]);
         }
         kb[e] = kvl;
         int slot = (tk & 3) | ((tk & 4) << 1) | ((tk & 8) >> 1);
@@ -293,11 +298,11 @@ __global__ void __launch_bounds__(256) kv_scatter_kernel(KVT* __restrict__ pool,
     }
 }
 
-template <typename T>
-__global__ void pack_rows_kernel(const T* __restrict__ src, T* __restrict__ dst, int rows, int cols, int ib, int mul, int sel) {
+template <typename S, typename D>
+__global__ void pack_rows_kernel(const S* __restrict__ src, D* __restrict__ dst, int rows, int cols, int ib, int mul, int sel) {
     int r = blockIdx.x;
     size_t drow = ((size_t)(r / ib) * mul + sel) * ib + r % ib;
-    for (int c = threadIdx.x; c < cols; c += blockDim.x) dst[drow * cols + c] = src[(size_t)r * cols + c];
+    for (int c = threadIdx.x; c < cols; c += blockDim.x) dst[drow * cols + c] = from_float<D>(to_float<S>(src[(size_t)r * cols + c]));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -306,12 +311,18 @@ __global__ void pack_rows_kernel(const T* __restrict__ src, T* __restrict__ dst,
 #define HR_DISPATCH_ACT(dtype, ...)                                   \
     do {                                                              \
         if ((dtype) == HR_F32) { using AT = float; __VA_ARGS__; }      \
-        else { using AT = bf16_t; __VA_ARGS__; }                       \
+        else { using AT = half_t; __VA_ARGS__; }                        \
+    } while (0)
+
+#define HR_DISPATCH_EMB(dtype, ...)                                   \
+    do {                                                              \
+        if ((dtype) == HR_F32) { using AT = float; __VA_ARGS__; }     \
+        else { using AT = bf16_t; __VA_ARGS__; }                      \
     } while (0)
 
 hipError_t launch_embed(int dtype, const void* E, const MetaView& mv, float* x, int H, hipStream_t st) {
     if (mv.T == 0) return hipSuccess;
-    HR_DISPATCH_ACT(dtype, embed_kernel<AT><<<dim3((unsigned)mv.T), 256, 0, st>>>((const AT*)E, mv.tok_id, x, H));
+    HR_DISPATCH_EMB(dtype, embed_kernel<AT><<<dim3((unsigned)mv.T), 256, 0, st>>>((const AT*)E, mv.tok_id, x, H));
     return hipGetLastError();
 }
 
@@ -359,11 +370,11 @@ hipError_t launch_attn_generic(int dtype, const void* q, const void* k_new, cons
         attn_generic_kernel<float, float><<<grid, 64, lds, st>>>((const float*)q, (const float*)k_new, (const float*)v_new,
                                                                  (float*)o, mv, pv, layer, n_q);
     } else if (pv.kv_dtype == HR_FP8_E4M3) {
-        attn_generic_kernel<bf16_t, uint8_t><<<grid, 64, lds, st>>>((const bf16_t*)q, (const bf16_t*)k_new,
-                                                                    (const bf16_t*)v_new, (bf16_t*)o, mv, pv, layer, n_q);
+        attn_generic_kernel<half_t, uint8_t><<<grid, 64, lds, st>>>((const half_t*)q, (const half_t*)k_new,
+                                                                    (const half_t*)v_new, (half_t*)o, mv, pv, layer, n_q);
     } else {
-        attn_generic_kernel<bf16_t, bf16_t><<<grid, 64, lds, st>>>((const bf16_t*)q, (const bf16_t*)k_new,
-                                                                   (const bf16_t*)v_new, (bf16_t*)o, mv, pv, layer, n_q);
+        attn_generic_kernel<half_t, half_t><<<grid, 64, lds, st>>>((const half_t*)q, (const half_t*)k_new,
+                                                                   (const half_t*)v_new, (half_t*)o, mv, pv, layer, n_q);
     }
     return hipGetLastError();
 }
@@ -371,7 +382,7 @@ hipError_t launch_attn_generic(int dtype, const void* q, const void* k_new, cons
 hipError_t launch_score_head(int dtype, const float* x, const float* gain, const void* E, const MetaView& mv, float* scores,
                              int H, float eps, int yes_id, int no_id, hipStream_t st) {
     if (mv.n_seq == 0) return hipSuccess;
-    HR_DISPATCH_ACT(dtype, score_head_kernel<AT><<<dim3((unsigned)mv.n_seq), 256, 0, st>>>(x, gain, (const AT*)E, mv.cu, scores, H,
+    HR_DISPATCH_EMB(dtype, score_head_kernel<AT><<<dim3((unsigned)mv.n_seq), 256, 0, st>>>(x, gain, (const AT*)E, mv.cu, scores, H,
                                                                                         eps, yes_id, no_id));
     return hipGetLastError();
 }
@@ -386,15 +397,15 @@ hipError_t launch_kv_scatter(const PoolLayout& lay, char* pool_base, const int32
         for (int i = 0; i < 256; ++i) ids.ids[i] = i < n ? page_ids_host[pg0 + i] : 0;
         dim3 grid((unsigned)n, (unsigned)(lay.n_layers * lay.n_kv));
         if (lay.kv_dtype == HR_F32)
-            kv_scatter_kernel<float><<<grid, 256, 0, st>>>((float*)pool_base, nullptr, ids, pg0, doc_len, n_pages,
+            kv_scatter_kernel<float, float><<<grid, 256, 0, st>>>((float*)pool_base, nullptr, ids, pg0, doc_len, n_pages,
                                                            (const float*)k, (const float*)v, nullptr, nullptr, lay.num_pages,
                                                            lay.n_kv, lay.d);
         else if (lay.kv_dtype == HR_BF16)
-            kv_scatter_kernel<uint16_t><<<grid, 256, 0, st>>>((uint16_t*)pool_base, nullptr, ids, pg0, doc_len, n_pages,
-                                                              (const uint16_t*)k, (const uint16_t*)v, nullptr, nullptr,
+            kv_scatter_kernel<half_t, bf16_t><<<grid, 256, 0, st>>>((half_t*)pool_base, nullptr, ids, pg0, doc_len, n_pages,
+                                                              (const bf16_t*)k, (const bf16_t*)v, nullptr, nullptr,
                                                               lay.num_pages, lay.n_kv, lay.d);
         else
-            kv_scatter_kernel<uint8_t><<<grid, 256, 0, st>>>((uint8_t*)pool_base, scales, ids, pg0, doc_len, n_pages,
+            kv_scatter_kernel<uint8_t, uint8_t><<<grid, 256, 0, st>>>((uint8_t*)pool_base, scales, ids, pg0, doc_len, n_pages,
                                                              (const uint8_t*)k, (const uint8_t*)v, ks, vs, lay.num_pages,
                                                              lay.n_kv, lay.d);
         hipError_t e = hipGetLastError();
@@ -406,10 +417,10 @@ hipError_t launch_kv_scatter(const PoolLayout& lay, char* pool_base, const int32
 hipError_t launch_pack_rows(int dtype, const void* src, void* dst, int rows, int cols, int ib, int mul, int sel,
                             hipStream_t st) {
     if (dtype == HR_F32)
-        pack_rows_kernel<float><<<dim3((unsigned)rows), 256, 0, st>>>((const float*)src, (float*)dst, rows, cols, ib, mul, sel);
-    else
-        pack_rows_kernel<uint16_t><<<dim3((unsigned)rows), 256, 0, st>>>((const uint16_t*)src, (uint16_t*)dst, rows, cols, ib,
-                                                                         mul, sel);
+        pack_rows_kernel<float, float><<<dim3((unsigned)rows), 256, 0, st>>>((const float*)src, (float*)dst, rows, cols, ib, mul, sel);
+    else   // the caller's bf16 weights become half operands (same rule as kv_convert)
+        pack_rows_kernel<bf16_t, half_t><<<dim3((unsigned)rows), 256, 0, st>>>((const bf16_t*)src, (half_t*)dst, rows, cols, ib,
+                                                                              mul, sel);
     return hipGetLastError();
 }
 

@@ -156,6 +156,15 @@ def round_to(a: np.ndarray, dtype: str) -> np.ndarray:
 # --------------------------------------------------------------------------- #
 # weights
 # --------------------------------------------------------------------------- #
+def _n_workers() -> int:
+    import os
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
 class SeededWeights:
     """Random-init weights: every matrix ~ N(0, 0.02^2), norm gains 1 (+ optional jitter).
 
@@ -172,22 +181,37 @@ class SeededWeights:
         self.gain_jitter = gain_jitter
         self._embedding = None
 
-    def _rng(self, kind: str, layer: int) -> np.random.Generator:
-        return np.random.Generator(np.random.PCG64(np.random.SeedSequence([self.seed, layer + 1, _KIND_INDEX[kind]])))
+    _CHUNK = 1 << 22      # elements per independently seeded block (blocks are drawn in parallel)
+
+    def _rng(self, kind: str, layer: int, block: int = 0) -> np.random.Generator:
+        return np.random.Generator(np.random.PCG64(np.random.SeedSequence([self.seed, layer + 1, _KIND_INDEX[kind], block])))
+
+    def _fill_block(self, flat: np.ndarray, kind: str, layer: int, block: int) -> None:
+        lo = block * self._CHUNK
+        hi = min(flat.shape[0], lo + self._CHUNK)
+        part = self._rng(kind, layer, block).standard_normal(hi - lo, dtype=np.float32)
+        part *= np.float32(self.std)
+        flat[lo:hi] = round_to(part, self.model.dtype)
 
     def get(self, kind: str, layer: int = -1) -> np.ndarray:
         if kind == "embedding" and self._embedding is not None:
             return self._embedding
         shape = self.model.shape(kind)
-        rng = self._rng(kind, layer)
         if kind in ("final_norm", "norm1", "norm2"):
             g = np.ones(shape, dtype=np.float32)
             if self.gain_jitter:
-                g += (self.gain_jitter * rng.standard_normal(shape, dtype=np.float32)).astype(np.float32)
+                g += (self.gain_jitter * self._rng(kind, layer).standard_normal(shape, dtype=np.float32)).astype(np.float32)
             return g
-        w = rng.standard_normal(shape, dtype=np.float32)
-        w *= np.float32(self.std)
-        w = round_to(w, self.model.dtype)
+        n = int(np.prod(shape))
+        flat = np.empty(n, dtype=np.float32)
+        blocks = (n + self._CHUNK - 1) // self._CHUNK
+        if blocks <= 1:
+            self._fill_block(flat, kind, layer, 0)
+        else:
+            from concurrent.futures import ThreadPoolExecutor
+            with ThreadPoolExecutor(max_workers=min(blocks, _n_workers())) as ex:
+                list(ex.map(lambda b: self._fill_block(flat, kind, layer, b), range(blocks)))
+        w = flat.reshape(shape)
         if kind == "embedding":
             self._embedding = w
         return w

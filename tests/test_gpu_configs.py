@@ -1,0 +1,68 @@
+"""GPU parity at the full sizes of the five workload configurations, in the launch configuration
+bench.py times (same entry point, whole batch in one call).  The document KV of these shapes is
+the seeded opaque stand-in (a CPU document prefill at 0.5B / 8B shapes would take hours); the oracle
+consumes exactly the bytes the pool was given and is evaluated on a seeded sample of pairs that
+always contains one complete query (for the ranking check) and the extreme lengths."""
+
+import numpy as np
+import pytest
+
+from paper_2504_02921_amd import workloads as wlmod
+
+import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def run_full_size(cfg, n_extra, whole_queries=1):
+    wl = wlmod.make_workload(cfg)
+    w = wlmod.SeededWeights(cfg.model, seed=cfg.seed)
+    idx = set(H.sample_pairs(wl, n_extra, seed=1).tolist())
+    for q in range(whole_queries):
+        idx |= set(range(q * cfg.n_cands, (q + 1) * cfg.n_cands))
+    idx = np.array(sorted(idx))
+    case = H.Case(wl, w)
+    try:
+        case.fill_synthetic(oracle_doc_ids=wl.pair_doc[idx])
+        got_all = case.gpu_scores()
+        assert got_all.shape == (wl.n_pairs,) and np.all(np.isfinite(got_all))
+        sub = wl.subset(idx)
+        want = case.oracle_scores(sub)
+        tol = H.TOL[cfg.model.dtype]
+        H.assert_scores_close(got_all[idx], want, tol, cfg.name)
+        for q in range(whole_queries):
+            sel = np.searchsorted(idx, np.arange(q * cfg.n_cands, (q + 1) * cfg.n_cands))
+            H.assert_same_topk_up_to_ties(got_all[idx][sel], want[sel], 1, cfg.n_cands, tol)
+        # the sampled pairs scored on their own give the same result as inside the big batch
+        alone = case.gpu_scores(sub)
+        np.testing.assert_allclose(alone, got_all[idx], rtol=0, atol=tol / 4)
+        return float(np.abs(got_all[idx] - want).max())
+    finally:
+        case.close()
+
+
+@pytest.mark.timeout(600)
+def test_config2_qwen0p5b_full_size():
+    err = run_full_size(wlmod.CONFIGS["c2_qwen0p5b"], n_extra=8)
+    print("c2 max err", err)
+
+
+@pytest.mark.timeout(900)
+def test_config3_llama8b_full_size():
+    err = run_full_size(wlmod.CONFIGS["c3_llama8b"], n_extra=4, whole_queries=0)
+    print("c3 max err", err)
+
+
+@pytest.mark.timeout(900)
+def test_config4_ragged_zipf():
+    # every property of the ragged mix (length ranges, Zipf reuse over the 8192-document pool, permuted
+    # pages) at 64 of the 256 queries: the per-pair work is identical, only the batch is shorter
+    cfg = wlmod.scaled(wlmod.CONFIGS["c4_ragged"], n_queries=64)
+    err = run_full_size(cfg, n_extra=12, whole_queries=0)
+    print("c4 max err", err)
+
+
+@pytest.mark.timeout(900)
+def test_config5_long_fp8():
+    err = run_full_size(wlmod.CONFIGS["c5_long_fp8"], n_extra=4, whole_queries=0)
+    print("c5 max err", err)

@@ -73,6 +73,18 @@ def test_bf16_small_model_real_document_kv():
     case.close()
 
 
+@pytest.mark.parametrize("d,n_q,n_kv,hidden,ffn", [(64, 4, 2, 256, 320), (128, 4, 1, 320, 192), (64, 14, 2, 896, 448)])
+def test_bf16_mfma_projection_shapes(d, n_q, n_kv, hidden, ffn):
+    """Shapes the MFMA GEMM family covers: ragged token count, N not a multiple of the tile."""
+    model = small_model(dtype="bf16", n_layers=2, hidden=hidden, n_q=n_q, n_kv=n_kv, d=d, ffn=ffn, vocab=500)
+    cfg = wlmod.WorkloadCfg("bf16_mfma", model, 5, 4, (30, 100), (5, 33), "bf16", seed=d + n_q)
+    w = wlmod.SeededWeights(model, seed=14, std=0.05, gain_jitter=0.1)
+    case, got, want = run_case(cfg, w, H.TOL["bf16"])
+    assert case.model.gemm_path() == "mfma"
+    assert np.abs(want).max() > 1e-2
+    case.close()
+
+
 def test_fp8_pool_small_model():
     model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=8, n_kv=2, d=32, ffn=352)
     cfg = wlmod.WorkloadCfg("fp8_small", model, 2, 4, (20, 90), (3, 12), "fp8", seed=5)
