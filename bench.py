@@ -203,8 +203,9 @@ def main():
 
         n_cpu = args.cpu_pairs
         if n_cpu <= 0:
-            el1, _, _ = run_oracle(order[:1])
-            n_cpu = int(max(1, min(wl.n_pairs, 64, round(15.0 / max(el1, 1e-3)))))
+            run_oracle(order[:1])                              # warms the BLAS threads and the weight cache
+            el2, _, _ = run_oracle(order[:2])
+            n_cpu = int(max(2, min(wl.n_pairs, 256, round(15.0 / max(el2 / 2, 1e-3)))))
         el, s_cpu, sub = run_oracle(order[:n_cpu])
         s_gpu = scores[torch.from_numpy(order[:n_cpu].copy()).to(dev)].cpu().numpy()
         cpu = {"value": round(n_cpu / el, 4), "unit": "pairs/s", "cores": int(cores), "kind": "oracle",

@@ -19,10 +19,7 @@ enum PageState : uint8_t { PAGE_FREE = 0, PAGE_RESERVED = 1, PAGE_USED = 2 };
 
 // Physical arrangement of the pool (private to the library):
 //   data:   [layer][page][kv_head][K | V] blocks of 16 * head_dim elements.
-//           K block: [16 tokens][head_dim].
-//           V block: [head_dim][16 slots]; token t of the page sits in slot v_slot(t)
-//           (bits 2 and 3 of t swapped), which puts the 8 keys one MFMA lane consumes next to
-//           each other.
+//           Element order inside the K and V blocks: see hr_layout.h.
 //   scales: fp8 pools only, after the data: [layer][page][kv_head][2] fp32 (K scale, V scale).
 struct PoolLayout {
     int n_layers = 0, n_kv = 0, d = 0, num_pages = 0, kv_dtype = 0;
@@ -37,8 +34,6 @@ struct PoolLayout {
     }
     size_t scale_index(int layer, int page, int kvh, int which) const { return block_index(layer, page, kvh, which); }
 };
-
-inline int v_slot(int t) { return (t & 3) | ((t & 4) << 1) | ((t & 8) >> 1); }
 
 bool pool_cfg_valid(const hr_pool_cfg* cfg);
 bool model_cfg_valid(const hr_model_cfg* cfg);

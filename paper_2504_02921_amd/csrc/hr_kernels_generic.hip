@@ -6,6 +6,7 @@
 
 #include "hr_device_types.h"
 #include "hr_kernels.h"
+#include "hr_layout.h"
 
 namespace hr {
 
@@ -191,8 +192,8 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(const T* __restrict__ 
         if (j < D) {
             int page = pt[j >> 4], slot = j & 15;
             size_t bi = ((((size_t)layer * pv.num_pages + page) * n_kv + h) * 2 + 0);
-            const KVT* kr = pool + bi * blk + (size_t)slot * d;
-            for (int c = 0; c < d; ++c) s = fmaf(sq[c], kv_load<KVT>(kr, c), s);
+            const KVT* kr = pool + bi * blk;
+            for (int c = 0; c < d; ++c) s = fmaf(sq[c], kv_load<KVT>(kr, k_elem(slot, c, d)), s);
             if (pv.scales) s *= pv.scales[bi];
         } else {
             const T* kr = k_new + ((size_t)(t0 + j - D) * n_kv + h) * d;
@@ -218,13 +219,10 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(const T* __restrict__ 
         for (int pg = 0; pg < n_pages; ++pg) {
             int page = pt[pg];
             size_t bi = ((((size_t)layer * pv.num_pages + page) * n_kv + h) * 2 + 1);
-            const KVT* vb = pool + bi * blk + (size_t)c * kPageTokens;
+            const KVT* vb = pool + bi * blk;
             float part = 0.f;
             int lim = min(kPageTokens, D - pg * kPageTokens);
-            for (int tk = 0; tk < lim; ++tk) {
-                int slot = (tk & 3) | ((tk & 4) << 1) | ((tk & 8) >> 1);
-                part = fmaf(ss[pg * kPageTokens + tk], kv_load<KVT>(vb, slot), part);
-            }
+            for (int tk = 0; tk < lim; ++tk) part = fmaf(ss[pg * kPageTokens + tk], kv_load<KVT>(vb, v_elem(tk, c, d)), part);
             acc += pv.scales ? part * pv.scales[bi] : part;
         }
         for (int j = 0; j <= i; ++j) acc = fmaf(ss[D + j], to_float(v_new[((size_t)(t0 + j) * n_kv + h) * d + c]), acc);
@@ -257,7 +255,7 @@ __global__ void __launch_bounds__(256) score_head_kernel(const float* __restrict
 // ------------------------------------------------------------------------------------------------
 struct PageIdChunk { int32_t ids[256]; };   // page ids travel as kernel arguments: no device staging
 
-// pool write: logical [L][D][n_kv][d] -> pages (K row-major, V transposed with slot swizzle), tail zeroed
+// pool write: logical [L][D][n_kv][d] -> pages in the private arrangement (see hr_layout.h), tail zeroed
 // grid: (n_pages, n_layers * n_kv); 256 threads
 // ------------------------------------------------------------------------------------------------
 template <typename SRC, typename DST> __device__ __forceinline__ DST kv_convert(SRC v) { return (DST)v; }
@@ -287,9 +285,8 @@ __global__ void __launch_bounds__(256) kv_scatter_kernel(KVT* __restrict__ pool,
             kvl = kv_convert<KVS, KVT>(k[src]);
             vvl = kv_convert<KVS, KVT>(v[src]);
         }
-        kb[e] = kvl;
-        int slot = (tk & 3) | ((tk & 4) << 1) | ((tk & 8) >> 1);
-        vb[c * kPageTokens + slot] = vvl;
+        kb[k_elem(tk, c, d)] = kvl;
+        vb[v_elem(tk, c, d)] = vvl;
     }
     if (scales && threadIdx.x == 0) {
         size_t si = ((size_t)layer * n_pages + pg) * n_kv + h;

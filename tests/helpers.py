@@ -93,7 +93,7 @@ class Case:
 
     def oracle_scores(self, wl: Optional[wlmod.Workload] = None) -> np.ndarray:
         wl = self.wl if wl is None else wl
-        assert all(int(d) in self.oracle_docs for d in wl.pair_doc)
+        assert all(int(d) in self.oracle_docs or wl.pool_doc_lens[int(d)] == 0 for d in wl.pair_doc)
         return orr.score_cached(self.w, wl.cfg.model, self.opool, wl.page_table, wl.doc_lens, wl.query_tokens, wl.query_lens)
 
     def close(self):

@@ -85,6 +85,32 @@ def test_bf16_mfma_projection_shapes(d, n_q, n_kv, hidden, ffn):
     case.close()
 
 
+@pytest.mark.parametrize("d,n_q,n_kv,kv,doc_len,q_len", [
+    (64, 4, 2, "bf16", (1, 40), (1, 5)),        # tiny documents and queries: masks everywhere, one row block
+    (64, 14, 2, "bf16", (100, 300), (33, 64)),  # group of 7, up to 448 rows: 8 waves x 2 blocks, two query sub-tiles
+    (128, 8, 2, "bf16", (17, 200), (30, 64)),   # head_dim 128, 256 rows: 4 waves x 2 blocks
+    (128, 4, 1, "fp8", (60, 260), (20, 40)),    # fp8 pages, head_dim 128
+    (64, 4, 4, "fp8", (16, 129), (1, 33)),      # fp8 pages, head_dim 64, no grouping
+    (64, 8, 2, "bf16", 0, (1, 40)),             # no cached document at all: plain causal pass
+])
+def test_mfma_attention_shapes_and_edges(d, n_q, n_kv, kv, doc_len, q_len):
+    hidden = 256
+    model = small_model(dtype="bf16", n_layers=2, hidden=hidden, n_q=n_q, n_kv=n_kv, d=d, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("mfma_attn", model, 4, 3, doc_len, q_len, kv, pool_docs=7 if doc_len else None,
+                            zipf_a=0.3 if doc_len else None, seed=n_q * 3 + d)
+    w = wlmod.SeededWeights(model, seed=15, std=0.05, gain_jitter=0.1)
+    if doc_len == 0:
+        import dataclasses
+        wl = wlmod.make_workload(cfg)
+        case = H.Case(dataclasses.replace(wl, num_pages=1), w)
+        got, want = case.gpu_scores(), case.oracle_scores()
+        H.assert_scores_close(got, want, H.TOL["bf16"], "no document")
+    else:
+        case, got, want = run_case(cfg, w, H.TOL["bf16"])
+    assert case.model.attention_path(case.pool) == "mfma"
+    case.close()
+
+
 def test_fp8_pool_small_model():
     model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=8, n_kv=2, d=32, ffn=352)
     cfg = wlmod.WorkloadCfg("fp8_small", model, 2, 4, (20, 90), (3, 12), "fp8", seed=5)
