@@ -15,6 +15,7 @@
 // why pages store V transposed in exactly that grouping.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <type_traits>
 
 #include "hr_device_types.h"
@@ -118,7 +119,7 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(const half_t* __rest
             const char* kb = sb + (st * 2 + (ln >> 4)) * GG::PAGE_BYTES;
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) {
-                const int e = t * HD + (((2 * kk + hh) ^ (t & 7)) << 3);
+                const int e = t * HD + (((2 * kk + hh) ^ k_swizzle(t, HD, GG::ESZ)) << 3);
                 if constexpr (KV8) kf[kk] = fp8x8_to_half(*(const uint2*)(kb + e));
                 else kf[kk] = *(const halfx8*)(kb + e * 2);
             }
@@ -265,7 +266,7 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(const half_t* __rest
                 vv = *(const halfx8*)(v_new + src);
             }
             char* pb = smem + pg * GN::PAGE_BYTES;
-            *(halfx8*)(pb + (t * HD + ((ch ^ (t & 7)) << 3)) * 2) = kv;
+            *(halfx8*)(pb + (t * HD + ((ch ^ k_swizzle(t, HD, 2)) << 3)) * 2) = kv;
             half_t* vb = (half_t*)(pb + GN::BLOCK_BYTES);
 #pragma unroll
             for (int e = 0; e < 8; ++e) vb[v_elem(t, ch * 8 + e, HD)] = vv[e];
@@ -343,13 +344,24 @@ hipError_t launch_attn_mfma(const void* q, const void* k_new, const void* v_new,
 #define HR_ATTN_CASE(HD, NW, R)                                                                       \
     return fp8 ? launch_one<HD, NW, R, true>(qh, kh, vh, oh, mv, pv, layer, n_q, st)                   \
                : launch_one<HD, NW, R, false>(qh, kh, vh, oh, mv, pv, layer, n_q, st)
+    static int var = -1;
+    if (var < 0) {
+        const char* e = getenv("HR_ATTN_VARIANT");
+        var = e ? atoi(e) : 1;
+    }
     if (pv.d == 64) {
         if (rows <= 128) { HR_ATTN_CASE(64, 4, 1); }
-        if (rows <= 256) { HR_ATTN_CASE(64, 4, 2); }
+        if (rows <= 256) {
+            if (var == 1) { HR_ATTN_CASE(64, 8, 1); }
+            HR_ATTN_CASE(64, 4, 2);
+        }
         HR_ATTN_CASE(64, 8, 2);
     } else {
         if (rows <= 128) { HR_ATTN_CASE(128, 4, 1); }
-        if (rows <= 256) { HR_ATTN_CASE(128, 4, 2); }
+        if (rows <= 256) {
+            if (var == 1) { HR_ATTN_CASE(128, 8, 1); }
+            HR_ATTN_CASE(128, 4, 2);
+        }
         HR_ATTN_CASE(128, 8, 2);
     }
 #undef HR_ATTN_CASE

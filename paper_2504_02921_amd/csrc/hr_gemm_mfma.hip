@@ -9,11 +9,15 @@
 //
 // Tiling: 256 x BN x 64 macro tile per 256-thread workgroup (4 wavefronts as 2 x 2, each wave
 // 128 x BN/2 = 4 x (BN/64) blocks of v_mfma_f32_32x32x16_f16), LDS double-buffered, rows of 64
-// k (128 B) with the 16-byte chunk index XOR-swizzled by (row & 7) so that both the ds_write_b128
-// of the loader and the ds_read_b128 of the fragment reads are bank-conflict free.
+// k (128 B) with the 16-byte chunk index XOR-swizzled by the row pair ((row >> 1) & 7): LDS serves
+// 256 bytes per cycle to 16 lanes of a ds_read_b128, i.e. two 128-byte rows side by side, so 16
+// consecutive rows must use 8 different chunk positions per row parity (measured: 217 B/clk/CU with
+// this pattern against 119 with a (row & 7) swizzle and 32 unswizzled).
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin over 8 XCDs) works on a
 // contiguous run of tiles, grouped 8 tiles tall, keeping its private L2 on few A/W panels.
 #include <hip/hip_runtime.h>
+
+#include <cstdlib>
 
 #include "hr_device_types.h"
 #include "hr_kernels.h"
@@ -21,11 +25,12 @@
 namespace hr {
 
 typedef __attribute__((ext_vector_type(8))) _Float16 halfx8;
+typedef __attribute__((ext_vector_type(4))) _Float16 halfx4;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
 
 namespace {
 
-constexpr int BM = 256, BK = 64;
+constexpr int BK = 64;
 constexpr int kXcds = 8, kGroupM = 8;
 
 struct TileCoord { int tm, tn; bool valid; };
@@ -46,11 +51,28 @@ __device__ __forceinline__ TileCoord map_tile(int pid, int tiles_m, int tiles_n)
     return c;
 }
 
-template <int EPI, int BN, int HB>
-__global__ void __launch_bounds__(256) gemm_mfma_kernel(GemmArgs a) {
-    constexpr int WNB = BN / 64;             // 32-wide column blocks per wave
-    constexpr int WN = BN / 2;               // wave tile width
-    constexpr int PA = BM / 32, PB = BN / 32;  // loader passes (32 rows per pass)
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+
+// BM x BN x 64 macro tile, WM x WN wavefronts, each wave (BM/WM) x (BN/WN) = MI x NI blocks of 32 x 32.
+//
+// Data path: global_load_lds_dwordx4 (HBM/L2 -> LDS without passing through VGPRs; lane l of a wave
+// writes LDS bytes [base + 16 l, base + 16 l + 16)), two LDS stages.  The loads of k-tile kt + 1 are
+// issued at the top of iteration kt and waited for just before the last k-step of the iteration,
+// where the only workgroup barrier of the iteration sits; the fragments of the next k-step are read
+// one step ahead and the scheduler is pinned to alternate one ds_read with one MFMA.
+// Accumulation is transposed (D = W_frag * A_frag^T): a lane owns ONE output row (lane & 31) and
+// 4 consecutive columns per register quad, so the epilogues address one row pointer per block and
+// store 8 / 16 bytes at a time.
+template <int EPI, int BM, int BN, int WM, int WN, int HB>
+__global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM, TN = BN / WN;      // wave tile
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int RPP = NT / 8;                     // rows per loader pass (8 lanes cover one 128-byte k row)
+    constexpr int PA = BM / RPP, PB = BN / RPP;
+    constexpr int KS = BK / 16;
+    static_assert(RPP % 16 == 0 && BM % RPP == 0 && BN % RPP == 0, "loader shape");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     half_t* sA = (half_t*)smem;                         // [2][BM][BK]
     half_t* sB = sA + 2 * BM * BK;                      // [2][BN][BK]
@@ -60,163 +82,206 @@ __global__ void __launch_bounds__(256) gemm_mfma_kernel(GemmArgs a) {
     if (!tc.valid) return;
     const int64_t m0 = (int64_t)tc.tm * BM;
     const int n0 = tc.tn * BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
     const int K = a.K;
     const half_t* A = (const half_t*)a.A;
     const half_t* W = (const half_t*)a.W;
 
-    // loader: thread -> (row within a 32-row pass, 16-byte chunk of the 128-byte k row)
-    const int lrow = tid >> 3, lchunk = tid & 7;
+    // loader: lane -> LDS chunk (row lrow of the pass, physical 16-byte chunk tid & 7); it fetches the logical
+    // chunk that the row-pair swizzle maps there
+    const int lrow = tid >> 3;
+    const int lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
     const half_t* pa[PA];
     const half_t* pb[PB];
 #pragma unroll
     for (int p = 0; p < PA; ++p) {
-        int64_t r = m0 + p * 32 + lrow;
+        int64_t r = m0 + p * RPP + lrow;
         r = r < a.M ? r : a.M - 1;
         pa[p] = A + r * K + lchunk * 8;
     }
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
-        int r = n0 + p * 32 + lrow;
+        int r = n0 + p * RPP + lrow;
         r = r < a.N ? r : a.N - 1;
         pb[p] = W + (size_t)r * K + lchunk * 8;
     }
-    const int lds_off = lrow * BK + ((lchunk ^ (lrow & 7)) * 8);   // (p*32 + lrow) & 7 == lrow & 7
-
-    halfx8 ga[PA], gb[PB];
-    auto gload = [&](int kt) {
+    auto dma = [&](int kt, int buf) {
+        half_t* da = sA + buf * BM * BK + wave * 64 * 8;      // wave-uniform: the hardware adds 16 bytes per lane
+        half_t* db = sB + buf * BN * BK + wave * 64 * 8;
 #pragma unroll
-        for (int p = 0; p < PA; ++p) ga[p] = *(const halfx8*)(pa[p] + kt * BK);
+        for (int p = 0; p < PA; ++p)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pa[p] + kt * BK), (lds_ptr_t)(da + p * NT * 8), 16, 0, 0);
 #pragma unroll
-        for (int p = 0; p < PB; ++p) gb[p] = *(const halfx8*)(pb[p] + kt * BK);
-    };
-    auto lstore = [&](int buf) {
-        half_t* da = sA + buf * BM * BK + lds_off;
-        half_t* db = sB + buf * BN * BK + lds_off;
-#pragma unroll
-        for (int p = 0; p < PA; ++p) *(halfx8*)(da + p * 32 * BK) = ga[p];
-#pragma unroll
-        for (int p = 0; p < PB; ++p) *(halfx8*)(db + p * 32 * BK) = gb[p];
+        for (int p = 0; p < PB; ++p)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pb[p] + kt * BK), (lds_ptr_t)(db + p * NT * 8), 16, 0, 0);
     };
 
-    floatx16 acc[4][WNB];
+    floatx16 acc[MI][NI];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < WNB; ++j)
+        for (int j = 0; j < NI; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int frow = lane & 31, fh = lane >> 5;
-    const int a_row0 = wm * 128 + frow;
-    const int b_row0 = wn * WN + frow;
-    const int sw = frow & 7;                  // (row0 + 32 * i) & 7 == frow & 7
+    const int a_row0 = wm * TM + frow;
+    const int b_row0 = wn * TN + frow;
+    const int sw = (frow >> 1) & 7;           // row pair index: rows are 128 bytes, the bank window 256
 
+    halfx8 af[2][MI], bfr[2][NI];             // fragment double buffer
+    auto fload = [&](int slot, const half_t* cA, const half_t* cB, int kk) {
+        const int pch = ((kk * 2 + fh) ^ sw) * 8;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[slot][i] = *(const halfx8*)(cA + (a_row0 + i * 32) * BK + pch);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) bfr[slot][j] = *(const halfx8*)(cB + (b_row0 + j * 32) * BK + pch);
+    };
+    auto mfmas = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bfr[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
+    };
+
+#ifdef HR_GEMM_TRACE
+    long long* trace = (blockIdx.x == 8 && tid == 0) ? (long long*)a.out2 : nullptr;   // out2 is unused outside the QKV epilogue
+    int tp = 0;
+#define HR_STAMP() do { if (trace) trace[tp++] = __builtin_readcyclecounter(); } while (0)
+#else
+#define HR_STAMP() do { } while (0)
+#endif
     const int nk = K / BK;
-    gload(0);
-    lstore(0);
+    HR_STAMP();
+    dma(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
     __syncthreads();
+    fload(0, sA, sB, 0);
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
-        if (kt + 1 < nk) gload(kt + 1);
+        const bool more = kt + 1 < nk;
+        HR_STAMP();
+        if (more) dma(kt + 1, cur ^ 1);
         const half_t* cA = sA + cur * BM * BK;
         const half_t* cB = sB + cur * BN * BK;
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int pch = ((kk * 2 + fh) ^ sw) * 8;
-            halfx8 af[4], bfr[WNB];
+        for (int kk = 0; kk < KS - 1; ++kk) {
+            fload((kk + 1) & 1, cA, cB, kk + 1);
+            mfmas(kk & 1);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) af[i] = *(const halfx8*)(cA + (a_row0 + i * 32) * BK + pch);
-#pragma unroll
-            for (int j = 0; j < WNB; ++j) bfr[j] = *(const halfx8*)(cB + (b_row0 + j * 32) * BK + pch);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < WNB; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            for (int n = 0; n < MI + NI; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI), 0);
         }
-        if (kt + 1 < nk) lstore(cur ^ 1);
+        HR_STAMP();
+        // the next k-tile has landed (own loads) and every wave is past its last read of the other stage
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
+        HR_STAMP();
+        if (more) fload(KS & 1, sA + (cur ^ 1) * BM * BK, sB + (cur ^ 1) * BN * BK, 0);
+        mfmas((KS - 1) & 1);
+        static_assert(KS % 2 == 0, "slot parity of the first fragment of a tile");
     }
 
-    // ---- epilogue: lane holds column (lane & 31) of each 32x32 block, rows 8*(r/4) + 4*(lane>>5) + r%4
-    const int64_t row_base = m0 + wm * 128 + 4 * fh;
-    const int col_base = n0 + wn * WN + frow;
+    HR_STAMP();
+    // ---- epilogue: lane owns output row (lane & 31) of each block; register r holds column 8*(r>>2) + 4*(lane>>5) + (r&3)
+    const int64_t row_base = m0 + wm * TM + frow;
+    const int col_base = n0 + wn * TN + 4 * fh;
     if constexpr (EPI == EPI_RESID_ADD) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MI; ++i) {
+            const int64_t row = row_base + i * 32;
+            if (row >= a.M) continue;
+            float* xr = a.x + row * a.N;
 #pragma unroll
-            for (int j = 0; j < WNB; ++j) {
-                const int col = col_base + j * 32;
-                if (col >= a.N) continue;
+            for (int j = 0; j < NI; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-                    if (row < a.M) {
-                        float* px = a.x + row * a.N + col;
-                        *px += acc[i][j][r];
-                    }
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int col = col_base + j * 32 + 8 * r4;
+                    if (col >= a.N) continue;                     // N is a multiple of 8: whole quads
+                    float4 v = *(float4*)(xr + col);
+                    v.x += acc[i][j][r4 * 4 + 0];
+                    v.y += acc[i][j][r4 * 4 + 1];
+                    v.z += acc[i][j][r4 * 4 + 2];
+                    v.w += acc[i][j][r4 * 4 + 3];
+                    *(float4*)(xr + col) = v;
                 }
-            }
+        }
     } else if constexpr (EPI == EPI_SWIGLU) {
+        static_assert(EPI != EPI_SWIGLU || NI % 2 == 0, "gate/up block pairs");
         half_t* out = (half_t*)a.out0;
         const int F = a.N / 2;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MI; ++i) {
+            const int64_t row = row_base + i * 32;
+            if (row >= a.M) continue;
+            half_t* orow = out + row * F;
 #pragma unroll
-            for (int j = 0; j < WNB; j += 2) {
-                const int col = (n0 + wn * WN) / 2 + (j / 2) * 32 + frow;
-                if (col >= F) continue;
+            for (int j = 0; j < NI; j += 2)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-                    if (row < a.M) {
-                        float g = acc[i][j][r], u = acc[i][j + 1][r];
-                        out[row * F + col] = from_float<half_t>(g / (1.0f + __expf(-g)) * u);
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int col = (n0 + wn * TN) / 2 + (j / 2) * 32 + 8 * r4 + 4 * fh;
+                    if (col >= F) continue;
+                    halfx4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float g = acc[i][j][r4 * 4 + e], u = acc[i][j + 1][r4 * 4 + e];
+                        const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+                        w[e] = from_float<half_t>(g * sg * u);
                     }
+                    *(halfx4*)(orow + col) = w;
                 }
-            }
+        }
     } else {   // EPI_QKV_ROPE
         constexpr int hb = HB;                                  // 32-wide blocks per half head
+        static_assert(EPI != EPI_QKV_ROPE || NI % (2 * HB) == 0, "a wave must hold whole heads");
         const int d = a.d, half = d / 2;
         const int nq = a.n_q * d, nkv = a.n_kv * d;
-        half_t* q = (half_t*)a.out0;
-        half_t* k = (half_t*)a.out1;
-        half_t* v = (half_t*)a.out2;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MI; ++i) {
+            const int64_t row = row_base + i * 32;
+            if (row >= a.M) continue;
+            const float2* rp = a.rope + row * half;
 #pragma unroll
-            for (int j = 0; j < WNB; ++j) {
-                const int col = col_base + j * 32;
-                if (col >= a.N) continue;
+            for (int j = 0; j < NI; ++j) {
                 const int blk = j % (2 * hb);                 // block index inside its head
                 const bool lo = blk < hb;
-                const int jj = (lo ? blk : blk - hb) * 32 + frow;   // rotary index
                 const int jp = lo ? j + hb : j - hb;           // partner block (same lane, same register)
-                half_t* dst;
-                int ld;
-                bool rot = true;
-                if (col < nq) { dst = q + col; ld = nq; }
-                else if (col < nq + nkv) { dst = k + (col - nq); ld = nkv; }
-                else { dst = v + (col - nq - nkv); ld = nkv; rot = false; }
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t row = row_base + i * 32 + 8 * (r >> 2) + (r & 3);
-                    if (row >= a.M) continue;
-                    float val = acc[i][j][r];
-                    if (rot) {
-                        const float2 cs = a.rope[row * half + jj];
-                        const float other = acc[i][jp][r];
-                        val = lo ? val * cs.x - other * cs.y : val * cs.x + other * cs.y;
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int col = col_base + j * 32 + 8 * r4;
+                    if (col >= a.N) continue;
+                    half_t* dst;
+                    bool rot = true;
+                    if (col < nq) dst = (half_t*)a.out0 + row * nq + col;
+                    else if (col < nq + nkv) dst = (half_t*)a.out1 + row * nkv + (col - nq);
+                    else { dst = (half_t*)a.out2 + row * nkv + (col - nq - nkv); rot = false; }
+                    const int jj = (lo ? blk : blk - hb) * 32 + 8 * r4 + 4 * fh;   // rotary index of the quad
+                    halfx4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float val = acc[i][j][r4 * 4 + e];
+                        if (rot) {
+                            const float2 cs = rp[jj + e];
+                            const float other = acc[i][jp][r4 * 4 + e];
+                            val = lo ? val * cs.x - other * cs.y : val * cs.x + other * cs.y;
+                        }
+                        w[e] = from_float<half_t>(val);
                     }
-                    dst[row * ld] = from_float<half_t>(val);
+                    *(halfx4*)dst = w;
                 }
             }
+        }
     }
+    HR_STAMP();
 }
 
-template <int EPI, int BN, int HB>
+template <int EPI, int BM, int BN, int WM, int WN, int HB>
 hipError_t launch_tile(const GemmArgs& a, hipStream_t st) {
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (a.N + BN - 1) / BN;
     const int n_tiles = tiles_m * tiles_n;
@@ -224,12 +289,47 @@ hipError_t launch_tile(const GemmArgs& a, hipStream_t st) {
     const size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(half_t);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, BN, HB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, BM, BN, WM, WN, HB>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_mfma_kernel<EPI, BN, HB><<<dim3((unsigned)(per_xcd * kXcds)), 256, lds, st>>>(a);
+    gemm_mfma_kernel<EPI, BM, BN, WM, WN, HB><<<dim3((unsigned)(per_xcd * kXcds)), WM * WN * 64, lds, st>>>(a);
     return hipGetLastError();
+}
+
+int tuning_variant() {
+    static int v = -2;
+    if (v == -2) {
+        const char* e = getenv("HR_GEMM_VARIANT");     // tuning runs only: force one tile shape
+        v = e ? atoi(e) : -1;
+    }
+    return v;
+}
+
+int cu_count() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
+
+// Tile shape choice.  Two shapes are kept: "big" = 256 x 256 with 8 waves (one workgroup per CU, the
+// highest rate per output) and "small" = 128 x 128 with 4 waves (two workgroups per CU, ~14 % more
+// time per output but four times finer tiles).  With T x N outputs spread over 256 CUs the last round
+// of tiles is what decides (e.g. N = 896: 3.5 big column tiles), so the cost of a shape is modelled as
+// rounds x resident workgroups x tile area x relative cost per output, from measured rates.
+bool prefer_big(int64_t M, int N, int small_bn) {
+    const int64_t cus = cu_count();
+    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    const int64_t small_tiles = ((M + 127) / 128) * ((N + small_bn - 1) / small_bn);
+    const double big = (double)((big_tiles + cus - 1) / cus) * 256.0 * 256.0 * 1.0;
+    const double small = (double)((small_tiles + 2 * cus - 1) / (2 * cus)) * 2.0 * 128.0 * small_bn * 1.14;
+    return big <= small;
 }
 
 }  // namespace
@@ -246,11 +346,27 @@ bool gemm_mfma_supported(const hr_model_cfg& c) {
 hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st) {
     if (a.M == 0) return hipSuccess;
     if (a.K % BK != 0) return hipErrorInvalidValue;
+    const int var = tuning_variant();
+    const bool wide_head = epi == EPI_QKV_ROPE && a.d == 128;       // a wave must span a whole 128-wide head
+    bool big = prefer_big(a.M, a.N, wide_head ? 256 : 128);
+    if (var == 0) big = true;
+    if (var == 2) big = false;
     switch (epi) {
         case EPI_QKV_ROPE:
-            return a.d == 64 ? launch_tile<EPI_QKV_ROPE, 256, 1>(a, st) : launch_tile<EPI_QKV_ROPE, 256, 2>(a, st);
-        case EPI_RESID_ADD: return launch_tile<EPI_RESID_ADD, 256, 1>(a, st);
-        case EPI_SWIGLU: return launch_tile<EPI_SWIGLU, 256, 1>(a, st);
+            if (!wide_head) {
+                if (var == 1) return launch_tile<EPI_QKV_ROPE, 256, 256, 2, 2, 1>(a, st);
+                if (var == 3) return launch_tile<EPI_QKV_ROPE, 256, 128, 4, 2, 1>(a, st);
+                return big ? launch_tile<EPI_QKV_ROPE, 256, 256, 2, 4, 1>(a, st) : launch_tile<EPI_QKV_ROPE, 128, 128, 2, 2, 1>(a, st);
+            }
+            return big ? launch_tile<EPI_QKV_ROPE, 256, 256, 4, 2, 2>(a, st) : launch_tile<EPI_QKV_ROPE, 128, 256, 2, 2, 2>(a, st);
+        case EPI_RESID_ADD:
+            if (var == 1) return launch_tile<EPI_RESID_ADD, 256, 256, 2, 2, 1>(a, st);
+            if (var == 3) return launch_tile<EPI_RESID_ADD, 256, 128, 4, 2, 1>(a, st);
+            return big ? launch_tile<EPI_RESID_ADD, 256, 256, 2, 4, 1>(a, st) : launch_tile<EPI_RESID_ADD, 128, 128, 2, 2, 1>(a, st);
+        case EPI_SWIGLU:
+            if (var == 1) return launch_tile<EPI_SWIGLU, 256, 256, 2, 2, 1>(a, st);
+            if (var == 3) return launch_tile<EPI_SWIGLU, 256, 128, 4, 2, 1>(a, st);
+            return big ? launch_tile<EPI_SWIGLU, 256, 256, 2, 4, 1>(a, st) : launch_tile<EPI_SWIGLU, 128, 128, 2, 2, 1>(a, st);
     }
     return hipErrorInvalidValue;
 }

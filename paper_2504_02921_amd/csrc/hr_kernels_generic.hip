@@ -193,7 +193,7 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(const T* __restrict__ 
             int page = pt[j >> 4], slot = j & 15;
             size_t bi = ((((size_t)layer * pv.num_pages + page) * n_kv + h) * 2 + 0);
             const KVT* kr = pool + bi * blk;
-            for (int c = 0; c < d; ++c) s = fmaf(sq[c], kv_load<KVT>(kr, k_elem(slot, c, d)), s);
+            for (int c = 0; c < d; ++c) s = fmaf(sq[c], kv_load<KVT>(kr, k_elem(slot, c, d, (int)sizeof(KVT))), s);
             if (pv.scales) s *= pv.scales[bi];
         } else {
             const T* kr = k_new + ((size_t)(t0 + j - D) * n_kv + h) * d;
@@ -285,7 +285,7 @@ __global__ void __launch_bounds__(256) kv_scatter_kernel(KVT* __restrict__ pool,
             kvl = kv_convert<KVS, KVT>(k[src]);
             vvl = kv_convert<KVS, KVT>(v[src]);
         }
-        kb[k_elem(tk, c, d)] = kvl;
+        kb[k_elem(tk, c, d, (int)sizeof(KVT))] = kvl;
         vb[v_elem(tk, c, d)] = vvl;
     }
     if (scales && threadIdx.x == 0) {
