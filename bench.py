@@ -216,7 +216,7 @@ def main():
         "metric": "rerank_pairs_per_sec", "value": round(pairs_per_s, 2), "unit": "pairs/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": m.dtype if cfg.kv_dtype != "fp8" else f"{m.dtype}+fp8kv", "data": "synthetic",
+        "dtype": ("f32" if m.dtype == "f32" else "f16") + ("+fp8kv" if cfg.kv_dtype == "fp8" else ""), "data": "synthetic",
         "config": {"workload": cfg.name, "model_shape": m.name, "pairs": wl.n_pairs, "query_tokens": T,
                    "doc_len": cfg.doc_len, "query_len": cfg.query_len, "kv_dtype": cfg.kv_dtype,
                    "gemm_path": model.gemm_path(), "attention_path": model.attention_path(pool),

@@ -4,8 +4,9 @@
 // group) that share this kv head; wave w owns 32-row blocks w, w + NW, ...  The document's pages are
 // streamed HBM -> LDS in 32 KiB stages (double buffered, every page is one contiguous burst and is
 // copied verbatim: the pool already holds the LDS-friendly arrangement), all keys of the document are
-// visible to every row; then the pair's own query keys are staged once and processed with the causal
-// mask.  Softmax is the online form in fp32.
+// visible to every row; then the pair's own query keys, which the QKV projection wrote as pages of the
+// same arrangement, follow in the same stream and are processed with the causal mask.  Softmax is the
+// online form in fp32.
 //
 // MFMA orientation (v_mfma_f32_32x32x16_f16): scores are computed transposed, S^T = K * Q^T, so a
 // lane owns ONE query row (column lane & 31) and 16 of the 32 keys of a sub-tile.  Row maxima and
@@ -15,6 +16,7 @@
 // why pages store V transposed in exactly that grouping.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <type_traits>
 
@@ -28,6 +30,14 @@ typedef __attribute__((ext_vector_type(8))) _Float16 halfx8;
 typedef __attribute__((ext_vector_type(4))) _Float16 halfx4;
 typedef __attribute__((ext_vector_type(2))) _Float16 halfx2;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
+typedef __attribute__((ext_vector_type(2))) float floatx2;
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
+
+#ifdef HR_ATTN_TRACE
+__device__ long long* g_attn_trace_dev = nullptr;
+long long* g_attn_trace = nullptr;
+#endif
 
 namespace {
 
@@ -43,21 +53,30 @@ struct Geo {
     static constexpr int TK = kPageTokens * PPS;                 // keys per stage
 };
 
-// 8 consecutive fp8 codes (one 64-bit LDS word) -> 8 halves, exact (every E4M3 value is a half)
-__device__ __forceinline__ halfx8 fp8x8_to_half(uint2 w) {
-    halfx2 a = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.x, 1.0f, false);
-    halfx2 b = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.x, 1.0f, true);
-    halfx2 c = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.y, 1.0f, false);
-    halfx2 d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.y, 1.0f, true);
+// 8 consecutive fp8 codes (one 64-bit LDS word) -> 8 halves.  v_cvt_scalef32_pk_f16_fp8 multiplies by the power of
+// two in `scale` only (its mantissa is ignored - measured), so the result is exact: every E4M3 value times a power of
+// two is a half (down to 2^-24).
+__device__ __forceinline__ halfx8 fp8x8_to_half(uint2 w, float scale = 1.0f) {
+    halfx2 a = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.x, scale, false);
+    halfx2 b = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.x, scale, true);
+    halfx2 c = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.y, scale, false);
+    halfx2 d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.y, scale, true);
     halfx8 r;
     r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1]; r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
     return r;
 }
 
+// What a workgroup needs to know about one work item = (pair, kv head)
+struct ItemCtx {
+    int p, h, t0, qn, D, n_pages, n_tiles, nq_pages, n_new_tiles;
+    const int32_t* pt;        // page-table row
+    const char* layer_base;   // pool address of page 0 for this (layer, kv head)
+    const char* new_base;     // first page of the pair's own K/V
+};
+
 template <int HD, int NW, int R, bool FP8>
-__global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(const half_t* __restrict__ q, const half_t* __restrict__ k_new,
-                                                           const half_t* __restrict__ v_new, half_t* __restrict__ o,
-                                                           MetaView mv, PoolView pv, int layer, int n_q) {
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((HD == 64 && R == 1 && NW == 8) ? 4 : (HD * R <= 128 ? 2 : 1), 8))) attn_mfma_kernel(const half_t* __restrict__ q, const char* __restrict__ kv_new,
+                                                           half_t* __restrict__ o, MetaView mv, PoolView pv, int layer, int n_q) {
     using G = Geo<HD, FP8>;
     using GN = Geo<HD, false>;                       // the pair's own keys are always half
     constexpr int NT = NW * 64;
@@ -67,54 +86,138 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(const half_t* __rest
     extern __shared__ __attribute__((aligned(16))) char smem[];      // [2][kStageBytes] + scales
     float* s_scale = (float*)(smem + 2 * kStageBytes);              // [2][PPS][2]  (fp8 only)
 
+#ifdef HR_ATTN_TRACE
+    long long* trace = (blockIdx.x == 100 && threadIdx.x == 0) ? g_attn_trace_dev : nullptr;
+    int tp = 0;
+#define HR_ASTAMP() do { if (trace && tp < 900) trace[tp++] = __builtin_readcyclecounter(); } while (0)
+#else
+#define HR_ASTAMP() do { } while (0)
+#endif
     const int n_kv = pv.n_kv;
-    const int p = blockIdx.x / n_kv, h = blockIdx.x - p * n_kv;
-    const int t0 = mv.cu[p];
-    const int qn = mv.cu[p + 1] - t0;
-    const int D = mv.prefix_len[p];
     const int g = n_q / n_kv;
-    const int M = qn * g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 31, hh = lane >> 5;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const float c_log2 = 1.4426950408889634f / sqrtf((float)HD);
+    const size_t page_stride = (size_t)n_kv * G::PAGE_BYTES;                         // between consecutive page ids
+    const int n_items = mv.n_seq * n_kv;
 
-    // ---- this lane's query rows and Q^T fragments (B operand: 8 consecutive channels of one row)
-    halfx8 qf[R][KC];
+    auto load_ctx = [&](int item) {
+        ItemCtx c;
+        c.p = item / n_kv;
+        c.h = item - c.p * n_kv;
+        c.t0 = mv.cu[c.p];
+        c.qn = mv.cu[c.p + 1] - c.t0;
+        c.D = mv.prefix_len[c.p];
+        c.n_pages = (c.D + kPageTokens - 1) / kPageTokens;
+        c.n_tiles = (c.n_pages + G::PPS - 1) / G::PPS;
+        c.nq_pages = ((c.qn + 31) / 32) * 2;                    // whole 32-key sub-tiles
+        c.n_new_tiles = (c.nq_pages + GN::PPS - 1) / GN::PPS;
+        c.pt = mv.page_table + (size_t)c.p * mv.pt_stride;
+        c.layer_base = pv.data + ((size_t)layer * pv.num_pages * n_kv + c.h) * G::PAGE_BYTES;
+        c.new_base = kv_new + ((size_t)(mv.new_cu[c.p] >> 4) * n_kv + c.h) * GN::PAGE_BYTES;
+        return c;
+    };
+
+    // ---- KV stream: the document's pages, then the pair's own (causal) keys, which the QKV projection has already
+    // written as half pages in the same arrangement.  HBM -> LDS directly (global_load_lds_dwordx4: lane l of a
+    // wave writes LDS bytes [base + 16 l, +16)), two stages, pages land verbatim.
+    float stg_scale = 0.f;
+    // Page ids (and fp8 scales' page) travel one step ahead of the data: ids_load(c, t) requests the ids of document
+    // tile t into registers, dma_doc(c, t, buf) consumes them.  The page-table latency is thus never on the path
+    // between two stages.
+    int pgid[NPASS];
+    int pgid_scale = 0;
+    auto ids_load = [&](const ItemCtx& c, int tile) {
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            const int slot = (ps * NT * 16 + tid * 16) / G::PAGE_BYTES;
+            int pgi = tile * G::PPS + slot;
+            pgi = pgi < c.n_pages ? pgi : c.n_pages - 1;       // past the end: re-read the last page (finite data, masked)
+            pgid[ps] = c.pt[pgi];
+        }
+        if constexpr (FP8) {
+            if (tid < G::PPS * 2) {
+                int pgi = tile * G::PPS + (tid >> 1);
+                pgi = pgi < c.n_pages ? pgi : c.n_pages - 1;
+                pgid_scale = c.pt[pgi];
+            }
+        }
+    };
+    auto dma_doc = [&](const ItemCtx& c, int buf) {
+        char* dst = smem + buf * kStageBytes + wave_u * 1024;
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            const int off = ps * NT * 16 + tid * 16;
+            const int within = off % G::PAGE_BYTES;
+            const char* src = c.layer_base + (size_t)pgid[ps] * page_stride + within;
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(dst + ps * NT * 16), 16, 0, 0);
+        }
+        if constexpr (FP8) {
+            if (tid < G::PPS * 2) stg_scale = pv.scales[(((size_t)layer * pv.num_pages + pgid_scale) * n_kv + c.h) * 2 + (tid & 1)];
+        }
+    };
+    auto dma_new = [&](const ItemCtx& c, int nt, int buf) {
+        char* dst = smem + buf * kStageBytes + wave_u * 1024;
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            const int off = ps * NT * 16 + wave_u * 1024;      // whole waves stay inside one page
+            const int slot = off / GN::PAGE_BYTES, within = off - slot * GN::PAGE_BYTES + lane * 16;
+            const int pgi = nt * GN::PPS + slot;
+            if (pgi < c.nq_pages) {                            // wave-uniform
+                const char* src = c.new_base + (size_t)pgi * n_kv * GN::PAGE_BYTES + within;
+                __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(dst + ps * NT * 16), 16, 0, 0);
+            }
+        }
+    };
+    auto dma_first = [&](const ItemCtx& c, int buf) {          // first stage of a work item (ids already requested)
+        if (c.n_tiles > 0) dma_doc(c, buf);
+        else dma_new(c, 0, buf);                               // there is always at least one query key
+    };
+    // Invariant: pgid holds the ids of the next document tile in stream order after the last requested one.  Called
+    // right after the stage of document tile `tile` of item `c_item` has been requested (documents of length 0 have
+    // no tiles and are skipped; normally the scan takes one step).
+    auto ids_after = [&](const ItemCtx& c, int tile, int c_item) {
+        if (tile + 1 < c.n_tiles) {
+            ids_load(c, tile + 1);
+            return;
+        }
+        for (int it = c_item + (int)gridDim.x; it < n_items; it += (int)gridDim.x) {
+            const ItemCtx n = load_ctx(it);
+            if (n.n_tiles > 0) {
+                ids_load(n, 0);
+                return;
+            }
+        }
+    };
+    auto scale_store = [&](int buf) {
+        if constexpr (FP8) {
+            if (tid < G::PPS * 2) s_scale[buf * G::PPS * 2 + tid] = stg_scale;
+        }
+    };
+
+    halfx8 qf[R][KC];      // Q^T fragments (B operand), loaded once the first stage is on its way
     int row_i[R];          // query token index of the lane's row in block rb
     size_t row_off[R];     // element offset of that row in q / o
     bool row_ok[R];
-#pragma unroll
-    for (int rb = 0; rb < R; ++rb) {
-        int row = (wave + rb * NW) * 32 + ln;
-        row_ok[rb] = row < M;
-        int rc = row < M ? row : M - 1;
-        int i = rc / g, a = rc - i * g;
-        row_i[rb] = i;
-        row_off[rb] = ((size_t)(t0 + i) * n_q + h * g + a) * HD;
-#pragma unroll
-        for (int kk = 0; kk < KC; ++kk) qf[rb][kk] = *(const halfx8*)(q + row_off[rb] + (2 * kk + hh) * 8);
-    }
-
     floatx16 oacc[R][MB];
     float m_run[R], l_run[R];
-#pragma unroll
-    for (int rb = 0; rb < R; ++rb) {
-        m_run[rb] = -INFINITY;
-        l_run[rb] = 0.f;
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[rb][mb][r] = 0.f;
-    }
+    int M = 0;             // query rows of the current work item
 
-    // ---- one 32-key sub-tile held in LDS (two pages) against every row block of this wave
+    // ---- one 32-key sub-tile held in LDS (two pages) against every row block of this wave.
+    // Order: K fragments -> S = K Q^T for all row blocks -> V^T fragments (K registers are dead by then, the
+    // LDS latency hides under the softmax) -> softmax -> O^T += V^T P^T.
     auto process = [&](auto kv8_tag, auto causal_tag, const char* sb, int st, int key0, int n_valid, const float* sc) {
+#ifdef HR_ATTN_SKIP_COMPUTE
+        return;      // memory-structure probe: stream the pages, do no arithmetic
+#endif
         constexpr bool KV8 = decltype(kv8_tag)::value;
         constexpr bool CAUSAL = decltype(causal_tag)::value;
         using GG = Geo<HD, KV8>;
-        // K fragments (A operand): lane = key row ln of the sub-tile, channels chunk (2 kk + hh)
-        halfx8 kf[KC];
+        floatx16 s[R];
         {
+            // K fragments (A operand): lane = key row ln of the sub-tile, channels chunk (2 kk + hh)
+            halfx8 kf[KC];
             const int t = ln & 15;
             const char* kb = sb + (st * 2 + (ln >> 4)) * GG::PAGE_BYTES;
 #pragma unroll
@@ -123,48 +226,60 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(const half_t* __rest
                 if constexpr (KV8) kf[kk] = fp8x8_to_half(*(const uint2*)(kb + e));
                 else kf[kk] = *(const halfx8*)(kb + e * 2);
             }
+#pragma unroll
+            for (int rb = 0; rb < R; ++rb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
+                if ((wave + rb * NW) * 32 >= M) continue;          // wave-uniform
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk) s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[kk], qf[rb][kk], s[rb], 0, 0, 0);
+            }
         }
-        // V^T fragments (A operand): lane = channel mb*32 + ln, 8 keys of key group hh of page s
+        // fp8 pages: K scale goes into the softmax exponent (fp32).  The V scale is split into its power of two,
+        // applied exactly while expanding the codes, and its mantissa in [1, 2), applied to the probabilities: folding
+        // the whole scale (~1e-2) into P would push probabilities into the subnormal range of half.
+        float cs0 = c_log2, cs1 = c_log2, vs0 = 1.f, vs1 = 1.f, vp0 = 1.f, vp1 = 1.f;
+        if constexpr (KV8) {
+            cs0 *= sc[(st * 2) * 2];
+            cs1 *= sc[(st * 2 + 1) * 2];
+            vp0 = sc[(st * 2) * 2 + 1];
+            vp1 = sc[(st * 2 + 1) * 2 + 1];
+            vs0 = __uint_as_float((__float_as_uint(vp0) & 0x007FFFFFu) | 0x3F800000u);
+            vs1 = __uint_as_float((__float_as_uint(vp1) & 0x007FFFFFu) | 0x3F800000u);
+        }
+        // V^T fragments (A operand): lane = channel mb*32 + ln, 8 keys of key group hh of page s2
         halfx8 vf[MB][2];
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            const char* vb = sb + (st * 2 + s) * GG::PAGE_BYTES + GG::BLOCK_BYTES;
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const char* vb = sb + (st * 2 + s2) * GG::PAGE_BYTES + GG::BLOCK_BYTES;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 const int e = (hh * HD + mb * 32 + ln) * 8;
-                if constexpr (KV8) vf[mb][s] = fp8x8_to_half(*(const uint2*)(vb + e));
-                else vf[mb][s] = *(const halfx8*)(vb + e * 2);
+                if constexpr (KV8) vf[mb][s2] = fp8x8_to_half(*(const uint2*)(vb + e), s2 == 0 ? vp0 : vp1);
+                else vf[mb][s2] = *(const halfx8*)(vb + e * 2);
             }
-        }
-        float cs0 = c_log2, cs1 = c_log2, vs0 = 1.f, vs1 = 1.f;
-        if constexpr (KV8) {
-            cs0 *= sc[(st * 2) * 2];
-            vs0 = sc[(st * 2) * 2 + 1];
-            cs1 *= sc[(st * 2 + 1) * 2];
-            vs1 = sc[(st * 2 + 1) * 2 + 1];
         }
 #pragma unroll
         for (int rb = 0; rb < R; ++rb) {
             if ((wave + rb * NW) * 32 >= M) continue;          // wave-uniform
-            floatx16 s;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-            for (int kk = 0; kk < KC; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[kk], qf[rb][kk], s, 0, 0, 0);
+            floatx16& sr = s[rb];
             // lane holds keys key0 + 8*(r>>2) + 4*hh + (r&3) of query row ln
             const int limit = CAUSAL ? min(n_valid, row_i[rb] + 1) : n_valid;     // keys [0, limit) visible (sub-tile relative)
-            const bool need_mask = limit < 32;
-            float mx = -INFINITY;
+            if (limit < 32) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                float v = s[r] * (r < 8 ? cs0 : cs1);
-                if (need_mask) {
+                for (int r = 0; r < 16; ++r) {
                     const int key = 8 * (r >> 2) + 4 * hh + (r & 3);
-                    v = key < limit ? v : -INFINITY;
+                    sr[r] = key < limit ? sr[r] : -INFINITY;
                 }
-                s[r] = v;
-                mx = fmaxf(mx, v);
             }
+            // row maximum of the scaled logits: the two pages of a sub-tile may carry different (positive) K scales
+            float mx0 = sr[0], mx1 = sr[8];
+#pragma unroll
+            for (int r = 1; r < 8; ++r) {
+                mx0 = fmaxf(mx0, sr[r]);
+                mx1 = fmaxf(mx1, sr[8 + r]);
+            }
+            float mx = fmaxf(mx0 * cs0, mx1 * cs1);
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_new = fmaxf(m_run[rb], mx);
             const float alpha = m_run[rb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[rb] - m_new);
@@ -172,9 +287,9 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(const half_t* __rest
             float lsum = 0.f;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                float pr = __builtin_amdgcn_exp2f(s[r] - m_use);
+                const float pr = __builtin_amdgcn_exp2f(fmaf(sr[r], r < 8 ? cs0 : cs1, -m_use));
                 lsum += pr;
-                s[r] = pr;
+                sr[r] = pr;
             }
             l_run[rb] = l_run[rb] * alpha + lsum;
             m_run[rb] = m_new;
@@ -186,9 +301,12 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(const half_t* __rest
             }
             halfx8 pf[2];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                pf[0][j] = (half_t)(KV8 ? s[j] * vs0 : s[j]);
-                pf[1][j] = (half_t)(KV8 ? s[8 + j] * vs1 : s[8 + j]);
+            for (int j = 0; j < 8; j += 2) {
+                const floatx2 a = {KV8 ? sr[j] * vs0 : sr[j], KV8 ? sr[j + 1] * vs0 : sr[j + 1]};
+                const floatx2 b = {KV8 ? sr[8 + j] * vs1 : sr[8 + j], KV8 ? sr[9 + j] * vs1 : sr[9 + j]};
+                const halfx2 ha = __builtin_convertvector(a, halfx2), hb2 = __builtin_convertvector(b, halfx2);
+                pf[0][j] = ha[0]; pf[0][j + 1] = ha[1];
+                pf[1][j] = hb2[0]; pf[1][j + 1] = hb2[1];
             }
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
@@ -198,113 +316,154 @@ __global__ void __launch_bounds__(NW * 64) attn_mfma_kernel(const half_t* __rest
         }
     };
 
-    // ---- document pages: HBM -> registers -> LDS, double buffered
-    const int n_pages = (D + kPageTokens - 1) / kPageTokens;
-    const int n_tiles = (n_pages + G::PPS - 1) / G::PPS;
-    const int32_t* pt = mv.page_table + (size_t)p * mv.pt_stride;
-    const char* pool = pv.data;
-    const size_t page_stride = (size_t)n_kv * G::PAGE_BYTES;                         // between consecutive page ids
-    const char* layer_base = pool + ((size_t)layer * pv.num_pages * n_kv + h) * G::PAGE_BYTES;
-    uint4 stg[NPASS];
-    float stg_scale = 0.f;
-    auto gload = [&](int tile) {
+    // ---- persistent loop over work items.  The first stage of the next item is requested while the last stage of
+    // the current one is consumed, and its Q fragments are fetched before the current item's output is stored, so
+    // only the very first item of a workgroup pays the start-up latency.
+    auto setup_rows = [&](const ItemCtx& c) {
+        M = c.qn * g;
 #pragma unroll
-        for (int ps = 0; ps < NPASS; ++ps) {
-            const int off = ps * NT * 16 + tid * 16;
-            const int slot = off / G::PAGE_BYTES, within = off - slot * G::PAGE_BYTES;
-            int pgi = tile * G::PPS + slot;
-            pgi = pgi < n_pages ? pgi : n_pages - 1;           // past the end: re-read the last page (finite data, masked)
-            stg[ps] = *(const uint4*)(layer_base + (size_t)pt[pgi] * page_stride + within);
-        }
-        if constexpr (FP8) {
-            if (tid < G::PPS * 2) {
-                int pgi = tile * G::PPS + (tid >> 1);
-                pgi = pgi < n_pages ? pgi : n_pages - 1;
-                stg_scale = pv.scales[(((size_t)layer * pv.num_pages + pt[pgi]) * n_kv + h) * 2 + (tid & 1)];
-            }
-        }
-    };
-    auto lstore = [&](int buf) {
+        for (int rb = 0; rb < R; ++rb) {
+            int row = (wave + rb * NW) * 32 + ln;
+            row_ok[rb] = row < M;
+            int rc = row < M ? row : M - 1;
+            int i = rc / g, a = rc - i * g;
+            row_i[rb] = i;
+            row_off[rb] = ((size_t)(c.t0 + i) * n_q + c.h * g + a) * HD;
 #pragma unroll
-        for (int ps = 0; ps < NPASS; ++ps) *(uint4*)(smem + buf * kStageBytes + ps * NT * 16 + tid * 16) = stg[ps];
-        if constexpr (FP8) {
-            if (tid < G::PPS * 2) s_scale[buf * G::PPS * 2 + tid] = stg_scale;
+            for (int kk = 0; kk < KC; ++kk) qf[rb][kk] = *(const halfx8*)(q + row_off[rb] + (2 * kk + hh) * 8);
         }
     };
 
-    if (n_tiles > 0) {
-        gload(0);
-        lstore(0);
-    }
-    __syncthreads();
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int cur = tile & 1;
-        if (tile + 1 < n_tiles) gload(tile + 1);
-        const char* sb = smem + cur * kStageBytes;
-        const float* sc = s_scale + cur * G::PPS * 2;
+    halfx4 opk[R][MB][4];                           // previous item's output, packed, waiting to be stored
+    size_t out_off[R];
+    bool out_ok[R];
+    bool out_pending = false;
+    auto flush_out = [&]() {
+        if (!out_pending) return;
+#pragma unroll
+        for (int rb = 0; rb < R; ++rb) {
+            if (!out_ok[rb]) continue;
+            half_t* dst = o + out_off[rb];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) *(halfx4*)(dst + mb * 32 + 8 * r4 + 4 * hh) = opk[rb][mb][r4];
+        }
+        out_pending = false;
+    };
+
+    int stage = 0;                                  // LDS stage that holds (or will hold) the current item's next tile
+    ItemCtx cur = load_ctx(blockIdx.x);
+    HR_ASTAMP();
+    if (cur.n_tiles > 0) ids_load(cur, 0);
+    dma_first(cur, 0);
+    ids_after(cur, 0, (int)blockIdx.x);
+    setup_rows(cur);
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int next_item = item + gridDim.x;
+        const bool has_next = next_item < n_items;
+        const ItemCtx nxt = has_next ? load_ctx(next_item) : cur;
+#pragma unroll
+        for (int rb = 0; rb < R; ++rb) {
+            m_run[rb] = -INFINITY;
+            l_run[rb] = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[rb][mb][r] = 0.f;
+        }
+        if (cur.n_tiles > 0) scale_store(stage);
+        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0): this wave's part of the stage has landed
+        __syncthreads();                          // ... and everyone is past the previous item's last stage
+        flush_out();                              // previous item's output: completes under this item's first stage
+
+        for (int tile = 0; tile < cur.n_tiles; ++tile) {
+            HR_ASTAMP();
+            // every wave is past its reads of the other stage (barrier at the end of the previous iteration)
+            if (tile + 1 < cur.n_tiles) {
+                dma_doc(cur, stage ^ 1);
+                ids_after(cur, tile + 1, item);
+            } else {
+                dma_new(cur, 0, stage ^ 1);
+            }
+            const char* sb = smem + stage * kStageBytes;
+            const float* sc = s_scale + stage * G::PPS * 2;
 #pragma unroll 1
-        for (int st = 0; st < G::TK / 32; ++st) {
-            const int key0 = tile * G::TK + st * 32;
-            if (key0 >= D) break;
-            process(std::integral_constant<bool, FP8>{}, std::false_type{}, sb, st, key0, D - key0, sc);
-        }
-        if (tile + 1 < n_tiles) lstore(cur ^ 1);
-        __syncthreads();
-    }
-
-    // ---- the pair's own query keys (causal), staged once as half pseudo-pages in the same arrangement
-    {
-        const int nq_pages = ((qn + 31) / 32) * 2;                   // whole 32-key sub-tiles
-        const int chunks = nq_pages * kPageTokens * (HD / 8);       // 16-byte chunks of K (and of V)
-        for (int idx = tid; idx < chunks; idx += NT) {
-            const int j = idx / (HD / 8), ch = idx - j * (HD / 8);   // key j, channel chunk ch
-            const int pg = j >> 4, t = j & 15;
-            halfx8 kv = {0, 0, 0, 0, 0, 0, 0, 0}, vv = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (j < qn) {
-                const size_t src = ((size_t)(t0 + j) * n_kv + h) * HD + ch * 8;
-                kv = *(const halfx8*)(k_new + src);
-                vv = *(const halfx8*)(v_new + src);
+            for (int st = 0; st < G::TK / 32; ++st) {
+                const int key0 = tile * G::TK + st * 32;
+                if (key0 >= cur.D) break;
+                process(std::integral_constant<bool, FP8>{}, std::false_type{}, sb, st, key0, cur.D - key0, sc);
             }
-            char* pb = smem + pg * GN::PAGE_BYTES;
-            *(halfx8*)(pb + (t * HD + ((ch ^ k_swizzle(t, HD, 2)) << 3)) * 2) = kv;
-            half_t* vb = (half_t*)(pb + GN::BLOCK_BYTES);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) vb[v_elem(t, ch * 8 + e, HD)] = vv[e];
+            HR_ASTAMP();
+            if (tile + 1 < cur.n_tiles) scale_store(stage ^ 1);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+            stage ^= 1;
         }
-        __syncthreads();
-        for (int st = 0; st < nq_pages / 2; ++st) {
-            const int key0 = st * 32;
-            // row i sees new keys 0..i: sub-tile relative limit is i + 1 - key0
-#pragma unroll
-            for (int rb = 0; rb < R; ++rb) row_i[rb] -= key0;
-            process(std::false_type{}, std::true_type{}, smem, st, key0, qn - key0, nullptr);
-#pragma unroll
-            for (int rb = 0; rb < R; ++rb) row_i[rb] += key0;
-        }
-    }
-
-    // ---- normalise and store: lane owns query row ln of each block, channels mb*32 + 8*(r>>2) + 4*hh + (r&3)
-#pragma unroll
-    for (int rb = 0; rb < R; ++rb) {
-        const float l = l_run[rb] + __shfl_xor(l_run[rb], 32, 64);
-        if (!row_ok[rb]) continue;
-        const float inv = 1.0f / l;
-        half_t* dst = o + row_off[rb];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                halfx4 w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = from_float<half_t>(oacc[rb][mb][r4 * 4 + e] * inv);
-                *(halfx4*)(dst + mb * 32 + 8 * r4 + 4 * hh) = w;
+        for (int nt = 0; nt < cur.n_new_tiles; ++nt) {
+            HR_ASTAMP();
+            const bool last = nt + 1 == cur.n_new_tiles;
+            if (!last) dma_new(cur, nt + 1, stage ^ 1);
+            else if (has_next) {
+                dma_first(nxt, stage ^ 1);
+                if (nxt.n_tiles > 0) ids_after(nxt, 0, next_item);
             }
+            const char* sb = smem + stage * kStageBytes;
+#pragma unroll 1
+            for (int st = 0; st < GN::TK / 32; ++st) {
+                const int key0 = nt * GN::TK + st * 32;
+                if (key0 >= cur.qn) break;
+                // row i sees new keys 0..i: the sub-tile relative limit is i + 1 - key0
+#pragma unroll
+                for (int rb = 0; rb < R; ++rb) row_i[rb] -= key0;
+                process(std::false_type{}, std::true_type{}, sb, st, key0, cur.qn - key0, nullptr);
+#pragma unroll
+                for (int rb = 0; rb < R; ++rb) row_i[rb] += key0;
+            }
+            HR_ASTAMP();
+            if (!last) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+                __syncthreads();
+            }
+            stage ^= 1;
+        }
+
+        // ---- normalise; the output is packed to half and kept in registers: the stores are issued after the next
+        // item's first barrier (flush_out), so neither their issue nor their completion sits in front of a vmcnt wait.
+        // The next item's Q fragments are requested now so their latency hides as well.
+#pragma unroll
+        for (int rb = 0; rb < R; ++rb) {
+            const float l = l_run[rb] + __shfl_xor(l_run[rb], 32, 64);
+            const float inv = 1.0f / l;
+            out_off[rb] = row_off[rb];
+            out_ok[rb] = row_ok[rb];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) opk[rb][mb][r4][e] = from_float<half_t>(oacc[rb][mb][r4 * 4 + e] * inv);
+        }
+        out_pending = true;
+        if (has_next) setup_rows(nxt);
+        HR_ASTAMP();
+        cur = nxt;
     }
+    flush_out();
+}
+
+int attn_wgs_override() {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = getenv("HR_ATTN_WGS");      // tuning runs only
+        v = e ? atoi(e) : 0;
+    }
+    return v;
 }
 
 template <int HD, int NW, int R, bool FP8>
-hipError_t launch_one(const half_t* q, const half_t* k, const half_t* v, half_t* o, const MetaView& mv, const PoolView& pv,
-                      int layer, int n_q, hipStream_t st) {
+hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const MetaView& mv, const PoolView& pv, int layer, int n_q,
+                      hipStream_t st) {
     const size_t lds = 2 * kStageBytes + 2 * Geo<HD, FP8>::PPS * 2 * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
@@ -313,7 +472,23 @@ hipError_t launch_one(const half_t* q, const half_t* k, const half_t* v, half_t*
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    attn_mfma_kernel<HD, NW, R, FP8><<<dim3((unsigned)(mv.n_seq * pv.n_kv)), NW * 64, lds, st>>>(q, k, v, o, mv, pv, layer, n_q);
+#ifdef HR_ATTN_TRACE
+    (void)hipMemcpyToSymbolAsync(HIP_SYMBOL(g_attn_trace_dev), &g_attn_trace, sizeof(long long*), 0, hipMemcpyHostToDevice, st);
+#endif
+    // persistent grid: as many workgroups as can be resident (LDS: two per CU), each loops over work items
+    static int max_wgs = 0;
+    if (max_wgs == 0) {
+        int dev = 0, per_cu = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<HD, NW, R, FP8>, NW * 64, lds) != hipSuccess || per_cu < 1)
+            per_cu = 1;
+        max_wgs = prop.multiProcessorCount * per_cu;
+    }
+    const int n_items = mv.n_seq * pv.n_kv;
+    const int env_wgs = attn_wgs_override();
+    const int grid = std::min(n_items, env_wgs > 0 ? env_wgs : max_wgs);
+    attn_mfma_kernel<HD, NW, R, FP8><<<dim3((unsigned)grid), NW * 64, lds, st>>>(q, kv_new, o, mv, pv, layer, n_q);
     return hipGetLastError();
 }
 
@@ -332,22 +507,21 @@ bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len) {
     return true;
 }
 
-hipError_t launch_attn_mfma(const void* q, const void* k_new, const void* v_new, void* o, const MetaView& mv, const PoolView& pv,
-                            int layer, int n_q, int max_q_len, hipStream_t st) {
+hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv, const PoolView& pv, int layer,
+                            int n_q, int max_q_len, hipStream_t st) {
     if (mv.n_seq == 0) return hipSuccess;
     const int rows = n_q / pv.n_kv * max_q_len;
     const half_t* qh = (const half_t*)q;
-    const half_t* kh = (const half_t*)k_new;
-    const half_t* vh = (const half_t*)v_new;
+    const char* kvn = (const char*)kv_new_pages;
     half_t* oh = (half_t*)o;
     const bool fp8 = pv.kv_dtype == HR_FP8_E4M3;
 #define HR_ATTN_CASE(HD, NW, R)                                                                       \
-    return fp8 ? launch_one<HD, NW, R, true>(qh, kh, vh, oh, mv, pv, layer, n_q, st)                   \
-               : launch_one<HD, NW, R, false>(qh, kh, vh, oh, mv, pv, layer, n_q, st)
+    return fp8 ? launch_one<HD, NW, R, true>(qh, kvn, oh, mv, pv, layer, n_q, st)                       \
+               : launch_one<HD, NW, R, false>(qh, kvn, oh, mv, pv, layer, n_q, st)
     static int var = -1;
     if (var < 0) {
         const char* e = getenv("HR_ATTN_VARIANT");
-        var = e ? atoi(e) : 1;
+        var = e ? atoi(e) : 0;
     }
     if (pv.d == 64) {
         if (rows <= 128) { HR_ATTN_CASE(64, 4, 1); }

@@ -144,6 +144,10 @@ int run_layers(hr_model* m, const hr_pool* pool, const MetaView& mv, const Works
     }
     const bool mfma_attn = !m->force_generic && attn_mfma_supported(c, pv.kv_dtype, max_new_len);
 
+    // with the MFMA attention the new tokens' K/V are written straight into 16-slot pages (k and v regions together);
+    // slots past a sequence's end are never written by any layer, so one clear per call keeps them finite
+    const size_t kv_region = ws.off_o - ws.off_k;
+    if (mfma_attn) HR_TIMED(PC_EMBED, launch_fill_zero(k, kv_region, st));
     HR_TIMED(PC_EMBED, launch_embed(dt, m->embedding, mv, x, H, st));
     HR_TIMED(PC_EMBED, launch_rope_table(mv, rope, d, c.rope_base, st));
     for (int l = 0; l < c.n_layers; ++l) {
@@ -152,13 +156,14 @@ int run_layers(hr_model* m, const hr_pool* pool, const MetaView& mv, const Works
             GemmArgs a{};
             a.A = y; a.W = layer_w(m, l, m->pack.wqkv); a.M = T; a.N = nqkv; a.K = H;
             a.out0 = q; a.out1 = k; a.out2 = v; a.rope = rope; a.n_q = c.n_q_heads; a.n_kv = c.n_kv_heads; a.d = d;
+            if (mfma_attn) { a.kv_pages = k; a.new_slot = mv.new_slot; }
             HR_TIMED(PC_GEMM_QKV, launch_gemm_mfma(EPI_QKV_ROPE, a, st));
         } else {
             HR_TIMED(PC_GEMM_QKV, launch_gemm_generic(dt, y, layer_w(m, l, m->pack.wqkv), f32, T, nqkv, H, false, st));
             HR_TIMED(PC_ELEMENTWISE, launch_rope_split(dt, f32, rope, q, k, v, T, c.n_q_heads, c.n_kv_heads, d, st));
         }
         if (mfma_attn) {
-            HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, v, o, mv, pv, l, c.n_q_heads, max_new_len, st));
+            HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, o, mv, pv, l, c.n_q_heads, max_new_len, st));
         } else {
             HR_TIMED(PC_ATTENTION, launch_attn_generic(dt, q, k, v, o, mv, pv, l, c.n_q_heads, max_keys, st));
         }
@@ -195,6 +200,8 @@ MetaView make_meta_view(const int32_t* dev_meta, const MetaLayout& ml, int64_t n
     mv.tok_seq = dev_meta + ml.tok_seq;
     mv.prefix_len = dev_meta + ml.prefix_len;
     mv.page_table = dev_meta + ml.page_table;
+    mv.new_slot = dev_meta + ml.new_slot;
+    mv.new_cu = dev_meta + ml.new_cu;
     mv.pt_stride = (int32_t)pt_stride;
     mv.n_seq = (int32_t)n_seq;
     mv.T = T;

@@ -21,6 +21,7 @@
 
 #include "hr_device_types.h"
 #include "hr_kernels.h"
+#include "hr_layout.h"
 
 namespace hr {
 
@@ -242,6 +243,12 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
         static_assert(EPI != EPI_QKV_ROPE || NI % (2 * HB) == 0, "a wave must hold whole heads");
         const int d = a.d, half = d / 2;
         const int nq = a.n_q * d, nkv = a.n_kv * d;
+        int slot_i[MI];
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int64_t row = row_base + i * 32;
+            slot_i[i] = (a.kv_pages && row < a.M) ? a.new_slot[row] : 0;
+        }
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             const int64_t row = row_base + i * 32;
@@ -256,11 +263,19 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const int col = col_base + j * 32 + 8 * r4;
                     if (col >= a.N) continue;
-                    half_t* dst;
+                    half_t* dst = nullptr;
                     bool rot = true;
+                    int kv_head = -1, kv_c = 0;           // paged K/V: kv head and channel of the quad
+                    bool is_v = false;
                     if (col < nq) dst = (half_t*)a.out0 + row * nq + col;
-                    else if (col < nq + nkv) dst = (half_t*)a.out1 + row * nkv + (col - nq);
-                    else { dst = (half_t*)a.out2 + row * nkv + (col - nq - nkv); rot = false; }
+                    else if (col < nq + nkv) {
+                        if (a.kv_pages) { kv_head = (col - nq) / d; kv_c = (col - nq) - kv_head * d; }
+                        else dst = (half_t*)a.out1 + row * nkv + (col - nq);
+                    } else {
+                        rot = false;
+                        if (a.kv_pages) { kv_head = (col - nq - nkv) / d; kv_c = (col - nq - nkv) - kv_head * d; is_v = true; }
+                        else dst = (half_t*)a.out2 + row * nkv + (col - nq - nkv);
+                    }
                     const int jj = (lo ? blk : blk - hb) * 32 + 8 * r4 + 4 * fh;   // rotary index of the quad
                     halfx4 w;
 #pragma unroll
@@ -272,6 +287,19 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
                             val = lo ? val * cs.x - other * cs.y : val * cs.x + other * cs.y;
                         }
                         w[e] = from_float<half_t>(val);
+                    }
+                    if (kv_head >= 0) {
+                        // 16-slot pages in the pool arrangement: [page][kv head][K block | V block]
+                        const int slot = slot_i[i];
+                        half_t* blk0 = (half_t*)a.kv_pages + ((size_t)(slot >> 4) * a.n_kv + kv_head) * (2 * kPageTokens * d);
+                        const int t = slot & 15;
+                        if (!is_v) *(halfx4*)(blk0 + k_elem(t, kv_c, d, 2)) = w;
+                        else {
+                            half_t* vb = blk0 + kPageTokens * d;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) vb[v_elem(t, kv_c + e, d)] = w[e];
+                        }
+                        continue;
                     }
                     *(halfx4*)dst = w;
                 }

@@ -69,6 +69,8 @@ MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride) {
     m.tok_seq = o;     o = up(o + (size_t)T);
     m.prefix_len = o;  o = up(o + (size_t)n_seq);
     m.page_table = o;  o = up(o + (size_t)n_seq * (size_t)pt_stride);
+    m.new_slot = o;    o = up(o + (size_t)T);
+    m.new_cu = o;      o = up(o + (size_t)n_seq + 1);
     m.total = o;
     return m;
 }
@@ -87,8 +89,11 @@ Workspace make_workspace(const hr_model_cfg& c, int64_t n_seq, int64_t T, int64_
     w.off_x = o;    o = align_up(o + t * H * sizeof(float));
     w.off_y = o;    o = align_up(o + t * H * asz);
     w.off_q = o;    o = align_up(o + t * nq * asz);
-    w.off_k = o;    o = align_up(o + t * nkv * asz);
-    w.off_v = o;    o = align_up(o + t * nkv * asz);
+    // new-token K and V: either [T][n_kv][d] each, or pages of 16 slots (32-slot aligned per sequence), K|V blocks
+    // interleaved like the pool; one region of 2 * (T + 32 n_seq) token slots serves both forms
+    const size_t kv_slots = t + 32 * (size_t)n_seq;
+    w.off_k = o;    o = align_up(o + kv_slots * nkv * asz);
+    w.off_v = o;    o = align_up(o + kv_slots * nkv * asz);
     w.off_o = o;    o = align_up(o + t * nq * asz);
     w.off_m = o;    o = align_up(o + t * F * asz);
     w.off_f32 = o;
@@ -164,7 +169,10 @@ void fill_meta(int32_t* meta, const MetaLayout& ml, int64_t n_seq, const int32_t
     int32_t* tok_pos = meta + ml.tok_pos;
     int32_t* tok_seq = meta + ml.tok_seq;
     int32_t* pre = meta + ml.prefix_len;
+    int32_t* new_slot = meta + ml.new_slot;
+    int32_t* new_cu = meta + ml.new_cu;
     int64_t t = 0;
+    int64_t slot0 = 0;
     cu[0] = 0;
     for (int64_t p = 0; p < n_seq; ++p) {
         int32_t D = prefix_lens ? prefix_lens[p] : 0;
@@ -173,9 +181,13 @@ void fill_meta(int32_t* meta, const MetaLayout& ml, int64_t n_seq, const int32_t
             tok_id[t] = tokens[t];
             tok_pos[t] = D + i;       // positions continue right after the document
             tok_seq[t] = (int32_t)p;
+            new_slot[t] = (int32_t)(slot0 + i);
         }
         cu[p + 1] = (int32_t)t;
+        new_cu[p] = (int32_t)slot0;
+        slot0 += ((int64_t)new_lens[p] + 31) / 32 * 32;
     }
+    new_cu[n_seq] = (int32_t)slot0;
     if (page_table && pt_stride > 0)
         std::memcpy(meta + ml.page_table, page_table, sizeof(int32_t) * (size_t)n_seq * (size_t)pt_stride);
 }

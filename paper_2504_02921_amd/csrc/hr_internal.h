@@ -59,8 +59,10 @@ struct Workspace {
 Workspace make_workspace(const hr_model_cfg& cfg, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch);
 
 // Metadata block layout (int32 offsets inside the block), uploaded once per call.
+// new_slot[t] / new_cu[p]: where the K/V of new token t goes when the new keys are kept as 16-token
+// pages per sequence (each sequence starts on a 32-slot boundary so that MFMA sub-tiles are whole).
 struct MetaLayout {
-    size_t cu = 0, tok_id = 0, tok_pos = 0, tok_seq = 0, prefix_len = 0, page_table = 0, total = 0;
+    size_t cu = 0, tok_id = 0, tok_pos = 0, tok_seq = 0, prefix_len = 0, page_table = 0, new_slot = 0, new_cu = 0, total = 0;
 };
 MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride);
 

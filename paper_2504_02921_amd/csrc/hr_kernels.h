@@ -24,6 +24,8 @@ struct MetaView {
     const int32_t* tok_seq;     // [T] sequence of each token
     const int32_t* prefix_len;  // [n_seq] cached-document length
     const int32_t* page_table;  // [n_seq][pt_stride]
+    const int32_t* new_slot;    // [T] slot of each new token in the paged new-KV buffer
+    const int32_t* new_cu;      // [n_seq + 1] first slot of each sequence (multiples of 32)
     int32_t pt_stride;
     int32_t n_seq;
     int64_t T;
@@ -64,11 +66,17 @@ struct GemmArgs {
     void* out2;         // EPI_QKV_ROPE: v
     const float2* rope; // [M][d/2]
     int n_q, n_kv, d;
+    // EPI_QKV_ROPE, optional: K and V of the new tokens go to 16-slot pages (pool arrangement) at kv_pages,
+    // token t at slot new_slot[t]; out1 / out2 are ignored then
+    void* kv_pages;
+    const int32_t* new_slot;
 };
 hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st);
 
 bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len);
-hipError_t launch_attn_mfma(const void* q, const void* k_new, const void* v_new, void* o, const MetaView& mv,
+// kv_new_pages: the new tokens' K/V as pages (see GemmArgs::kv_pages)
+hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv,
                             const PoolView& pv, int layer, int n_q, int max_q_len, hipStream_t st);
+hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t st);
 
 }  // namespace hr

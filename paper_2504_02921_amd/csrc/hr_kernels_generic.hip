@@ -4,6 +4,8 @@
 // weight packing) serve every path.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "hr_device_types.h"
 #include "hr_kernels.h"
 #include "hr_layout.h"
@@ -302,9 +304,23 @@ __global__ void pack_rows_kernel(const S* __restrict__ src, D* __restrict__ dst,
     for (int c = threadIdx.x; c < cols; c += blockDim.x) dst[drow * cols + c] = from_float<D>(to_float<S>(src[(size_t)r * cols + c]));
 }
 
+__global__ void fill_zero_kernel(uint4* dst, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = make_uint4(0, 0, 0, 0);
+}
+
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
+hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t st) {     // bytes: multiple of 16
+    if (bytes == 0) return hipSuccess;
+    const size_t n16 = bytes / 16;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 4096);
+    fill_zero_kernel<<<dim3(blocks), 256, 0, st>>>((uint4*)dst, n16);
+    return hipGetLastError();
+}
+
 #define HR_DISPATCH_ACT(dtype, ...)                                   \
     do {                                                              \
         if ((dtype) == HR_F32) { using AT = float; __VA_ARGS__; }      \
