@@ -66,6 +66,43 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ 
     for (int c = threadIdx.x; c < H; c += 256) yr[c] = from_float<T>(xr[c] * rs * gain[c]);
 }
 
+// Same, for 16-bit outputs and H a multiple of 4 up to 4 * 256 * VPT: the row stays in registers between the
+// reduction and the scaling (one pass over HBM), 16-byte loads, 8-byte stores.
+template <int VPT>
+__global__ void __launch_bounds__(256) rmsnorm_vec_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                          half_t* __restrict__ y, int H, float eps) {
+    __shared__ float red[4];
+    const size_t t = blockIdx.x;
+    const float4* xr = (const float4*)(x + t * H);
+    const float4* gr = (const float4*)gain;
+    const int n4 = H >> 2;
+    float4 v[VPT];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int c = threadIdx.x + i * 256;
+        v[i] = c < n4 ? xr[c] : make_float4(0.f, 0.f, 0.f, 0.f);
+        ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
+    }
+    ss = block_sum_256(ss, red);
+    const float rs = 1.0f / sqrtf(ss / (float)H + eps);
+    typedef __attribute__((ext_vector_type(4))) _Float16 h4;
+    h4* yr = (h4*)(y + t * H);
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+        const int c = threadIdx.x + i * 256;
+        if (c < n4) {
+            const float4 g = gr[c];
+            h4 o;
+            o[0] = from_float<half_t>(v[i].x * rs * g.x);
+            o[1] = from_float<half_t>(v[i].y * rs * g.y);
+            o[2] = from_float<half_t>(v[i].z * rs * g.z);
+            o[3] = from_float<half_t>(v[i].w * rs * g.w);
+            yr[c] = o;
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // generic GEMM: C[M][N] (+)= A[M][K] W[N][K]^T, 64x64 tile, 256 threads x (4x4), fp32 FMA
 // ------------------------------------------------------------------------------------------------
@@ -349,6 +386,12 @@ hipError_t launch_rope_table(const MetaView& mv, float2* tab, int head_dim, floa
 
 hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st) {
     if (T == 0) return hipSuccess;
+    if (dtype != HR_F32 && H % 4 == 0 && H <= 4096) {
+        if (H <= 1024) rmsnorm_vec_kernel<1><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps);
+        else if (H <= 2048) rmsnorm_vec_kernel<2><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps);
+        else rmsnorm_vec_kernel<4><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps);
+        return hipGetLastError();
+    }
     HR_DISPATCH_ACT(dtype, rmsnorm_kernel<AT><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (AT*)y, H, eps));
     return hipGetLastError();
 }
