@@ -43,7 +43,7 @@ def main():
     ap.add_argument("--workload", default="c2_qwen0p5b")
     ap.add_argument("--cpu-pairs", type=int, default=0, help="pairs for the CPU-oracle leg (0 = pick for ~15 s)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-reuse-pairs", type=int, default=16, help="pairs for the no-reuse reference (0 = skip)")
+    ap.add_argument("--no-reuse-pairs", type=int, default=256, help="pairs for the no-reuse reference (0 = skip)")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events during the timed steps")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -207,6 +207,9 @@ def main():
             el2, _, _ = run_oracle(order[:2])
             n_cpu = int(max(2, min(wl.n_pairs, 256, round(15.0 / max(el2 / 2, 1e-3)))))
         el, s_cpu, sub = run_oracle(order[:n_cpu])
+        while el < 8.0 and n_cpu < min(wl.n_pairs, 1024) and args.cpu_pairs <= 0:   # aim for 10-30 s of oracle time
+            n_cpu = int(min(wl.n_pairs, 1024, max(n_cpu + 1, round(n_cpu * 15.0 / max(el, 1e-3)))))
+            el, s_cpu, sub = run_oracle(order[:n_cpu])
         s_gpu = scores[torch.from_numpy(order[:n_cpu].copy()).to(dev)].cpu().numpy()
         cpu = {"value": round(n_cpu / el, 4), "unit": "pairs/s", "cores": int(cores), "kind": "oracle",
                "sample": f"{n_cpu} seeded pairs of {wl.n_pairs} ({el:.1f} s, float64 numpy" + ("" if oweights.keep else "; weight generation inside the timed call") + f")",

@@ -196,6 +196,22 @@ int hr_rerank_score_full(hr_model* model, int32_t n_pairs,
                          const int32_t* query_tokens, const int32_t* query_lens,
                          void* workspace_dev, size_t workspace_bytes, float* scores_dev, void* stream);
 
+/* ---- document prefill (stage one of the two-stage inference, Section 3.3 Property 1) ---- */
+
+/* Workspace bytes for hr_doc_prefill; 0 if the model / shape is not covered (see hr_doc_prefill). */
+size_t hr_doc_prefill_workspace_bytes(const hr_model* model, int32_t n_docs, int64_t total_tokens);
+
+/* Run n_docs documents alone through the layers (positions 0..len-1, causal) and store every layer's post-RoPE
+ * K and V in the pool pages the caller names, ready for hr_rerank_score.  Same kernels as the scoring pass: a
+ * document is processed as chunks of 64 tokens whose prefix is the document's own earlier pages.
+ *   doc_tokens  host int32, the documents' token ids back to back
+ *   doc_lens    host int32 [n_docs], each >= 1
+ *   page_table  host int32 [n_docs][pt_stride]; row d names ceil(doc_lens[d]/16) distinct free (or reserved) pages
+ * 16-bit pools and MFMA-covered models only (HR_ERR_UNSUPPORTED_SHAPE otherwise); pages are marked used on
+ * success.  Work is enqueued on `stream`. */
+int hr_doc_prefill(hr_model* model, hr_pool* pool, int32_t n_docs, const int32_t* doc_tokens, const int32_t* doc_lens,
+                   const int32_t* page_table, int32_t pt_stride, void* workspace_dev, size_t workspace_bytes, void* stream);
+
 /* ---- introspection for benchmarks ---- */
 
 /* Name of the kernel family a model/pool combination runs ("generic", "mfma"); never NULL. */

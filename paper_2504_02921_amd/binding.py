@@ -57,7 +57,7 @@ EXPORTS = [
     "hr_status_str", "hr_last_error", "hr_kv_pool_bytes", "hr_kv_pool_create", "hr_kv_pool_destroy", "hr_kv_pool_free_pages",
     "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_free", "hr_weights_pack_bytes", "hr_weights_load",
     "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_validate",
-    "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_attention_path", "hr_gemm_path",
+    "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
     "hr_profile_enable", "hr_profile_count", "hr_profile_name", "hr_profile_read",
 ]
 
@@ -96,6 +96,8 @@ def _load() -> C.CDLL:
         "hr_rerank_full_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int64]),
         "hr_rerank_score_full": (C.c_int, [C.c_void_p, C.c_int32, i32p, i32p, i32p, i32p, C.c_void_p, C.c_size_t,
                                            C.c_void_p, C.c_void_p]),
+        "hr_doc_prefill_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int64]),
+        "hr_doc_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, i32p, i32p, i32p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
         "hr_attention_path": (C.c_char_p, [C.c_void_p, C.c_void_p]),
         "hr_gemm_path": (C.c_char_p, [C.c_void_p]),
         "hr_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
@@ -314,6 +316,23 @@ class Model:
                                       C.c_void_p(ws.data_ptr()), ws.numel(), C.c_void_p(scores.data_ptr()), _stream_ptr(stream))
         check(st, "hr_rerank_score_full")
         return scores[:P]
+
+    def doc_prefill(self, pool: KVPool, doc_tokens: Sequence[np.ndarray], page_lists: Sequence[np.ndarray], stream=None) -> None:
+        """Compute and store the documents' K/V on the device (stage one)."""
+        n = len(doc_tokens)
+        dl = _i32([len(d) for d in doc_tokens])
+        stride = max(len(p) for p in page_lists)
+        pt = np.full((n, stride), -1, np.int32)
+        for i, pg in enumerate(page_lists):
+            pt[i, :len(pg)] = pg
+        toks = _i32(np.concatenate(doc_tokens))
+        nbytes = int(lib.hr_doc_prefill_workspace_bytes(self.handle, n, int(dl.sum())))
+        if nbytes == 0:
+            raise HrError(HR_ERR_UNSUPPORTED_SHAPE, "hr_doc_prefill_workspace_bytes")
+        ws = self._workspace(nbytes)
+        st = lib.hr_doc_prefill(self.handle, pool.handle, n, _i32p(toks), _i32p(dl), _i32p(pt), stride,
+                                C.c_void_p(ws.data_ptr()), ws.numel(), _stream_ptr(stream))
+        check(st, "hr_doc_prefill")
 
     def close(self):
         if getattr(self, "handle", None):

@@ -111,8 +111,22 @@ struct ProfScope {
     } while (0)
 
 // One pass of all layers over the T new tokens described by `mv`, scores for every sequence.
-int run_layers(hr_model* m, const hr_pool* pool, const MetaView& mv, const Workspace& ws, char* wsb, int max_keys,
-               int max_new_len, float* scores, hipStream_t st) {
+// Where a prefill pass stores each layer's K/V: pool page dst_page[i] <- new-KV page src_page[i] (device arrays)
+struct PrefillTarget {
+    hr_pool* pool;
+    const int32_t* src_page;
+    const int32_t* dst_page;
+    int n_pages;
+};
+
+// One pass of all layers over the T new tokens described by `mv`.
+//   pool         cached-document pool (scoring pass), or nullptr
+//   self_prefix  the sequences are chunks of longer sequences whose earlier tokens are found as pages of this call's
+//                own new-KV buffer (no-reuse pass, document prefill)
+//   fill         if set, every layer's K/V pages are copied into that pool and the pass stops after the last
+//                layer's K/V (no scores)
+int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaView& mv, const Workspace& ws, char* wsb,
+               int max_keys, int max_new_len, float* scores, hipStream_t st, const PrefillTarget* fill = nullptr) {
     const hr_model_cfg& c = m->cfg;
     const int dt = c.dtype;
     const int H = c.hidden, d = c.head_dim, F = c.ffn;
@@ -141,8 +155,10 @@ int run_layers(hr_model* m, const hr_pool* pool, const MetaView& mv, const Works
         pv.kv_dtype = dt;
         pv.esz = dtype_size(dt);
         pv.num_pages = 1;
+        if (self_prefix) pv.data = (const char*)k;     // layer index 0 of a one-layer "pool" = the new-KV page buffer
     }
     const bool mfma_attn = !m->force_generic && attn_mfma_supported(c, pv.kv_dtype, max_new_len);
+    if (self_prefix && !mfma_attn) return HR_ERR_UNSUPPORTED_SHAPE;
 
     // with the MFMA attention the new tokens' K/V are written straight into 16-slot pages (k and v regions together);
     // slots past a sequence's end are never written by any layer, so one clear per call keeps them finite
@@ -162,8 +178,15 @@ int run_layers(hr_model* m, const hr_pool* pool, const MetaView& mv, const Works
             HR_TIMED(PC_GEMM_QKV, launch_gemm_generic(dt, y, layer_w(m, l, m->pack.wqkv), f32, T, nqkv, H, false, st));
             HR_TIMED(PC_ELEMENTWISE, launch_rope_split(dt, f32, rope, q, k, v, T, c.n_q_heads, c.n_kv_heads, d, st));
         }
+        if (fill) {
+            // this layer's K/V pages are final: store them, and stop once the last layer's are in
+            char* layer_base = fill->pool->base + (size_t)l * fill->pool->cfg.num_pages * c.n_kv_heads * 2 * kPageTokens * d * 2;
+            HR_TIMED(PC_ELEMENTWISE, launch_pages_to_pool((const char*)k, layer_base, fill->src_page, fill->dst_page, fill->n_pages,
+                                                          c.n_kv_heads * 2 * kPageTokens * d * 2, st));
+            if (l + 1 == c.n_layers) return HR_OK;
+        }
         if (mfma_attn) {
-            HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, o, mv, pv, l, c.n_q_heads, max_new_len, st));
+            HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, o, mv, pv, self_prefix ? 0 : l, c.n_q_heads, max_new_len, st));
         } else {
             HR_TIMED(PC_ATTENTION, launch_attn_generic(dt, q, k, v, o, mv, pv, l, c.n_q_heads, max_keys, st));
         }
@@ -202,10 +225,22 @@ MetaView make_meta_view(const int32_t* dev_meta, const MetaLayout& ml, int64_t n
     mv.page_table = dev_meta + ml.page_table;
     mv.new_slot = dev_meta + ml.new_slot;
     mv.new_cu = dev_meta + ml.new_cu;
+    mv.out_row = dev_meta + ml.out_row;
+    mv.n_out = (int32_t)n_seq;
     mv.pt_stride = (int32_t)pt_stride;
     mv.n_seq = (int32_t)n_seq;
     mv.T = T;
     return mv;
+}
+
+// chunk length of the self-prefix passes: as many query rows per kv head as the attention kernel takes
+int full_chunk(const hr_model* m) {
+    const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
+    return g * 64 <= 512 ? 64 : 32;
+}
+
+bool chunked_ok(const hr_model* m) {
+    return !m->force_generic && m->mfma_gemm && hr::attn_mfma_supported(m->cfg, HR_BF16, full_chunk(m));
 }
 
 }  // namespace
@@ -327,7 +362,7 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     int max_keys = 0;
     for (int32_t p = 0; p < n_pairs; ++p) max_keys = std::max(max_keys, doc_lens[p] + query_lens[p]);
     hr::MetaView mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, n_pairs, T, pt_stride);
-    return run_layers(m, pool, mv, ws, wsb, max_keys, max_q, scores_dev, st);
+    return run_layers(m, pool, false, mv, ws, wsb, max_keys, max_q, scores_dev, st);
 }
 
 int hr_rerank_validate(const hr_model_cfg* cfg, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table,
@@ -343,6 +378,14 @@ int hr_rerank_validate(const hr_model_cfg* cfg, const hr_pool* pool, int32_t n_p
 
 size_t hr_rerank_full_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t total_tokens) {
     if (!m || n_pairs < 0 || total_tokens < 0) return 0;
+    if (chunked_ok(m)) {
+        // upper bounds without the lengths: every pair adds at most one partial chunk; a row of the self page table
+        // is at most as long as the longest sequence, itself at most total_tokens
+        const int ch = full_chunk(m);
+        const int64_t n_chunks = total_tokens / ch + n_pairs;
+        const int64_t stride = std::max<int64_t>(1, std::min<int64_t>(total_tokens, kGenericMaxKeys) / hr::kPageTokens);
+        return hr::make_workspace(m->cfg, n_chunks, total_tokens, stride, false, n_pairs, 0).total;
+    }
     return hr::make_workspace(m->cfg, n_pairs, total_tokens, 0, !m->mfma_gemm).total;
 }
 
@@ -365,8 +408,6 @@ int hr_rerank_score_full(hr_model* m, int32_t n_pairs, const int32_t* doc_tokens
     }
     if (T > (int64_t)1 << 30) return HR_ERR_LEN_RANGE;
     if (Td > 0 && !doc_tokens) return HR_ERR_INVALID_ARG;
-    hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, 0, !m->mfma_gemm);
-    if (workspace_bytes < ws.total) return HR_ERR_WORKSPACE_SMALL;
     // concatenated [doc ; query] token stream and its lengths
     std::vector<int32_t> toks((size_t)T), lens((size_t)n_pairs);
     {
@@ -381,16 +422,113 @@ int hr_rerank_score_full(hr_model* m, int32_t n_pairs, const int32_t* doc_tokens
         if (toks[t] < 0 || toks[t] >= m->cfg.vocab) return HR_ERR_TOKEN_RANGE;
 
     hipStream_t st = (hipStream_t)stream;
+    char* wsb = (char*)workspace_dev;
+    if (chunked_ok(m)) {
+        const int ch = full_chunk(m);
+        hr::ChunkPlan cp = hr::make_chunk_plan(n_pairs, lens.data(), ch);
+        hr::Workspace ws = hr::make_workspace(m->cfg, cp.n_chunks, T, cp.pt_stride, false, n_pairs, 0);
+        if (workspace_bytes < ws.total) return HR_ERR_WORKSPACE_SMALL;
+        hr::MetaLayout ml = hr::make_meta_layout(cp.n_chunks, T, cp.pt_stride, n_pairs, 0);
+        int rc = stage_reserve(m, ml.total);
+        if (rc != HR_OK) return rc;
+        hr::fill_meta(m->stage, ml, cp.n_chunks, cp.prefix_lens.data(), cp.new_lens.data(), toks.data(), cp.page_table.data(),
+                      cp.pt_stride, cp.out_row.data(), n_pairs);
+        HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, m->stage, ml.total * sizeof(int32_t), hipMemcpyHostToDevice, st));
+        HR_HIP(hipEventRecord(m->stage_ev, st));
+        m->stage_pending = true;
+        hr::MetaView mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, cp.n_chunks, T, cp.pt_stride);
+        mv.n_out = n_pairs;
+        return run_layers(m, nullptr, true, mv, ws, wsb, max_len, ch, scores_dev, st);
+    }
+    hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, 0, !m->mfma_gemm);
+    if (workspace_bytes < ws.total) return HR_ERR_WORKSPACE_SMALL;
     hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, 0);
     int rc = stage_reserve(m, ml.total);
     if (rc != HR_OK) return rc;
     hr::fill_meta(m->stage, ml, n_pairs, nullptr, lens.data(), toks.data(), nullptr, 0);
-    char* wsb = (char*)workspace_dev;
     HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, m->stage, ml.total * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HR_HIP(hipEventRecord(m->stage_ev, st));
     m->stage_pending = true;
     hr::MetaView mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, n_pairs, T, 0);
-    return run_layers(m, nullptr, mv, ws, wsb, max_len, max_len, scores_dev, st);
+    return run_layers(m, nullptr, false, mv, ws, wsb, max_len, max_len, scores_dev, st);
+}
+
+size_t hr_doc_prefill_workspace_bytes(const hr_model* m, int32_t n_docs, int64_t total_tokens) {
+    if (!m || n_docs < 0 || total_tokens < 0 || !chunked_ok(m)) return 0;
+    const int ch = full_chunk(m);
+    const int64_t n_chunks = total_tokens / ch + n_docs;
+    const int64_t stride = std::max<int64_t>(1, std::min<int64_t>(total_tokens, kGenericMaxKeys) / hr::kPageTokens);
+    const int64_t pages = total_tokens / hr::kPageTokens + n_docs;
+    return hr::make_workspace(m->cfg, n_chunks, total_tokens, stride, false, n_docs, 2 * pages).total;
+}
+
+int hr_doc_prefill(hr_model* m, hr_pool* pool, int32_t n_docs, const int32_t* doc_tokens, const int32_t* doc_lens,
+                   const int32_t* page_table, int32_t pt_stride, void* workspace_dev, size_t workspace_bytes, void* stream) {
+    if (!m || !pool || n_docs < 0 || pt_stride < 0) return HR_ERR_INVALID_ARG;
+    if (n_docs == 0) return HR_OK;
+    if (!doc_tokens || !doc_lens || !page_table || !workspace_dev) return HR_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace_dev % hr::kAlign != 0) return HR_ERR_INVALID_ARG;
+    const hr_model_cfg& c = m->cfg;
+    if (pool->cfg.n_layers != c.n_layers || pool->cfg.n_kv_heads != c.n_kv_heads || pool->cfg.head_dim != c.head_dim)
+        return HR_ERR_MISMATCH;
+    if (pool->cfg.kv_dtype != HR_BF16 || !chunked_ok(m)) return HR_ERR_UNSUPPORTED_SHAPE;
+    int64_t T = 0;
+    int max_len = 0;
+    std::vector<int32_t> dst;          // flat list of target pages, document after document
+    for (int32_t d = 0; d < n_docs; ++d) {
+        if (doc_lens[d] <= 0 || doc_lens[d] > kGenericMaxKeys) return HR_ERR_LEN_RANGE;
+        const int64_t np = ((int64_t)doc_lens[d] + hr::kPageTokens - 1) / hr::kPageTokens;
+        if (np > pt_stride) return HR_ERR_TABLE_SHORT;
+        int rc = hr::pool_check_write(pool, doc_lens[d], page_table + (size_t)d * pt_stride);
+        if (rc != HR_OK) return rc;
+        for (int64_t i = 0; i < np; ++i) dst.push_back(page_table[(size_t)d * pt_stride + i]);
+        max_len = std::max(max_len, doc_lens[d]);
+        T += doc_lens[d];
+    }
+    {   // the same page must not be given to two documents of this call
+        std::vector<int32_t> sorted(dst);
+        std::sort(sorted.begin(), sorted.end());
+        if (std::adjacent_find(sorted.begin(), sorted.end()) != sorted.end()) return HR_ERR_PAGE_DUP;
+    }
+    for (int64_t t = 0; t < T; ++t)
+        if (doc_tokens[t] < 0 || doc_tokens[t] >= c.vocab) return HR_ERR_TOKEN_RANGE;
+
+    const int ch = full_chunk(m);
+    hr::ChunkPlan cp = hr::make_chunk_plan(n_docs, doc_lens, ch);
+    const int64_t n_pages = (int64_t)dst.size();
+    hr::Workspace ws = hr::make_workspace(c, cp.n_chunks, T, cp.pt_stride, false, n_docs, 2 * n_pages);
+    if (workspace_bytes < ws.total) return HR_ERR_WORKSPACE_SMALL;
+    hr::MetaLayout ml = hr::make_meta_layout(cp.n_chunks, T, cp.pt_stride, n_docs, 2 * n_pages);
+    int rc = stage_reserve(m, ml.total);
+    if (rc != HR_OK) return rc;
+    hr::fill_meta(m->stage, ml, cp.n_chunks, cp.prefix_lens.data(), cp.new_lens.data(), doc_tokens, cp.page_table.data(), cp.pt_stride,
+                  cp.out_row.data(), n_docs);
+    {
+        int32_t* src = m->stage + ml.dst_table;
+        int32_t* dstp = src + n_pages;
+        int64_t i = 0;
+        for (int32_t d = 0; d < n_docs; ++d) {
+            const int64_t np = ((int64_t)doc_lens[d] + hr::kPageTokens - 1) / hr::kPageTokens;
+            for (int64_t pg = 0; pg < np; ++pg, ++i) {
+                src[i] = cp.first_page[d] + (int32_t)pg;
+                dstp[i] = dst[i];
+            }
+        }
+    }
+    hipStream_t st = (hipStream_t)stream;
+    char* wsb = (char*)workspace_dev;
+    HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, m->stage, ml.total * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HR_HIP(hipEventRecord(m->stage_ev, st));
+    m->stage_pending = true;
+    hr::MetaView mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, cp.n_chunks, T, cp.pt_stride);
+    mv.n_out = n_docs;
+    PrefillTarget pf{pool, (const int32_t*)(wsb + ws.off_meta) + ml.dst_table, (const int32_t*)(wsb + ws.off_meta) + ml.dst_table + n_pages,
+                     (int)n_pages};
+    rc = run_layers(m, nullptr, true, mv, ws, wsb, max_len, ch, nullptr, st, &pf);
+    if (rc != HR_OK) return rc;
+    for (int32_t d = 0; d < n_docs; ++d)
+        hr::pool_mark(pool, page_table + (size_t)d * pt_stride, (doc_lens[d] + hr::kPageTokens - 1) / hr::kPageTokens, hr::PAGE_USED);
+    return HR_OK;
 }
 
 int hr_profile_enable(hr_model* m, int enable) {

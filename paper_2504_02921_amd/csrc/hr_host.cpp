@@ -59,7 +59,8 @@ PackLayout make_pack_layout(const hr_model_cfg& c) {
     return p;
 }
 
-MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride) {
+MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t n_out, int64_t dst_ints) {
+    if (n_out < 0) n_out = n_seq;
     MetaLayout m;
     auto up = [](size_t e) { return (e + 63) / 64 * 64; };
     size_t o = 0;
@@ -71,17 +72,20 @@ MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride) {
     m.page_table = o;  o = up(o + (size_t)n_seq * (size_t)pt_stride);
     m.new_slot = o;    o = up(o + (size_t)T);
     m.new_cu = o;      o = up(o + (size_t)n_seq + 1);
+    m.out_row = o;     o = up(o + (size_t)n_out);
+    m.dst_table = o;   o = up(o + (size_t)dst_ints);
     m.total = o;
     return m;
 }
 
-Workspace make_workspace(const hr_model_cfg& c, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch) {
+Workspace make_workspace(const hr_model_cfg& c, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch,
+                         int64_t n_out, int64_t dst_ints) {
     Workspace w;
     size_t asz = dtype_size(c.dtype);
     size_t H = c.hidden, d = c.head_dim, F = c.ffn;
     size_t nq = (size_t)c.n_q_heads * d, nkv = (size_t)c.n_kv_heads * d;
     size_t t = (size_t)T;
-    MetaLayout ml = make_meta_layout(n_seq, T, pt_stride);
+    MetaLayout ml = make_meta_layout(n_seq, T, pt_stride, n_out, dst_ints);
     w.meta_ints = ml.total;
     size_t o = 0;
     w.off_meta = o; o = align_up(o + ml.total * sizeof(int32_t));
@@ -163,7 +167,8 @@ int score_check_args(const hr_model_cfg& mc, const hr_pool* pool, int32_t n_pair
 }
 
 void fill_meta(int32_t* meta, const MetaLayout& ml, int64_t n_seq, const int32_t* prefix_lens,
-               const int32_t* new_lens, const int32_t* tokens, const int32_t* page_table, int64_t pt_stride) {
+               const int32_t* new_lens, const int32_t* tokens, const int32_t* page_table, int64_t pt_stride,
+               const int32_t* out_rows, int64_t n_out) {
     int32_t* cu = meta + ml.cu;
     int32_t* tok_id = meta + ml.tok_id;
     int32_t* tok_pos = meta + ml.tok_pos;
@@ -188,8 +193,43 @@ void fill_meta(int32_t* meta, const MetaLayout& ml, int64_t n_seq, const int32_t
         slot0 += ((int64_t)new_lens[p] + 31) / 32 * 32;
     }
     new_cu[n_seq] = (int32_t)slot0;
+    int32_t* out_row = meta + ml.out_row;
+    if (out_rows) {
+        std::memcpy(out_row, out_rows, sizeof(int32_t) * (size_t)n_out);
+    } else {                                           // default: the last new token of every sequence
+        for (int64_t p = 0; p < n_seq; ++p) out_row[p] = cu[p + 1] - 1;
+    }
     if (page_table && pt_stride > 0)
         std::memcpy(meta + ml.page_table, page_table, sizeof(int32_t) * (size_t)n_seq * (size_t)pt_stride);
+}
+
+ChunkPlan make_chunk_plan(int64_t n_seq, const int32_t* lens, int chunk) {
+    ChunkPlan cp;
+    int64_t slot = 0, row = 0;
+    for (int64_t s = 0; s < n_seq; ++s) {
+        const int64_t n_ch = ((int64_t)lens[s] + chunk - 1) / chunk;
+        cp.pt_stride = std::max<int64_t>(cp.pt_stride, (n_ch - 1) * chunk / kPageTokens);
+        cp.n_chunks += n_ch;
+    }
+    cp.page_table.assign((size_t)cp.n_chunks * (size_t)std::max<int64_t>(cp.pt_stride, 1), -1);
+    const int64_t stride = std::max<int64_t>(cp.pt_stride, 1);
+    cp.pt_stride = stride;
+    int64_t ci = 0;
+    for (int64_t s = 0; s < n_seq; ++s) {
+        const int64_t first_page = slot / kPageTokens;
+        cp.first_page.push_back((int32_t)first_page);
+        for (int64_t off = 0; off < lens[s]; off += chunk, ++ci) {
+            const int32_t n = (int32_t)std::min<int64_t>(chunk, lens[s] - off);
+            cp.prefix_lens.push_back((int32_t)off);
+            cp.new_lens.push_back(n);
+            for (int64_t pg = 0; pg < off / kPageTokens; ++pg) cp.page_table[ci * stride + pg] = (int32_t)(first_page + pg);
+            slot += (n + 31) / 32 * 32;          // same rule as fill_meta: full chunks keep a sequence's slots contiguous
+            row += n;
+        }
+        cp.out_row.push_back((int32_t)(row - 1));
+    }
+    cp.T = row;
+    return cp;
 }
 
 }  // namespace hr

@@ -56,15 +56,18 @@ struct Workspace {
     size_t total = 0;
 };
 // full_path: sequences carry their own document tokens (no page table).
-Workspace make_workspace(const hr_model_cfg& cfg, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch);
+Workspace make_workspace(const hr_model_cfg& cfg, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch,
+                         int64_t n_out = -1, int64_t dst_ints = 0);
 
 // Metadata block layout (int32 offsets inside the block), uploaded once per call.
 // new_slot[t] / new_cu[p]: where the K/V of new token t goes when the new keys are kept as 16-token
 // pages per sequence (each sequence starts on a 32-slot boundary so that MFMA sub-tiles are whole).
 struct MetaLayout {
-    size_t cu = 0, tok_id = 0, tok_pos = 0, tok_seq = 0, prefix_len = 0, page_table = 0, new_slot = 0, new_cu = 0, total = 0;
+    size_t cu = 0, tok_id = 0, tok_pos = 0, tok_seq = 0, prefix_len = 0, page_table = 0, new_slot = 0, new_cu = 0, out_row = 0,
+           dst_table = 0, total = 0;
 };
-MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride);
+// n_out: rows whose score is read (one per pair); dst_ints: extra table for the prefill target pages
+MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t n_out = -1, int64_t dst_ints = 0);
 
 }  // namespace hr
 
@@ -84,6 +87,21 @@ int score_check_args(const hr_model_cfg& mc, const hr_pool* pool, int32_t n_pair
                      int32_t pt_stride, const int32_t* doc_lens, const int32_t* query_tokens,
                      const int32_t* query_lens, int64_t max_keys, int64_t* total_q_out);
 // Fills the metadata block for a call.  new_lens[p] tokens at positions prefix_lens[p]..; tokens flat.
+// out_rows / n_out: rows whose score is read; nullptr = the last new token of every sequence (then the layout must
+// have been made with n_out == n_seq)
 void fill_meta(int32_t* meta, const MetaLayout& ml, int64_t n_seq, const int32_t* prefix_lens,
-               const int32_t* new_lens, const int32_t* tokens, const int32_t* page_table, int64_t pt_stride);
+               const int32_t* new_lens, const int32_t* tokens, const int32_t* page_table, int64_t pt_stride,
+               const int32_t* out_rows = nullptr, int64_t n_out = 0);
+
+// A long sequence run as chunks of at most `chunk` tokens: chunk c of a sequence is a pseudo-sequence whose
+// prefix is the sequence's own earlier tokens, found as pages of the call's new-token K/V buffer.  Used by the
+// no-reuse pass and by the document prefill (the scoring kernels are reused unchanged).
+struct ChunkPlan {
+    std::vector<int32_t> prefix_lens, new_lens;   // per pseudo-sequence
+    std::vector<int32_t> page_table;              // [n_chunks][pt_stride] pages of the new-KV buffer
+    std::vector<int32_t> out_row;                 // per original sequence: row of its last token
+    std::vector<int32_t> first_page;              // per original sequence: first page in the new-KV buffer
+    int64_t pt_stride = 0, n_chunks = 0, T = 0;
+};
+ChunkPlan make_chunk_plan(int64_t n_seq, const int32_t* lens, int chunk);
 }  // namespace hr

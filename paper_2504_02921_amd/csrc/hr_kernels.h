@@ -26,6 +26,8 @@ struct MetaView {
     const int32_t* page_table;  // [n_seq][pt_stride]
     const int32_t* new_slot;    // [T] slot of each new token in the paged new-KV buffer
     const int32_t* new_cu;      // [n_seq + 1] first slot of each sequence (multiples of 32)
+    const int32_t* out_row;     // [n_out] token row whose score is read
+    int32_t n_out;
     int32_t pt_stride;
     int32_t n_seq;
     int64_t T;
@@ -78,5 +80,9 @@ bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len);
 hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv,
                             const PoolView& pv, int layer, int n_q, int max_q_len, hipStream_t st);
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t st);
+// copy whole pages (all kv heads) from the new-KV page buffer to pool pages of one layer:
+// pool page dst_table[i] <- new page src_first[doc(i)] + i  (16-bit pools: same arrangement on both sides)
+hipError_t launch_pages_to_pool(const char* kv_new, char* pool_layer_base, const int32_t* src_page, const int32_t* dst_page,
+                                int n_pages, int page_bytes_all_heads, hipStream_t st);
 
 }  // namespace hr

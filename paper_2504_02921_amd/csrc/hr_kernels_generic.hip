@@ -274,11 +274,11 @@ __global__ void __launch_bounds__(64) attn_generic_kernel(const T* __restrict__ 
 // ------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void __launch_bounds__(256) score_head_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                         const T* __restrict__ E, const int32_t* __restrict__ cu,
+                                                         const T* __restrict__ E, const int32_t* __restrict__ out_row,
                                                          float* __restrict__ scores, int H, float eps, int yes_id, int no_id) {
     __shared__ float red[4];
     int p = blockIdx.x;
-    const float* xr = x + (size_t)(cu[p + 1] - 1) * H;
+    const float* xr = x + (size_t)out_row[p] * H;
     float ssq = 0.f;
     for (int c = threadIdx.x; c < H; c += 256) { float v = xr[c]; ssq += v * v; }
     ssq = block_sum_256(ssq, red);
@@ -347,9 +347,24 @@ __global__ void fill_zero_kernel(uint4* dst, size_t n16) {
     for (; i < n16; i += stride) dst[i] = make_uint4(0, 0, 0, 0);
 }
 
+__global__ void pages_to_pool_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, const int32_t* __restrict__ src_page,
+                                     const int32_t* __restrict__ dst_page, int n16) {
+    const uint4* s = src + (size_t)src_page[blockIdx.x] * n16;
+    uint4* d = dst + (size_t)dst_page[blockIdx.x] * n16;
+    for (int i = threadIdx.x; i < n16; i += blockDim.x) d[i] = s[i];
+}
+
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
+hipError_t launch_pages_to_pool(const char* kv_new, char* pool_layer_base, const int32_t* src_page, const int32_t* dst_page,
+                                int n_pages, int page_bytes_all_heads, hipStream_t st) {
+    if (n_pages == 0) return hipSuccess;
+    pages_to_pool_kernel<<<dim3((unsigned)n_pages), 256, 0, st>>>((const uint4*)kv_new, (uint4*)pool_layer_base, src_page, dst_page,
+                                                                  page_bytes_all_heads / 16);
+    return hipGetLastError();
+}
+
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t st) {     // bytes: multiple of 16
     if (bytes == 0) return hipSuccess;
     const size_t n16 = bytes / 16;
@@ -437,8 +452,8 @@ hipError_t launch_attn_generic(int dtype, const void* q, const void* k_new, cons
 
 hipError_t launch_score_head(int dtype, const float* x, const float* gain, const void* E, const MetaView& mv, float* scores,
                              int H, float eps, int yes_id, int no_id, hipStream_t st) {
-    if (mv.n_seq == 0) return hipSuccess;
-    HR_DISPATCH_EMB(dtype, score_head_kernel<AT><<<dim3((unsigned)mv.n_seq), 256, 0, st>>>(x, gain, (const AT*)E, mv.cu, scores, H,
+    if (mv.n_out == 0) return hipSuccess;
+    HR_DISPATCH_EMB(dtype, score_head_kernel<AT><<<dim3((unsigned)mv.n_out), 256, 0, st>>>(x, gain, (const AT*)E, mv.out_row, scores, H,
                                                                                         eps, yes_id, no_id));
     return hipGetLastError();
 }

@@ -1,0 +1,66 @@
+// Host-only logic of the library (layouts, chunk plan, metadata builder, validation) run on exact-size buffers
+// under AddressSanitizer / UBSan.  Built and run by tests/test_host_asan.py; no GPU involved.
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "hr_internal.h"
+
+#define CHECK(c) do { if (!(c)) { std::fprintf(stderr, "check failed: %s (line %d)\n", #c, __LINE__); return 1; } } while (0)
+
+int main() {
+    // chunk plan of mixed lengths, metadata written into a buffer of exactly the computed size
+    std::vector<int32_t> lens = {270, 4, 64, 65, 128, 2112, 1};
+    for (int chunk : {32, 64}) {
+        hr::ChunkPlan cp = hr::make_chunk_plan((int64_t)lens.size(), lens.data(), chunk);
+        hr::MetaLayout ml = hr::make_meta_layout(cp.n_chunks, cp.T, cp.pt_stride, (int64_t)lens.size(), 10);
+        std::vector<int32_t> meta(ml.total, -7), toks(cp.T, 1);
+        hr::fill_meta(meta.data(), ml, cp.n_chunks, cp.prefix_lens.data(), cp.new_lens.data(), toks.data(), cp.page_table.data(),
+                      cp.pt_stride, cp.out_row.data(), (int64_t)lens.size());
+        int64_t total = 0;
+        for (int32_t l : lens) total += l;
+        CHECK(cp.T == total);
+        CHECK(meta[ml.cu + cp.n_chunks] == total);
+        // every chunk starts on a 32-slot boundary and a sequence's pages are contiguous
+        int64_t ci = 0;
+        for (size_t s = 0; s < lens.size(); ++s) {
+            for (int64_t off = 0; off < lens[s]; off += chunk, ++ci) {
+                CHECK(meta[ml.new_cu + ci] % 32 == 0);
+                CHECK(meta[ml.new_cu + ci] == cp.first_page[s] * 16 + off);
+                CHECK(meta[ml.prefix_len + ci] == off);
+                for (int64_t pg = 0; pg < off / 16; ++pg) CHECK(meta[ml.page_table + ci * cp.pt_stride + pg] == cp.first_page[s] + pg);
+            }
+            CHECK(meta[ml.out_row + s] == meta[ml.cu + ci] - 1);
+        }
+    }
+    // scoring layout: positions continue after the document, slots are 32-aligned per pair
+    std::vector<int32_t> dl = {100, 0, 17}, ql = {5, 1, 33}, pt(3 * 7, 3), tk(39, 2);
+    hr::MetaLayout m2 = hr::make_meta_layout(3, 39, 7);
+    std::vector<int32_t> meta2(m2.total);
+    hr::fill_meta(meta2.data(), m2, 3, dl.data(), ql.data(), tk.data(), pt.data(), 7);
+    CHECK(meta2[m2.tok_pos + 0] == 100 && meta2[m2.tok_pos + 4] == 104 && meta2[m2.tok_pos + 5] == 0 && meta2[m2.tok_pos + 6] == 17);
+    CHECK(meta2[m2.new_cu + 0] == 0 && meta2[m2.new_cu + 1] == 32 && meta2[m2.new_cu + 2] == 64 && meta2[m2.new_cu + 3] == 128);
+    CHECK(meta2[m2.out_row + 0] == 4 && meta2[m2.out_row + 1] == 5 && meta2[m2.out_row + 2] == 38);
+    // pool bookkeeping and validation paths
+    hr_pool_cfg pc{2, 2, 64, 16, 8, HR_BF16};
+    hr_pool* pool = nullptr;
+    CHECK(hr_kv_pool_create(&pc, (void*)0x1000, hr_kv_pool_bytes(&pc), &pool) == HR_OK);
+    int32_t ids[3] = {1, 5, 1};
+    CHECK(hr::pool_check_write(pool, 40, ids) == HR_ERR_PAGE_DUP);
+    ids[2] = 7;
+    CHECK(hr::pool_check_write(pool, 40, ids) == HR_OK);
+    hr::pool_mark(pool, ids, 3, hr::PAGE_USED);
+    CHECK(hr_kv_pool_free_pages(pool) == 5);
+    hr_model_cfg mc{2, 128, 4, 2, 64, 256, 100, 1, 2, HR_BF16, 10000.f, 1e-6f};
+    int32_t table[2 * 3] = {1, 5, 7, 1, 5, -1};
+    int32_t dls[2] = {40, 32}, qls[2] = {3, 2}, qt[5] = {1, 2, 3, 4, 99};
+    int64_t T = 0;
+    CHECK(hr::score_check_args(mc, pool, 2, table, 3, dls, qt, qls, 1 << 20, &T) == HR_OK && T == 5);
+    qt[4] = 100;
+    CHECK(hr::score_check_args(mc, pool, 2, table, 3, dls, qt, qls, 1 << 20, &T) == HR_ERR_TOKEN_RANGE);
+    dls[1] = 48;
+    CHECK(hr::score_check_args(mc, pool, 2, table, 3, dls, qt, qls, 1 << 20, &T) == HR_ERR_TABLE_SHORT);
+    hr_kv_pool_destroy(pool);
+    std::printf("host logic clean under sanitizers\n");
+    return 0;
+}

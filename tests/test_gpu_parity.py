@@ -216,3 +216,37 @@ def test_device_side_error_paths():
     case.fill_from_prefill([0])
     assert np.array_equal(case.gpu_scores(), before)
     case.close()
+
+
+@pytest.mark.parametrize("d,n_q,n_kv", [(64, 4, 2), (128, 8, 2), (64, 14, 2)])
+def test_chunked_no_reuse_pass_and_device_prefill(d, n_q, n_kv):
+    """Long [doc ; query] sequences through the MFMA kernels in 64-token chunks (the sequence's own earlier pages
+    are the prefix), and the same machinery used as the document prefill that fills the pool on the device."""
+    import torch
+    model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=n_q, n_kv=n_kv, d=d, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("chunked", model, 3, 3, (1, 230), (1, 40), "bf16", seed=d + n_q)
+    w = wlmod.SeededWeights(model, seed=16, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(cfg, spare_pages=3)
+    case = H.Case(wl, w)
+    docs = [wl.doc_tokens(dd) for dd in wl.pair_doc]
+    qs = [wl.query_tokens_per_query[q] for q in wl.pair_query]
+    want = orr.score_full(w, model, docs, qs)
+    assert np.abs(want).max() > 1e-2
+    # (a) no-reuse pass
+    got_full = case.model.score_full(docs, qs)
+    torch.cuda.synchronize()
+    H.assert_scores_close(got_full.cpu().numpy().astype(np.float64), want, H.TOL["bf16"], "chunked no-reuse pass")
+    # (b) device prefill into the pool, then the ordinary scoring pass on top of it
+    uniq = sorted(set(int(x) for x in wl.pair_doc))
+    free_before = case.pool.free_pages
+    case.model.doc_prefill(case.pool, [wl.doc_tokens(u) for u in uniq], [wl.pool_doc_pages[u] for u in uniq])
+    torch.cuda.synchronize()
+    assert case.pool.free_pages == free_before - sum(len(wl.pool_doc_pages[u]) for u in uniq)
+    got_cached = case.gpu_scores()
+    H.assert_scores_close(got_cached, want, H.TOL["bf16"], "device prefill + scoring pass")
+    # writing into pages that now hold documents is refused
+    from paper_2504_02921_amd import binding as hb
+    with pytest.raises(hb.HrError) as e:
+        case.model.doc_prefill(case.pool, [wl.doc_tokens(uniq[0])], [wl.pool_doc_pages[uniq[0]]])
+    assert e.value.status == hb.HR_ERR_PAGE_IN_USE
+    case.close()
