@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reuse-pairs", type=int, default=256, help="pairs for the no-reuse reference (0 = skip)")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events during the timed steps")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run a plain device copy of this many MiB (known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build measures ONE GPU only (pairs shard over GPUs with no collective; see DESIGN.md). "
@@ -75,6 +77,13 @@ def main():
         f"gemm={model.gemm_path()} attention={model.attention_path(pool)}")
 
     scores = torch.empty(wl.n_pairs, dtype=torch.float32, device=dev)
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.bitwise_not(src, out=dst)     # a plain elementwise kernel with a name of its own: reads N, writes N
+        torch.cuda.synchronize()
+        del src, dst
 
     def step():
         model.score(pool, wl.page_table, wl.doc_lens, wl.query_tokens, wl.query_lens, out=scores)
@@ -93,6 +102,14 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     pairs_per_s = wl.n_pairs / (dt / args.steps)
     assert bool(torch.isfinite(scores).all()), "non-finite scores"
+
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (recorded summary, see profiles/)
+    traffic = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            traffic = json.load(f).get(cfg.name, {})
+    except (OSError, ValueError):
+        pass
 
     # ---- rooflines from the per-kernel events ------------------------------------------------
     T = wl.total_q_tokens
@@ -119,7 +136,8 @@ def main():
             if model.gemm_path() == "mfma":
                 ach = flop_per_launch[name] / avg_s / 1e12
                 return {"kernel": name, "bound": "mfma", "achieved": round(ach, 2), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None, "avg_launch_ms": round(avg_s * 1e3, 4)}
+                        "frac": round(ach / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic.get(name), "avg_launch_ms": round(avg_s * 1e3, 4),
+                        "algorithmic_flop_per_launch": flop_per_launch[name]}
             ach = flop_per_launch[name] / avg_s / 1e12
             return {"kernel": name, "bound": "alu", "achieved": round(ach, 3), "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / FP32_VECTOR_PEAK_TFLOPS, 4), "traffic": None, "avg_launch_ms": round(avg_s * 1e3, 4)}
@@ -128,7 +146,7 @@ def main():
             avg_s = prof["attention"]["ms"] / prof["attention"]["launches"] * 1e-3
             ach = kv_bytes_per_launch / avg_s / 1e9
             return {"kernel": "attention", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "avg_launch_ms": round(avg_s * 1e3, 4),
+                    "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic.get("attention"), "avg_launch_ms": round(avg_s * 1e3, 4),
                     "algorithmic_bytes_per_launch": int(kv_bytes_per_launch)}
 
         roof_attn = attn_roof()
