@@ -239,71 +239,93 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
                 }
         }
     } else {   // EPI_QKV_ROPE
-        constexpr int hb = HB;                                  // 32-wide blocks per half head
+        constexpr int hb = HB;                                  // 32-wide blocks per half head: head_dim = 64 * HB
         static_assert(EPI != EPI_QKV_ROPE || NI % (2 * HB) == 0, "a wave must hold whole heads");
-        const int d = a.d, half = d / 2;
+        constexpr int d = 64 * HB, half = d / 2;
         const int nq = a.n_q * d, nkv = a.n_kv * d;
+        // The (cos, sin) rows of this tile's tokens go to LDS first (the stages are free: nobody reads them behind
+        // the last barrier of the main loop).  A lane owns one token row and would otherwise fetch its 16-byte
+        // pieces of the table from 32 different cache lines per load instruction.  Chunks of 16 bytes are
+        // XOR-swizzled by the row so that the 16 rows read together hit 16 different bank groups.
+        constexpr int CPR = d / 4;                               // chunks per table row (d / 2 pairs of 8 bytes)
+        static_assert(EPI != EPI_QKV_ROPE || (BM * CPR) % NT == 0, "table loader shape");
+        static_assert(EPI != EPI_QKV_ROPE || BM * CPR * 16 <= 2 * (BM + BN) * BK * (int)sizeof(half_t), "table fits the stages");
+        {
+            const char* rope_bytes = (const char*)a.rope;
+#pragma unroll
+            for (int base = 0; base < BM * CPR; base += NT) {
+                const int L = base + tid;
+                const int row = L / CPR, pc = L % CPR;
+                int64_t gr = m0 + row;
+                gr = gr < a.M ? gr : a.M - 1;
+                const char* g = rope_bytes + (gr * half) * (int64_t)sizeof(float2) + ((pc ^ (row & 15)) << 4);
+                __builtin_amdgcn_global_load_lds((gbl_ptr_t)g, (lds_ptr_t)(smem + (size_t)(base + wave * 64) * 16), 16, 0, 0);
+            }
+        }
         int slot_i[MI];
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             const int64_t row = row_base + i * 32;
             slot_i[i] = (a.kv_pages && row < a.M) ? a.new_slot[row] : 0;
         }
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        // store one quad (4 consecutive columns of one row), already rotated and rounded
+        auto store_quad = [&](int i, int64_t row, int col, halfx4 w) {
+            if (col < nq) {
+                *(halfx4*)((half_t*)a.out0 + row * nq + col) = w;
+                return;
+            }
+            const bool is_v = col >= nq + nkv;
+            const int c_all = col - nq - (is_v ? nkv : 0);
+            if (!a.kv_pages) {
+                *(halfx4*)((half_t*)(is_v ? a.out2 : a.out1) + row * nkv + c_all) = w;
+                return;
+            }
+            // 16-slot pages in the pool arrangement: [page][kv head][K block | V block]
+            const int kv_head = c_all / d, kv_c = c_all - kv_head * d;
+            const int slot = slot_i[i];
+            half_t* blk0 = (half_t*)a.kv_pages + ((size_t)(slot >> 4) * a.n_kv + kv_head) * (2 * kPageTokens * d);
+            const int t = slot & 15;
+            if (!is_v) *(halfx4*)(blk0 + k_elem(t, kv_c, d, 2)) = w;
+            else {
+                half_t* vb = blk0 + kPageTokens * d;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) vb[v_elem(t, kv_c + e, d)] = w[e];
+            }
+        };
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             const int64_t row = row_base + i * 32;
             if (row >= a.M) continue;
-            const float2* rp = a.rope + row * half;
+            const int lrow = wm * TM + i * 32 + frow;              // row inside the tile
+            const char* trow = smem + (size_t)lrow * (CPR * 16);
 #pragma unroll
-            for (int j = 0; j < NI; ++j) {
-                const int blk = j % (2 * hb);                 // block index inside its head
-                const bool lo = blk < hb;
-                const int jp = lo ? j + hb : j - hb;           // partner block (same lane, same register)
+            for (int hbi = 0; hbi < hb; ++hbi)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const int col = col_base + j * 32 + 8 * r4;
-                    if (col >= a.N) continue;
-                    half_t* dst = nullptr;
-                    bool rot = true;
-                    int kv_head = -1, kv_c = 0;           // paged K/V: kv head and channel of the quad
-                    bool is_v = false;
-                    if (col < nq) dst = (half_t*)a.out0 + row * nq + col;
-                    else if (col < nq + nkv) {
-                        if (a.kv_pages) { kv_head = (col - nq) / d; kv_c = (col - nq) - kv_head * d; }
-                        else dst = (half_t*)a.out1 + row * nkv + (col - nq);
-                    } else {
-                        rot = false;
-                        if (a.kv_pages) { kv_head = (col - nq - nkv) / d; kv_c = (col - nq - nkv) - kv_head * d; is_v = true; }
-                        else dst = (half_t*)a.out2 + row * nkv + (col - nq - nkv);
-                    }
-                    const int jj = (lo ? blk : blk - hb) * 32 + 8 * r4 + 4 * fh;   // rotary index of the quad
-                    halfx4 w;
+                    // rotary indices hbi * 32 + 8 * r4 + 4 * fh + {0..3}: two chunks of two (cos, sin) pairs
+                    const int c0 = hbi * 16 + 4 * r4 + 2 * fh;
+                    const float4 cs01 = *(const float4*)(trow + ((c0 ^ (lrow & 15)) << 4));
+                    const float4 cs23 = *(const float4*)(trow + (((c0 + 1) ^ (lrow & 15)) << 4));
+                    const float cs_c[4] = {cs01.x, cs01.z, cs23.x, cs23.z}, cs_s[4] = {cs01.y, cs01.w, cs23.y, cs23.w};
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        float val = acc[i][j][r4 * 4 + e];
-                        if (rot) {
-                            const float2 cs = rp[jj + e];
-                            const float other = acc[i][jp][r4 * 4 + e];
-                            val = lo ? val * cs.x - other * cs.y : val * cs.x + other * cs.y;
-                        }
-                        w[e] = from_float<half_t>(val);
-                    }
-                    if (kv_head >= 0) {
-                        // 16-slot pages in the pool arrangement: [page][kv head][K block | V block]
-                        const int slot = slot_i[i];
-                        half_t* blk0 = (half_t*)a.kv_pages + ((size_t)(slot >> 4) * a.n_kv + kv_head) * (2 * kPageTokens * d);
-                        const int t = slot & 15;
-                        if (!is_v) *(halfx4*)(blk0 + k_elem(t, kv_c, d, 2)) = w;
-                        else {
-                            half_t* vb = blk0 + kPageTokens * d;
+                    for (int hd = 0; hd < NI / (2 * hb); ++hd) {
+                        const int jl = hd * 2 * hb + hbi, jh = jl + hb;       // low / high half of the head: same lane, same register
+                        const int col_l = col_base + jl * 32 + 8 * r4, col_h = col_base + jh * 32 + 8 * r4;
+                        if (col_l >= a.N) continue;                             // N is a multiple of the head size
+                        const bool rot = col_l < nq + nkv;                      // q and k rotate, v does not
+                        halfx4 wl, wh;
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) vb[v_elem(t, kv_c + e, d)] = w[e];
+                        for (int e = 0; e < 4; ++e) {
+                            const float lo = acc[i][jl][r4 * 4 + e], hi = acc[i][jh][r4 * 4 + e];
+                            wl[e] = from_float<half_t>(rot ? lo * cs_c[e] - hi * cs_s[e] : lo);
+                            wh[e] = from_float<half_t>(rot ? hi * cs_c[e] + lo * cs_s[e] : hi);
                         }
-                        continue;
+                        store_quad(i, row, col_l, wl);
+                        store_quad(i, row, col_h, wh);
                     }
-                    *(halfx4*)dst = w;
                 }
-            }
         }
     }
     HR_STAMP();
