@@ -194,24 +194,82 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
     const int64_t row_base = m0 + wm * TM + frow;
     const int col_base = n0 + wn * TN + 4 * fh;
     if constexpr (EPI == EPI_RESID_ADD) {
+        // x += C through LDS.  In the accumulator layout a lane holds 16 bytes of one row, so a direct update touches
+        // 32 rows per instruction; staged as an fp32 [BM][CW] tile (16-byte chunks XOR-swizzled by the row against
+        // bank conflicts of the column-wise writes) the update reads and writes whole 512-byte row segments.  The
+        // stages hold BM x CW floats, so the tile goes in PASSES column slabs; each wave tile lies in one slab.
+        constexpr int LDS_BYTES = 2 * (BM + BN) * BK * (int)sizeof(half_t);
+        constexpr int PASSES = (BM * BN * 4 + LDS_BYTES - 1) / LDS_BYTES;
+        constexpr int CW = BN / PASSES;                 // slab width in columns
+        constexpr int CPRW = CW / 4;                    // 16-byte chunks per slab row
+        constexpr int ITER = BM * CPRW / NT;
+        static_assert(EPI != EPI_RESID_ADD || (CW % TN == 0 && CPRW % 16 == 0 && (BM * CPRW) % (4 * NT) == 0 && BM * CW * 4 <= LDS_BYTES),
+                      "slab shape");
+        float* stage = (float*)smem;
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            const int64_t row = row_base + i * 32;
-            if (row >= a.M) continue;
-            float* xr = a.x + row * a.N;
+        for (int p = 0; p < PASSES; ++p) {
+            // x in four groups of G chunks per lane (registers): the first is requested before the stage is written, so
+            // its latency hides behind the write and the barrier.  Every address is clamped into the matrix, only
+            // valid chunks are written back.
+            constexpr int G = ITER / 4;
+            float4 xv[G];
+            auto load_x = [&](int first) {
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int col = col_base + j * 32 + 8 * r4;
-                    if (col >= a.N) continue;                     // N is a multiple of 8: whole quads
-                    float4 v = *(float4*)(xr + col);
-                    v.x += acc[i][j][r4 * 4 + 0];
-                    v.y += acc[i][j][r4 * 4 + 1];
-                    v.z += acc[i][j][r4 * 4 + 2];
-                    v.w += acc[i][j][r4 * 4 + 3];
-                    *(float4*)(xr + col) = v;
+                for (int it = 0; it < G; ++it) {
+                    const int L = (first + it) * NT + tid;
+                    const int row = L / CPRW, pch = L % CPRW;
+                    int col = n0 + p * CW + ((pch ^ (row & 15)) << 2);
+                    int64_t grow = m0 + row;
+                    grow = grow < a.M ? grow : a.M - 1;
+                    col = col < a.N ? col : a.N - 4;
+                    xv[it] = *(const float4*)(a.x + grow * a.N + col);
                 }
+            };
+            auto update_x = [&](int first) {
+#pragma unroll
+                for (int it = 0; it < G; ++it) {
+                    const int L = (first + it) * NT + tid;
+                    const int row = L / CPRW, pch = L % CPRW;
+                    const int col = n0 + p * CW + ((pch ^ (row & 15)) << 2);
+                    const int64_t grow = m0 + row;
+                    if (grow >= a.M || col >= a.N) continue;        // N is a multiple of 8: whole chunks
+                    const float4 c = *(const float4*)(stage + row * CW + (pch << 2));
+                    float4 v = xv[it];
+                    v.x += c.x;
+                    v.y += c.y;
+                    v.z += c.z;
+                    v.w += c.w;
+                    *(float4*)(a.x + grow * a.N + col) = v;
+                }
+            };
+            load_x(0);
+            if (p > 0) __syncthreads();                 // the previous slab has been read
+            if ((wn * TN) / CW == p) {
+                const int c_off = wn * TN - p * CW + 4 * fh;
+#pragma unroll
+                for (int i = 0; i < MI; ++i) {
+                    const int lr = wm * TM + i * 32 + frow;
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const int ch = (c_off + j * 32 + 8 * r4) >> 2;
+                            float4 v;
+                            v.x = acc[i][j][r4 * 4 + 0];
+                            v.y = acc[i][j][r4 * 4 + 1];
+                            v.z = acc[i][j][r4 * 4 + 2];
+                            v.w = acc[i][j][r4 * 4 + 3];
+                            *(float4*)(stage + lr * CW + ((ch ^ (lr & 15)) << 2)) = v;
+                        }
+                }
+            }
+            __syncthreads();
+            update_x(0);
+#pragma unroll
+            for (int g = 1; g < 4; ++g) {
+                load_x(g * G);
+                update_x(g * G);
+            }
         }
     } else if constexpr (EPI == EPI_SWIGLU) {
         static_assert(EPI != EPI_SWIGLU || NI % 2 == 0, "gate/up block pairs");
@@ -404,18 +462,12 @@ hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st)
     switch (epi) {
         case EPI_QKV_ROPE:
             if (!wide_head) {
-                if (var == 1) return launch_tile<EPI_QKV_ROPE, 256, 256, 2, 2, 1>(a, st);
-                if (var == 3) return launch_tile<EPI_QKV_ROPE, 256, 128, 4, 2, 1>(a, st);
                 return big ? launch_tile<EPI_QKV_ROPE, 256, 256, 2, 4, 1>(a, st) : launch_tile<EPI_QKV_ROPE, 128, 128, 2, 2, 1>(a, st);
             }
             return big ? launch_tile<EPI_QKV_ROPE, 256, 256, 4, 2, 2>(a, st) : launch_tile<EPI_QKV_ROPE, 128, 256, 2, 2, 2>(a, st);
         case EPI_RESID_ADD:
-            if (var == 1) return launch_tile<EPI_RESID_ADD, 256, 256, 2, 2, 1>(a, st);
-            if (var == 3) return launch_tile<EPI_RESID_ADD, 256, 128, 4, 2, 1>(a, st);
             return big ? launch_tile<EPI_RESID_ADD, 256, 256, 2, 4, 1>(a, st) : launch_tile<EPI_RESID_ADD, 128, 128, 2, 2, 1>(a, st);
         case EPI_SWIGLU:
-            if (var == 1) return launch_tile<EPI_SWIGLU, 256, 256, 2, 2, 1>(a, st);
-            if (var == 3) return launch_tile<EPI_SWIGLU, 256, 128, 4, 2, 1>(a, st);
             return big ? launch_tile<EPI_SWIGLU, 256, 256, 2, 4, 1>(a, st) : launch_tile<EPI_SWIGLU, 128, 128, 2, 2, 1>(a, st);
     }
     return hipErrorInvalidValue;
