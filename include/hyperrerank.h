@@ -221,6 +221,10 @@ int hr_doc_prefill(hr_model* model, hr_pool* pool, int32_t n_docs, const int32_t
  * recorded events, returns per class the summed duration in ms and the number of launches
  * (arrays of hr_profile_count entries, host) and clears the record. */
 int hr_profile_enable(hr_model* model, int enable);
+/* Restrict the timing to the classes whose bit (1 << class index) is set; the default is all classes.  Two
+ * event records cost a few microseconds of stream time per launch, which adds up over ~170 launches per call,
+ * so a benchmark times only the classes it reports while it measures the whole call. */
+int hr_profile_select(hr_model* model, uint32_t class_mask);
 int hr_profile_count(void);
 const char* hr_profile_name(int idx);
 int hr_profile_read(hr_model* model, double* ms_out, int64_t* launches_out);

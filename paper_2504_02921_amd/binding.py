@@ -58,7 +58,7 @@ EXPORTS = [
     "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_free", "hr_weights_pack_bytes", "hr_weights_load",
     "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
-    "hr_profile_enable", "hr_profile_count", "hr_profile_name", "hr_profile_read",
+    "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
 ]
 
 
@@ -101,6 +101,7 @@ def _load() -> C.CDLL:
         "hr_attention_path": (C.c_char_p, [C.c_void_p, C.c_void_p]),
         "hr_gemm_path": (C.c_char_p, [C.c_void_p]),
         "hr_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
+        "hr_profile_select": (C.c_int, [C.c_void_p, C.c_uint32]),
         "hr_profile_count": (C.c_int, []),
         "hr_profile_name": (C.c_char_p, [C.c_int]),
         "hr_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
@@ -277,6 +278,13 @@ class Model:
 
     def profile_enable(self, on: bool) -> None:
         check(lib.hr_profile_enable(self.handle, 1 if on else 0), "hr_profile_enable")
+
+    def profile_select(self, names=None) -> None:
+        """Time only the named kernel classes (None: all)."""
+        n = lib.hr_profile_count()
+        all_names = [lib.hr_profile_name(i).decode() for i in range(n)]
+        mask = 0xFFFFFFFF if names is None else sum(1 << all_names.index(x) for x in names)
+        check(lib.hr_profile_select(self.handle, mask), "hr_profile_select")
 
     def profile_read(self) -> Dict[str, Dict[str, float]]:
         n = lib.hr_profile_count()

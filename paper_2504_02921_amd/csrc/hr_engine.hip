@@ -23,6 +23,7 @@ struct hr_model {
     bool force_generic = false;
     // optional per-kernel timing with HIP events (benchmarks)
     bool prof_on = false;
+    uint32_t prof_mask = 0xFFFFFFFFu;     // kernel classes that are timed while prof_on
     std::vector<hipEvent_t> prof_events;          // pool, two per timed launch
     std::vector<int> prof_class;                  // class of each recorded launch
     size_t prof_used = 0;                         // events in use
@@ -86,7 +87,7 @@ struct ProfScope {
     hr_model* m;
     hipStream_t st;
     bool on;
-    ProfScope(hr_model* m_, int cls, hipStream_t st_) : m(m_), st(st_), on(m_->prof_on) {
+    ProfScope(hr_model* m_, int cls, hipStream_t st_) : m(m_), st(st_), on(m_->prof_on && ((m_->prof_mask >> cls) & 1u)) {
         if (!on) return;
         if (m->prof_used + 2 > m->prof_events.size()) {
             for (int i = 0; i < 64; ++i) {
@@ -534,6 +535,12 @@ int hr_doc_prefill(hr_model* m, hr_pool* pool, int32_t n_docs, const int32_t* do
 int hr_profile_enable(hr_model* m, int enable) {
     if (!m) return HR_ERR_INVALID_ARG;
     m->prof_on = enable != 0;
+    return HR_OK;
+}
+
+int hr_profile_select(hr_model* m, uint32_t class_mask) {
+    if (!m) return HR_ERR_INVALID_ARG;
+    m->prof_mask = class_mask;
     return HR_OK;
 }
 
