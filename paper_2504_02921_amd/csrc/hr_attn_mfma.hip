@@ -41,10 +41,13 @@ long long* g_attn_trace = nullptr;
 
 namespace {
 
-constexpr int kStageBytes = 32768;
+// LDS stage: 32 KiB of half pages; an fp8 pool streams the same number of keys per stage in 16 KiB and spends the
+// other 32 KiB on the expanded copy of the current stage, so both kinds fit two workgroups per CU.
+constexpr int kStageBytesHalf = 32768;
+constexpr int stage_bytes(bool fp8) { return fp8 ? kStageBytesHalf / 2 : kStageBytesHalf; }
 constexpr int kMaxRowsPerWg = 512;
 
-template <int HD, bool FP8>
+template <int HD, bool FP8, int kStageBytes>
 struct Geo {
     static constexpr int ESZ = FP8 ? 1 : 2;
     static constexpr int BLOCK_BYTES = kPageTokens * HD * ESZ;   // one K (or V) block
@@ -53,17 +56,33 @@ struct Geo {
     static constexpr int TK = kPageTokens * PPS;                 // keys per stage
 };
 
-// 8 consecutive fp8 codes (one 64-bit LDS word) -> 8 halves.  v_cvt_scalef32_pk_f16_fp8 multiplies by the power of
-// two in `scale` only (its mantissa is ignored - measured), so the result is exact: every E4M3 value times a power of
-// two is a half (down to 2^-24).
-__device__ __forceinline__ halfx8 fp8x8_to_half(uint2 w, float scale = 1.0f) {
-    halfx2 a = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.x, scale, false);
-    halfx2 b = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.x, scale, true);
-    halfx2 c = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.y, scale, false);
-    halfx2 d = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w.y, scale, true);
+// 8 consecutive fp8 codes (one 64-bit LDS word) -> 8 halves, times a power of two.
+// An E4M3 code s.eeee.mmm placed at bits 15, 13..7 of a half (sign kept, exponent and mantissa fields shifted down
+// by one) reads as (-1)^s 2^(e-15) (1 + m/8), or (-1)^s 2^-14 (m/8) when e = 0: in both cases the E4M3 value
+// (bias 7, subnormals m/8 * 2^-6) divided by 2^8.  So the conversion is a byte shuffle, two masks, a shift and one
+// packed half multiplication by 2^8 * 2^k, exact while the product is a half.  (The hardware's scaled conversion
+// instruction gives the same values but measured ~88 cycles per wavefront instruction, against 4 for these.)
+// The two NaN codes (0x7f, 0xff) read as +-480; a pool never holds them.
+__device__ __forceinline__ halfx8 fp8x8_to_half(uint2 w, halfx2 pow2) {
+    auto pair = [&](unsigned x, unsigned sel) {
+        const unsigned t = __builtin_amdgcn_perm(x, 0u, sel);                    // code bytes to the high byte of each 16-bit half
+        const unsigned h = (t & 0x80008000u) | ((t & 0x7F007F00u) >> 1);
+        halfx2 v;
+        __builtin_memcpy(&v, &h, 4);
+        return v * pow2;
+    };
+    const halfx2 a = pair(w.x, 0x050c040cu), b = pair(w.x, 0x070c060cu), c = pair(w.y, 0x050c040cu), d = pair(w.y, 0x070c060cu);
     halfx8 r;
     r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1]; r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
     return r;
+}
+
+// 2^8 times the power of two of a positive scale, as a pair of halves (clamped to the normal range of half)
+__device__ __forceinline__ halfx2 fp8_expand_factor(float scale) {
+    int e = (int)((__float_as_uint(scale) >> 23) & 0xFFu) - 127 + 8;
+    e = e < -14 ? -14 : (e > 15 ? 15 : e);
+    const _Float16 f = (_Float16)__uint_as_float((unsigned)(e + 127) << 23);
+    return halfx2{f, f};
 }
 
 // What a workgroup needs to know about one work item = (pair, kv head)
@@ -76,21 +95,36 @@ struct ItemCtx {
 
 template <int HD, int NW, int R, bool FP8>
 __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((HD == 64 && R == 1 && NW == 8) ? 4 : (HD * R <= 128 ? 2 : 1), 8))) attn_mfma_kernel(const half_t* __restrict__ q, const char* __restrict__ kv_new,
-                                                           half_t* __restrict__ o, MetaView mv, PoolView pv, int layer, int n_q) {
-    using G = Geo<HD, FP8>;
-    using GN = Geo<HD, false>;                       // the pair's own keys are always half
+                                                           half_t* __restrict__ o, MetaView mv, PoolView pv, int layer, int n_q,
+                                                           const int32_t* __restrict__ m_cu, const int32_t* __restrict__ m_prefix,
+                                                           const int32_t* __restrict__ m_pt, const int32_t* __restrict__ m_new_cu,
+                                                           const float* __restrict__ p_scales) {
+    // The metadata arrays come as separate read-only, non-aliased parameters so that the per-item lookups (uniform
+    // over the workgroup) compile to scalar loads: a vector load that is used right away makes the wave wait for
+    // everything it has in flight, including the stage it requested a moment earlier, because vector memory
+    // operations complete in order.
+    constexpr int kStageBytes = stage_bytes(FP8);
+    using G = Geo<HD, FP8, kStageBytes>;
+    using GN = Geo<HD, false, kStageBytes>;          // the pair's own keys are always half
     constexpr int NT = NW * 64;
     constexpr int NPASS = kStageBytes / (NT * 16);   // 16-byte loads per thread and stage
     constexpr int KC = HD / 16;                      // MFMA k-steps over head_dim
     constexpr int MB = HD / 32;                      // 32-channel blocks of the output
-    extern __shared__ __attribute__((aligned(16))) char smem[];      // [2][kStageBytes] + scales
+    extern __shared__ __attribute__((aligned(16))) char smem[];      // [2][kStageBytes] + scales + (fp8) expanded stage
     float* s_scale = (float*)(smem + 2 * kStageBytes);              // [2][PPS][2]  (fp8 only)
+    char* hbuf = smem + 2 * kStageBytes + 2 * G::PPS * 2 * sizeof(float);   // fp8 only: the current stage as half pages
 
 #ifdef HR_ATTN_TRACE
     long long* trace = (blockIdx.x == 100 && threadIdx.x == 0) ? g_attn_trace_dev : nullptr;
     int tp = 0;
 #define HR_ASTAMP() do { if (trace && tp < 900) trace[tp++] = __builtin_readcyclecounter(); } while (0)
+#ifdef HR_ATTN_TRACE2
+#define HR_PSTAMP() HR_ASTAMP()
 #else
+#define HR_PSTAMP() do { } while (0)
+#endif
+#else
+#define HR_PSTAMP() do { } while (0)
 #define HR_ASTAMP() do { } while (0)
 #endif
     const int n_kv = pv.n_kv;
@@ -106,16 +140,16 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
         ItemCtx c;
         c.p = item / n_kv;
         c.h = item - c.p * n_kv;
-        c.t0 = mv.cu[c.p];
-        c.qn = mv.cu[c.p + 1] - c.t0;
-        c.D = mv.prefix_len[c.p];
+        c.t0 = m_cu[c.p];
+        c.qn = m_cu[c.p + 1] - c.t0;
+        c.D = m_prefix[c.p];
         c.n_pages = (c.D + kPageTokens - 1) / kPageTokens;
         c.n_tiles = (c.n_pages + G::PPS - 1) / G::PPS;
         c.nq_pages = ((c.qn + 31) / 32) * 2;                    // whole 32-key sub-tiles
         c.n_new_tiles = (c.nq_pages + GN::PPS - 1) / GN::PPS;
-        c.pt = mv.page_table + (size_t)c.p * mv.pt_stride;
+        c.pt = m_pt + (size_t)c.p * mv.pt_stride;
         c.layer_base = pv.data + ((size_t)layer * pv.num_pages * n_kv + c.h) * G::PAGE_BYTES;
-        c.new_base = kv_new + ((size_t)(mv.new_cu[c.p] >> 4) * n_kv + c.h) * GN::PAGE_BYTES;
+        c.new_base = kv_new + ((size_t)(m_new_cu[c.p] >> 4) * n_kv + c.h) * GN::PAGE_BYTES;
         return c;
     };
 
@@ -136,12 +170,10 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             pgi = pgi < c.n_pages ? pgi : c.n_pages - 1;       // past the end: re-read the last page (finite data, masked)
             pgid[ps] = c.pt[pgi];
         }
-        if constexpr (FP8) {
-            if (tid < G::PPS * 2) {
-                int pgi = tile * G::PPS + (tid >> 1);
-                pgi = pgi < c.n_pages ? pgi : c.n_pages - 1;
-                pgid_scale = c.pt[pgi];
-            }
+        if constexpr (FP8) {      // every thread asks (threads past 2 * PPS repeat an earlier one): no branch, no copy that waits
+            int pgi = tile * G::PPS + ((tid >> 1) % G::PPS);
+            pgi = pgi < c.n_pages ? pgi : c.n_pages - 1;
+            pgid_scale = c.pt[pgi];
         }
     };
     auto dma_doc = [&](const ItemCtx& c, int buf) {
@@ -153,9 +185,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             const char* src = c.layer_base + (size_t)pgid[ps] * page_stride + within;
             __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(dst + ps * NT * 16), 16, 0, 0);
         }
-        if constexpr (FP8) {
-            if (tid < G::PPS * 2) stg_scale = pv.scales[(((size_t)layer * pv.num_pages + pgid_scale) * n_kv + c.h) * 2 + (tid & 1)];
-        }
+        if constexpr (FP8) stg_scale = p_scales[(((size_t)layer * pv.num_pages + pgid_scale) * n_kv + c.h) * 2 + (tid & 1)];
     };
     auto dma_new = [&](const ItemCtx& c, int nt, int buf) {
         char* dst = smem + buf * kStageBytes + wave_u * 1024;
@@ -204,16 +234,41 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     float m_run[R], l_run[R];
     int M = 0;             // query rows of the current work item
 
+    // fp8 pools: the stage that has just landed is expanded to half pages once, by all threads together (8 codes
+    // per step and thread), instead of by every wave for its own fragments: the conversions are the largest
+    // VALU item of the fp8 path and every wave of the workgroup needs every key.
+    auto expand_stage = [&](const char* sb, const float* sc) {
+        constexpr int UPP = G::PAGE_BYTES / 8;               // 8-byte words per fp8 page
+        constexpr int KU = G::BLOCK_BYTES / 8;               // ... of which the K block
+#pragma unroll
+        for (int u0 = 0; u0 < kStageBytes / 8; u0 += NT) {
+            const int u = u0 + tid;
+            const int page = u / UPP, w = u - page * UPP;    // whole waves stay inside one block of one page
+            const uint2 src = *(const uint2*)(sb + (size_t)u * 8);
+            char* dpage = hbuf + page * GN::PAGE_BYTES;
+            if (w < KU) {
+                const int t = w / (HD / 8), c8 = (w % (HD / 8)) ^ k_swizzle(t, HD, 1);
+                *(halfx8*)(dpage + (t * HD + ((c8 ^ k_swizzle(t, HD, 2)) << 3)) * 2) = fp8x8_to_half(src, fp8_expand_factor(1.0f));
+            } else {
+                *(halfx8*)(dpage + GN::BLOCK_BYTES + (w - KU) * 16) = fp8x8_to_half(src, fp8_expand_factor(sc[page * 2 + 1]));
+            }
+#ifdef HR_ATTN_TRACE3
+            HR_PSTAMP();
+#endif
+        }
+    };
+
     // ---- one 32-key sub-tile held in LDS (two pages) against every row block of this wave.
     // Order: K fragments -> S = K Q^T for all row blocks -> V^T fragments (K registers are dead by then, the
     // LDS latency hides under the softmax) -> softmax -> O^T += V^T P^T.
-    auto process = [&](auto kv8_tag, auto causal_tag, const char* sb, int st, int key0, int n_valid, const float* sc) {
+    // `sb` holds half pages; scaled_tag: they were expanded from fp8 codes and `sc` carries the pages' scales.
+    auto process = [&](auto scaled_tag, auto causal_tag, const char* sb, int st, int key0, int n_valid, const float* sc) {
 #ifdef HR_ATTN_SKIP_COMPUTE
         return;      // memory-structure probe: stream the pages, do no arithmetic
 #endif
-        constexpr bool KV8 = decltype(kv8_tag)::value;
+        constexpr bool KV8 = decltype(scaled_tag)::value;
         constexpr bool CAUSAL = decltype(causal_tag)::value;
-        using GG = Geo<HD, KV8>;
+        using GG = GN;
         floatx16 s[R];
         {
             // K fragments (A operand): lane = key row ln of the sub-tile, channels chunk (2 kk + hh)
@@ -223,8 +278,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) {
                 const int e = t * HD + (((2 * kk + hh) ^ k_swizzle(t, HD, GG::ESZ)) << 3);
-                if constexpr (KV8) kf[kk] = fp8x8_to_half(*(const uint2*)(kb + e));
-                else kf[kk] = *(const halfx8*)(kb + e * 2);
+                kf[kk] = *(const halfx8*)(kb + e * 2);
             }
 #pragma unroll
             for (int rb = 0; rb < R; ++rb) {
@@ -236,16 +290,15 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             }
         }
         // fp8 pages: K scale goes into the softmax exponent (fp32).  The V scale is split into its power of two,
-        // applied exactly while expanding the codes, and its mantissa in [1, 2), applied to the probabilities: folding
-        // the whole scale (~1e-2) into P would push probabilities into the subnormal range of half.
-        float cs0 = c_log2, cs1 = c_log2, vs0 = 1.f, vs1 = 1.f, vp0 = 1.f, vp1 = 1.f;
+        // applied exactly while the codes were expanded, and its mantissa in [1, 2), applied to the probabilities:
+        // folding the whole scale (~1e-2) into P would push probabilities into the subnormal range of half.
+        HR_PSTAMP();
+        float cs0 = c_log2, cs1 = c_log2, vs0 = 1.f, vs1 = 1.f;
         if constexpr (KV8) {
             cs0 *= sc[(st * 2) * 2];
             cs1 *= sc[(st * 2 + 1) * 2];
-            vp0 = sc[(st * 2) * 2 + 1];
-            vp1 = sc[(st * 2 + 1) * 2 + 1];
-            vs0 = __uint_as_float((__float_as_uint(vp0) & 0x007FFFFFu) | 0x3F800000u);
-            vs1 = __uint_as_float((__float_as_uint(vp1) & 0x007FFFFFu) | 0x3F800000u);
+            vs0 = __uint_as_float((__float_as_uint(sc[(st * 2) * 2 + 1]) & 0x007FFFFFu) | 0x3F800000u);
+            vs1 = __uint_as_float((__float_as_uint(sc[(st * 2 + 1) * 2 + 1]) & 0x007FFFFFu) | 0x3F800000u);
         }
         // V^T fragments (A operand): lane = channel mb*32 + ln, 8 keys of key group hh of page s2
         halfx8 vf[MB][2];
@@ -255,8 +308,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 const int e = (hh * HD + mb * 32 + ln) * 8;
-                if constexpr (KV8) vf[mb][s2] = fp8x8_to_half(*(const uint2*)(vb + e), s2 == 0 ? vp0 : vp1);
-                else vf[mb][s2] = *(const halfx8*)(vb + e * 2);
+                vf[mb][s2] = *(const halfx8*)(vb + e * 2);
             }
         }
 #pragma unroll
@@ -293,6 +345,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             }
             l_run[rb] = l_run[rb] * alpha + lsum;
             m_run[rb] = m_new;
+            HR_PSTAMP();
             if (__any(alpha != 1.0f)) {
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
@@ -313,6 +366,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                 oacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[mb][0], pf[0], oacc[rb][mb], 0, 0, 0);
                 oacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[mb][1], pf[1], oacc[rb][mb], 0, 0, 0);
             }
+            HR_PSTAMP();
         }
     };
 
@@ -379,6 +433,18 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
 
         for (int tile = 0; tile < cur.n_tiles; ++tile) {
             HR_ASTAMP();
+            const char* sb = smem + stage * kStageBytes;
+            const float* sc = s_scale + stage * G::PPS * 2;
+            if constexpr (FP8) {
+                // Before the next stage is requested: LDS accesses that follow a direct-to-LDS load in program order
+                // can be made to wait for it, and these would wait for a load that has just been issued.
+                HR_PSTAMP();
+                expand_stage(sb, sc);
+                HR_PSTAMP();
+                __syncthreads();
+                HR_PSTAMP();
+                sb = hbuf;
+            }
             // every wave is past its reads of the other stage (barrier at the end of the previous iteration)
             if (tile + 1 < cur.n_tiles) {
                 dma_doc(cur, stage ^ 1);
@@ -386,8 +452,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             } else {
                 dma_new(cur, 0, stage ^ 1);
             }
-            const char* sb = smem + stage * kStageBytes;
-            const float* sc = s_scale + stage * G::PPS * 2;
 #pragma unroll 1
             for (int st = 0; st < G::TK / 32; ++st) {
                 const int key0 = tile * G::TK + st * 32;
@@ -464,7 +528,8 @@ int attn_wgs_override() {
 template <int HD, int NW, int R, bool FP8>
 hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const MetaView& mv, const PoolView& pv, int layer, int n_q,
                       hipStream_t st) {
-    const size_t lds = 2 * kStageBytes + 2 * Geo<HD, FP8>::PPS * 2 * sizeof(float);
+    constexpr int SB = stage_bytes(FP8);
+    const size_t lds = 2 * SB + 2 * Geo<HD, FP8, SB>::PPS * 2 * sizeof(float) + (FP8 ? 2 * SB : 0);
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<HD, NW, R, FP8>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -488,7 +553,8 @@ hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const Meta
     const int n_items = mv.n_seq * pv.n_kv;
     const int env_wgs = attn_wgs_override();
     const int grid = std::min(n_items, env_wgs > 0 ? env_wgs : max_wgs);
-    attn_mfma_kernel<HD, NW, R, FP8><<<dim3((unsigned)grid), NW * 64, lds, st>>>(q, kv_new, o, mv, pv, layer, n_q);
+    attn_mfma_kernel<HD, NW, R, FP8><<<dim3((unsigned)grid), NW * 64, lds, st>>>(q, kv_new, o, mv, pv, layer, n_q, mv.cu, mv.prefix_len, mv.page_table,
+                                                                             mv.new_cu, pv.scales);
     return hipGetLastError();
 }
 
@@ -503,7 +569,7 @@ bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len) {
     const int g = c.n_q_heads / c.n_kv_heads;
     if ((int64_t)g * max_q_len > kMaxRowsPerWg) return false;
     const int q_keys = (max_q_len + 31) / 32 * 32;
-    if ((int64_t)q_keys * c.head_dim * 4 > 2 * kStageBytes) return false;
+    if ((int64_t)q_keys * c.head_dim * 4 > 2 * stage_bytes(kv_dtype == HR_FP8_E4M3)) return false;
     return true;
 }
 
@@ -523,18 +589,21 @@ hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, co
         const char* e = getenv("HR_ATTN_VARIANT");
         var = e ? atoi(e) : 0;
     }
+    const bool wide = var == 1;
     if (pv.d == 64) {
         if (rows <= 128) { HR_ATTN_CASE(64, 4, 1); }
         if (rows <= 256) {
-            if (var == 1) { HR_ATTN_CASE(64, 8, 1); }
+            if (wide) { HR_ATTN_CASE(64, 8, 1); }
             HR_ATTN_CASE(64, 4, 2);
         }
         HR_ATTN_CASE(64, 8, 2);
     } else {
         if (rows <= 128) { HR_ATTN_CASE(128, 4, 1); }
         if (rows <= 256) {
-            if (var == 1) { HR_ATTN_CASE(128, 8, 1); }
-            HR_ATTN_CASE(128, 4, 2);
+            // two row blocks per wave at d = 128 need more registers than two waves per SIMD leave (measured at 256 rows,
+            // fp8 pool: 2.1 ms with 4 waves x 2 blocks, 1.3 ms with 8 waves x 1 block)
+            if (var == 2) { HR_ATTN_CASE(128, 4, 2); }
+            HR_ATTN_CASE(128, 8, 1);
         }
         HR_ATTN_CASE(128, 8, 2);
     }
