@@ -212,6 +212,24 @@ size_t hr_doc_prefill_workspace_bytes(const hr_model* model, int32_t n_docs, int
 int hr_doc_prefill(hr_model* model, hr_pool* pool, int32_t n_docs, const int32_t* doc_tokens, const int32_t* doc_lens,
                    const int32_t* page_table, int32_t pt_stride, void* workspace_dev, size_t workspace_bytes, void* stream);
 
+/* ---- per-query selection (what the pipeline does with the scores: Section 3.1, "select top-k"; Table 1 reranks
+ * 5 / 10 / 20 candidates down to the best one) ---- */
+
+/* For each query the k best of its candidates, best first: score descending, candidate index ascending among equal
+ * scores (-0 equals +0; NaN ranks below every number).
+ *   scores_dev   device fp32, the scores of all pairs (what hr_rerank_score wrote)
+ *   seg_dev      device int32 [n_queries + 1], ascending: query i owns pairs seg[i] .. seg[i+1]-1
+ *   max_cands    host int, an upper bound of seg[i+1] - seg[i] (1 .. 4096); a longer segment is cut to its first
+ *                max_cands candidates
+ *   k            1 .. max_cands
+ *   topk_idx_dev device int32 [n_queries][k]: candidate index inside the query's segment, -1 where the query has
+ *                fewer than k candidates
+ *   topk_scores_dev  optional (may be NULL) device fp32 [n_queries][k], 0 where the index is -1
+ * Nothing is allocated; work is enqueued on `stream`; n_queries = 0 is a no-op.  HR_ERR_INVALID_ARG on null
+ * pointers or sizes out of range. */
+int hr_rerank_topk(const float* scores_dev, const int32_t* seg_dev, int32_t n_queries, int32_t max_cands, int32_t k,
+                   int32_t* topk_idx_dev, float* topk_scores_dev, void* stream);
+
 /* ---- introspection for benchmarks ---- */
 
 /* Name of the kernel family a model/pool combination runs ("generic", "mfma"); never NULL. */

@@ -255,6 +255,20 @@ def score_cached(weights, cfg, pool: PagedKV, page_table: np.ndarray, doc_lens: 
     return yes_no_score(weights, cfg, last)
 
 
+def topk(scores: np.ndarray, seg_offsets: Sequence[int], k: int) -> np.ndarray:
+    """Per-query selection (Section 3.1: the reranker's scores pick the top-k candidates): for query i over pairs
+    seg_offsets[i] .. seg_offsets[i+1]-1, the indices (inside the segment) of the k best, best first; score descending,
+    index ascending among equal scores, NaN below every number, -1 where the query has fewer than k candidates."""
+    s = np.asarray(scores, F64)
+    out = np.full((len(seg_offsets) - 1, k), -1, dtype=np.int64)
+    for i in range(len(seg_offsets) - 1):
+        row = s[seg_offsets[i]:seg_offsets[i + 1]]
+        key = np.where(np.isnan(row), -np.inf, row) + 0.0          # + 0.0 turns -0 into +0
+        order = np.argsort(-key, kind="stable")                      # stable: equal keys keep ascending index
+        out[i, :min(k, len(row))] = order[:k]
+    return out
+
+
 def topk_order(scores: np.ndarray, n_queries: int, n_cands: int) -> np.ndarray:
     """Per-query candidate ranking: score descending, candidate index ascending on ties."""
     s = np.asarray(scores, F64).reshape(n_queries, n_cands)

@@ -58,7 +58,7 @@ EXPORTS = [
     "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_free", "hr_weights_pack_bytes", "hr_weights_load",
     "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
-    "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
+    "hr_rerank_topk", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
 ]
 
 
@@ -100,6 +100,7 @@ def _load() -> C.CDLL:
         "hr_doc_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, i32p, i32p, i32p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]),
         "hr_attention_path": (C.c_char_p, [C.c_void_p, C.c_void_p]),
         "hr_gemm_path": (C.c_char_p, [C.c_void_p]),
+        "hr_rerank_topk": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
         "hr_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
         "hr_profile_select": (C.c_int, [C.c_void_p, C.c_uint32]),
         "hr_profile_count": (C.c_int, []),
@@ -174,6 +175,24 @@ def hr_weights_pack_bytes(cfg: hr_model_cfg) -> int:
 # ----------------------------------------------------------------------------------------------
 # convenience holders: own the torch tensors behind the handles
 # ----------------------------------------------------------------------------------------------
+def rerank_topk(scores, seg_offsets, k: int, with_scores: bool = False, stream=None):
+    """Per-query top-k of device scores: seg_offsets (host ints, [n_queries + 1]) delimits each query's pairs.
+    Returns an int32 device tensor [n_queries][k] of candidate indices inside each segment (-1 padded), and the
+    matching scores when asked."""
+    import torch
+    seg = _i32(seg_offsets)
+    n_q = len(seg) - 1
+    max_c = max(int((seg[1:] - seg[:-1]).max()) if n_q > 0 else 1, k, 1)      # an upper bound is all the library needs
+    seg_dev = torch.from_numpy(seg).to(scores.device)
+    idx = torch.empty((max(n_q, 0), k), dtype=torch.int32, device=scores.device)
+    sc = torch.empty((max(n_q, 0), k), dtype=torch.float32, device=scores.device) if with_scores else None
+    check(lib.hr_rerank_topk(C.c_void_p(scores.data_ptr()), C.c_void_p(seg_dev.data_ptr()), n_q, max_c, k,
+                             C.c_void_p(idx.data_ptr()), C.c_void_p(sc.data_ptr()) if with_scores else None, _stream_ptr(stream)),
+          "hr_rerank_topk")
+    idx._hr_seg = seg_dev          # keep the offsets alive until the result is dropped (the kernel may still be queued)
+    return (idx, sc) if with_scores else idx
+
+
 class KVPool:
     """Device buffer + library handle of one paged document-KV pool."""
 

@@ -532,6 +532,17 @@ int hr_doc_prefill(hr_model* m, hr_pool* pool, int32_t n_docs, const int32_t* do
     return HR_OK;
 }
 
+int hr_rerank_topk(const float* scores_dev, const int32_t* seg_dev, int32_t n_queries, int32_t max_cands, int32_t k,
+                   int32_t* topk_idx_dev, float* topk_scores_dev, void* stream) {
+    if (n_queries == 0) return HR_OK;
+    if (!scores_dev || !seg_dev || !topk_idx_dev || n_queries < 0 || max_cands < 1 || max_cands > 4096 || k < 1 || k > max_cands) {
+        snprintf(g_last_error, sizeof(g_last_error), "hr_rerank_topk: null pointer, or n_queries / max_cands (1..4096) / k (1..max_cands) out of range");
+        return HR_ERR_INVALID_ARG;
+    }
+    HR_HIP(launch_segment_topk(scores_dev, seg_dev, n_queries, max_cands, k, topk_idx_dev, topk_scores_dev, (hipStream_t)stream));
+    return HR_OK;
+}
+
 int hr_profile_enable(hr_model* m, int enable) {
     if (!m) return HR_ERR_INVALID_ARG;
     m->prof_on = enable != 0;

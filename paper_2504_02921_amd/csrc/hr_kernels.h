@@ -80,6 +80,9 @@ bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len);
 hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv,
                             const PoolView& pv, int layer, int n_q, int max_q_len, hipStream_t st);
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t st);
+// per-segment top-k by rank counting: idx [n_seg][k] (-1 padded), optional scores [n_seg][k]
+hipError_t launch_segment_topk(const float* scores, const int32_t* seg, int n_seg, int max_cands, int k, int32_t* idx, float* out_scores,
+                               hipStream_t st);
 // copy whole pages (all kv heads) from the new-KV page buffer to pool pages of one layer:
 // pool page dst_table[i] <- new page src_first[doc(i)] + i  (16-bit pools: same arrangement on both sides)
 hipError_t launch_pages_to_pool(const char* kv_new, char* pool_layer_base, const int32_t* src_page, const int32_t* dst_page,

@@ -495,4 +495,52 @@ hipError_t launch_pack_rows(int dtype, const void* src, void* dst, int rows, int
     return hipGetLastError();
 }
 
+
+// ---- per-query top-k.  One workgroup per query; the candidates' keys sit in LDS and every candidate counts the
+// candidates that beat it (higher score, or equal score and lower index), which is its rank: O(n^2) compares for
+// n <= 4096 candidates, no sorting network, and the order is total, so the result does not depend on scheduling.
+namespace {
+constexpr int kTopkThreads = 256;
+constexpr int kTopkMaxCands = 4096;
+
+__global__ void __launch_bounds__(kTopkThreads) segment_topk_kernel(const float* __restrict__ scores, const int32_t* __restrict__ seg,
+                                                                     int max_cands, int k, int32_t* __restrict__ idx,
+                                                                     float* __restrict__ out_scores) {
+    __shared__ float key[kTopkMaxCands];
+    const int q = blockIdx.x;
+    const int begin = seg[q];
+    int n = seg[q + 1] - begin;
+    n = n < 0 ? 0 : (n > max_cands ? max_cands : n);
+    for (int i = threadIdx.x; i < k; i += kTopkThreads) {
+        idx[(size_t)q * k + i] = -1;
+        if (out_scores) out_scores[(size_t)q * k + i] = 0.f;
+    }
+    for (int i = threadIdx.x; i < n; i += kTopkThreads) {
+        const float s = scores[begin + i];
+        key[i] = s != s ? -INFINITY : s;            // NaN ranks below every number (ties with -inf go by index)
+    }
+    __syncthreads();                                // also orders the -1 fill before the winners' stores below
+    for (int i = threadIdx.x; i < n; i += kTopkThreads) {
+        const float si = key[i];
+        int rank = 0;
+        for (int j = 0; j < n; ++j) {
+            const float sj = key[j];
+            rank += (sj > si || (sj == si && j < i)) ? 1 : 0;
+        }
+        if (rank < k) {
+            idx[(size_t)q * k + rank] = i;
+            if (out_scores) out_scores[(size_t)q * k + rank] = scores[begin + i];
+        }
+    }
+}
+}  // namespace
+
+hipError_t launch_segment_topk(const float* scores, const int32_t* seg, int n_seg, int max_cands, int k, int32_t* idx, float* out_scores,
+                               hipStream_t st) {
+    if (n_seg == 0) return hipSuccess;
+    if (max_cands < 1 || max_cands > kTopkMaxCands || k < 1 || k > max_cands) return hipErrorInvalidValue;
+    segment_topk_kernel<<<dim3((unsigned)n_seg), kTopkThreads, 0, st>>>(scores, seg, max_cands, k, idx, out_scores);
+    return hipGetLastError();
+}
+
 }  // namespace hr

@@ -142,6 +142,11 @@ def test_null_handles_are_rejected_everywhere():
     assert st == hb.HR_ERR_INVALID_ARG
     st = hb.lib.hr_rerank_score_full(None, 1, None, None, None, None, None, 0, None, None)
     assert st == hb.HR_ERR_INVALID_ARG
+    st = hb.lib.hr_rerank_topk(None, None, 1, 4, 1, None, None, None)
+    assert st == hb.HR_ERR_INVALID_ARG
+    fake = C.c_void_p(FAKE_DEV)
+    for n_q, max_c, k in [(-1, 4, 1), (1, 0, 1), (1, 4097, 1), (1, 4, 0), (1, 4, 5)]:      # sizes out of range: rejected before any launch
+        assert hb.lib.hr_rerank_topk(fake, fake, n_q, max_c, k, fake, None, None) == hb.HR_ERR_INVALID_ARG
     assert hb.lib.hr_attention_path(None, None).decode() == "none"
     assert hb.lib.hr_gemm_path(None).decode() == "none"
     hb.lib.hr_model_destroy(None)

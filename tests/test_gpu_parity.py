@@ -250,3 +250,32 @@ def test_chunked_no_reuse_pass_and_device_prefill(d, n_q, n_kv):
         case.model.doc_prefill(case.pool, [wl.doc_tokens(uniq[0])], [wl.pool_doc_pages[uniq[0]]])
     assert e.value.status == hb.HR_ERR_PAGE_IN_USE
     case.close()
+
+
+def test_topk_selection_on_device():
+    """hr_rerank_topk against the oracle's selection: bit-exact indices on scores with many ties, ragged queries,
+    NaN, k above / equal to / below the number of candidates, an empty query, one candidate, 4096 candidates."""
+    import torch
+    from paper_2504_02921_amd import binding as hb
+    rng = np.random.default_rng(11)
+    for lens, k in [([20] * 32, 5), ([0, 1, 7, 300, 2, 64], 8), ([4096, 3], 16), ([5, 5], 5), ([3], 1)]:
+        seg = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+        s = (np.round(rng.normal(size=int(seg[-1])) * 4) / 4).astype(np.float32)
+        s[rng.random(len(s)) < 0.02] = np.nan
+        s[rng.random(len(s)) < 0.02] = -0.0
+        dev = torch.from_numpy(s).to("cuda:0")
+        idx, sc = hb.rerank_topk(dev, seg, k, with_scores=True)
+        torch.cuda.synchronize()
+        want = orr.topk(s.astype(np.float64), seg, k)
+        np.testing.assert_array_equal(idx.cpu().numpy().astype(np.int64), want)
+        got_sc = sc.cpu().numpy()
+        for q in range(len(lens)):
+            for j in range(k):
+                if want[q, j] >= 0:
+                    ref = s[seg[q] + want[q, j]]
+                    assert (np.isnan(ref) and np.isnan(got_sc[q, j])) or ref == got_sc[q, j]
+                else:
+                    assert got_sc[q, j] == 0.0
+    # zero queries: nothing is launched
+    empty = hb.rerank_topk(torch.zeros(1, device="cuda:0"), np.array([0]), 3)
+    assert tuple(empty.shape) == (0, 3)

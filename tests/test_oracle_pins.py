@@ -415,6 +415,37 @@ def test_topk_order_ties_break_by_index():
     assert order.tolist() == [[1, 2, 0, 3], [0, 1, 2, 3]]
 
 
+def test_topk_against_brute_force_selection():
+    """Per-query selection: compared with repeatedly taking the best remaining candidate (score, then lower
+    index), on quantised scores so that ties are common; NaN below everything, -0 equal to +0, short queries padded."""
+    rng = np.random.default_rng(5)
+    for trial in range(20):
+        lens = rng.integers(0, 12, size=rng.integers(1, 6))
+        seg = np.concatenate([[0], np.cumsum(lens)])
+        s = np.round(rng.normal(size=seg[-1]) * 2) / 2
+        s[rng.random(len(s)) < 0.1] = np.nan
+        s[rng.random(len(s)) < 0.1] = -0.0
+        k = int(rng.integers(1, 8))
+        got = orr.topk(s, seg, k)
+        for q in range(len(lens)):
+            row = list(s[seg[q]:seg[q + 1]])
+            key = [(-np.inf if np.isnan(v) else float(v)) for v in row]
+            left = list(range(len(row)))
+            want = []
+            while left and len(want) < k:
+                best = left[0]
+                for i in left[1:]:
+                    if key[i] > key[best]:          # strictly better only: the earlier index keeps equal scores
+                        best = i
+                want.append(best)
+                left.remove(best)
+            want += [-1] * (k - len(want))
+            assert got[q].tolist() == want, (trial, q)
+    # worked example: ties by index, NaN last
+    assert orr.topk(np.array([1.0, 3.0, 3.0, np.nan, 2.0]), [0, 5], 4).tolist() == [[1, 2, 4, 0]]
+    assert orr.topk(np.array([np.nan, -np.inf]), [0, 2], 3).tolist() == [[0, 1, -1]]
+
+
 # ----------------------------------------------------------------------------- generators
 def test_generator_casts_and_workload_shapes():
     a = np.array([1.0, 1.00390625, 1.01171875, -3.0e-40, 65504.0], np.float32)
