@@ -28,6 +28,7 @@ namespace hr {
 typedef __attribute__((ext_vector_type(8))) _Float16 halfx8;
 typedef __attribute__((ext_vector_type(4))) _Float16 halfx4;
 typedef __attribute__((ext_vector_type(16))) float floatx16;
+typedef __attribute__((ext_vector_type(4))) unsigned uint4v;
 
 namespace {
 
@@ -273,19 +274,24 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
         }
     } else if constexpr (EPI == EPI_SWIGLU) {
         static_assert(EPI != EPI_SWIGLU || NI % 2 == 0, "gate/up block pairs");
+        // m = silu(g) * u goes through LDS as a half [BM][BN / 2] tile (16-byte chunks XOR-swizzled by the row) and
+        // leaves in whole row segments, like the residual update above.
+        constexpr int OW = BN / 2;                      // output columns of the tile
+        constexpr int CPRO = OW / 8;                    // 16-byte chunks per tile row: 16 (256-byte rows) or 8 (128-byte rows)
+        constexpr int ITER = BM * CPRO / NT;
+        static_assert(EPI != EPI_SWIGLU || ((CPRO == 16 || CPRO == 8) && (BM * CPRO) % NT == 0), "output tile shape");
+        auto swz = [](int r) { return CPRO == 16 ? (r & 15) : ((r >> 1) & 7); };
+        half_t* stage = (half_t*)smem;
         half_t* out = (half_t*)a.out0;
         const int F = a.N / 2;
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
-            const int64_t row = row_base + i * 32;
-            if (row >= a.M) continue;
-            half_t* orow = out + row * F;
+            const int lr = wm * TM + i * 32 + frow;
 #pragma unroll
             for (int j = 0; j < NI; j += 2)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const int col = (n0 + wn * TN) / 2 + (j / 2) * 32 + 8 * r4 + 4 * fh;
-                    if (col >= F) continue;
+                    const int ch = ((wn * TN) / 2 + (j / 2) * 32) / 8 + r4;
                     halfx4 w;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -293,8 +299,18 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
                         const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
                         w[e] = from_float<half_t>(g * sg * u);
                     }
-                    *(halfx4*)(orow + col) = w;
+                    *(halfx4*)(stage + lr * OW + ((ch ^ swz(lr)) << 3) + 4 * fh) = w;
                 }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            const int L = it * NT + tid;
+            const int row = L / CPRO, pch = L % CPRO;
+            const int col = n0 / 2 + ((pch ^ swz(row)) << 3);
+            const int64_t grow = m0 + row;
+            if (grow >= a.M || col >= F) continue;          // F is a multiple of 32: whole chunks
+            *(uint4v*)(out + grow * F + col) = *(const uint4v*)(stage + row * OW + (pch << 3));
         }
     } else {   // EPI_QKV_ROPE
         constexpr int hb = HB;                                  // 32-wide blocks per half head: head_dim = 64 * HB
