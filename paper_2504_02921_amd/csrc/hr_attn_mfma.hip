@@ -98,7 +98,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                                                            half_t* __restrict__ o, MetaView mv, PoolView pv, int layer, int n_q,
                                                            const int32_t* __restrict__ m_cu, const int32_t* __restrict__ m_prefix,
                                                            const int32_t* __restrict__ m_pt, const int32_t* __restrict__ m_new_cu,
-                                                           const float* __restrict__ p_scales) {
+                                                           const float* __restrict__ p_scales, int last_only) {
     // The metadata arrays come as separate read-only, non-aliased parameters so that the per-item lookups (uniform
     // over the workgroup) compile to scalar loads: a vector load that is used right away makes the wave wait for
     // everything it has in flight, including the stage it requested a moment earlier, because vector memory
@@ -373,14 +373,16 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     // ---- persistent loop over work items.  The first stage of the next item is requested while the last stage of
     // the current one is consumed, and its Q fragments are fetched before the current item's output is stored, so
     // only the very first item of a workgroup pays the start-up latency.
+    // last_only: only the last query token of every pair is computed (g rows per item, all of the pair's own keys
+    // visible) and its output goes to row `pair` of a compact [n_pairs][n_q][d] buffer: what the last layer needs.
     auto setup_rows = [&](const ItemCtx& c) {
-        M = c.qn * g;
+        M = last_only ? g : c.qn * g;
 #pragma unroll
         for (int rb = 0; rb < R; ++rb) {
             int row = (wave + rb * NW) * 32 + ln;
             row_ok[rb] = row < M;
             int rc = row < M ? row : M - 1;
-            int i = rc / g, a = rc - i * g;
+            int i = last_only ? c.qn - 1 : rc / g, a = last_only ? rc : rc - i * g;
             row_i[rb] = i;
             row_off[rb] = ((size_t)(c.t0 + i) * n_q + c.h * g + a) * HD;
 #pragma unroll
@@ -499,7 +501,12 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
         for (int rb = 0; rb < R; ++rb) {
             const float l = l_run[rb] + __shfl_xor(l_run[rb], 32, 64);
             const float inv = 1.0f / l;
-            out_off[rb] = row_off[rb];
+            if (last_only) {
+                const int row = (wave + rb * NW) * 32 + ln;
+                out_off[rb] = ((size_t)cur.p * n_q + cur.h * g + (row < g ? row : g - 1)) * HD;
+            } else {
+                out_off[rb] = row_off[rb];
+            }
             out_ok[rb] = row_ok[rb];
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
@@ -527,7 +534,7 @@ int attn_wgs_override() {
 
 template <int HD, int NW, int R, bool FP8>
 hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const MetaView& mv, const PoolView& pv, int layer, int n_q,
-                      hipStream_t st) {
+                      int last_only, hipStream_t st) {
     constexpr int SB = stage_bytes(FP8);
     const size_t lds = 2 * SB + 2 * Geo<HD, FP8, SB>::PPS * 2 * sizeof(float) + (FP8 ? 2 * SB : 0);
     static bool attr_set = false;
@@ -554,7 +561,7 @@ hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const Meta
     const int env_wgs = attn_wgs_override();
     const int grid = std::min(n_items, env_wgs > 0 ? env_wgs : max_wgs);
     attn_mfma_kernel<HD, NW, R, FP8><<<dim3((unsigned)grid), NW * 64, lds, st>>>(q, kv_new, o, mv, pv, layer, n_q, mv.cu, mv.prefix_len, mv.page_table,
-                                                                             mv.new_cu, pv.scales);
+                                                                             mv.new_cu, pv.scales, last_only);
     return hipGetLastError();
 }
 
@@ -574,16 +581,16 @@ bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len) {
 }
 
 hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv, const PoolView& pv, int layer,
-                            int n_q, int max_q_len, hipStream_t st) {
+                            int n_q, int max_q_len, hipStream_t st, bool last_only) {
     if (mv.n_seq == 0) return hipSuccess;
-    const int rows = n_q / pv.n_kv * max_q_len;
+    const int rows = n_q / pv.n_kv * (last_only ? 1 : max_q_len);
     const half_t* qh = (const half_t*)q;
     const char* kvn = (const char*)kv_new_pages;
     half_t* oh = (half_t*)o;
     const bool fp8 = pv.kv_dtype == HR_FP8_E4M3;
 #define HR_ATTN_CASE(HD, NW, R)                                                                       \
-    return fp8 ? launch_one<HD, NW, R, true>(qh, kvn, oh, mv, pv, layer, n_q, st)                       \
-               : launch_one<HD, NW, R, false>(qh, kvn, oh, mv, pv, layer, n_q, st)
+    return fp8 ? launch_one<HD, NW, R, true>(qh, kvn, oh, mv, pv, layer, n_q, last_only ? 1 : 0, st)   \
+               : launch_one<HD, NW, R, false>(qh, kvn, oh, mv, pv, layer, n_q, last_only ? 1 : 0, st)
     static int var = -1;
     if (var < 0) {
         const char* e = getenv("HR_ATTN_VARIANT");

@@ -23,6 +23,7 @@ struct hr_model {
     bool force_generic = false;
     // optional per-kernel timing with HIP events (benchmarks)
     bool prof_on = false;
+    bool no_last_short = false;           // HR_NO_LAST_SHORTCUT=1: run the last layer on every token (A/B runs)
     uint32_t prof_mask = 0xFFFFFFFFu;     // kernel classes that are timed while prof_on
     std::vector<hipEvent_t> prof_events;          // pool, two per timed launch
     std::vector<int> prof_class;                  // class of each recorded launch
@@ -160,6 +161,10 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
     }
     const bool mfma_attn = !m->force_generic && attn_mfma_supported(c, pv.kv_dtype, max_new_len);
     if (self_prefix && !mfma_attn) return HR_ERR_UNSUPPORTED_SHAPE;
+    // the shortened last layer needs one output row per sequence, the MFMA kernels, something to save (T > P), and
+    // room for P fp32 rows in the q buffer
+    const bool last_short = !m->no_last_short && mfma_attn && m->mfma_gemm && !fill && !self_prefix && mv.n_out == mv.n_seq &&
+                            T > mv.n_seq && (size_t)T * nq * dtype_size(dt) >= (size_t)mv.n_seq * H * sizeof(float) && H % 4 == 0;
 
     // with the MFMA attention the new tokens' K/V are written straight into 16-slot pages (k and v regions together);
     // slots past a sequence's end are never written by any layer, so one clear per call keeps them finite
@@ -185,6 +190,30 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
             HR_TIMED(PC_ELEMENTWISE, launch_pages_to_pool((const char*)k, layer_base, fill->src_page, fill->dst_page, fill->n_pages,
                                                           c.n_kv_heads * 2 * kPageTokens * d * 2, st));
             if (l + 1 == c.n_layers) return HR_OK;
+        }
+        if (last_short && l + 1 == c.n_layers) {
+            // Last layer, scoring pass: only each pair's last token feeds the score, so attention runs g rows per
+            // (pair, kv head) into a compact [P][n_q][d] buffer and the rest of the layer runs on P rows instead
+            // of T (exact: the other rows' outputs of this layer are never read).
+            const int64_t P = mv.n_seq;
+            float* x_last = (float*)q;                      // q is dead once attention has run
+            HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, o, mv, pv, l, c.n_q_heads, max_new_len, st, true));
+            HR_TIMED(PC_ELEMENTWISE, launch_gather_rows_f32(x, mv.out_row, x_last, (int)P, H, st));
+            GemmArgs a{};
+            a.A = o; a.W = layer_w(m, l, m->pack.wo); a.M = P; a.N = H; a.K = nq; a.x = x_last;
+            HR_TIMED(PC_GEMM_O, launch_gemm_mfma(EPI_RESID_ADD, a, st));
+            HR_TIMED(PC_RMSNORM, launch_rmsnorm(dt, x_last, m->norm2[l], y, P, H, c.rms_eps, st));
+            GemmArgs gu{};
+            gu.A = y; gu.W = layer_w(m, l, m->pack.wgu); gu.M = P; gu.N = 2 * F; gu.K = H; gu.out0 = mm;
+            HR_TIMED(PC_GEMM_GATE_UP, launch_gemm_mfma(EPI_SWIGLU, gu, st));
+            GemmArgs b{};
+            b.A = mm; b.W = layer_w(m, l, m->pack.wd); b.M = P; b.N = H; b.K = F; b.x = x_last;
+            HR_TIMED(PC_GEMM_DOWN, launch_gemm_mfma(EPI_RESID_ADD, b, st));
+            MetaView compact = mv;
+            compact.out_row = nullptr;                      // row p of x_last belongs to pair p
+            HR_TIMED(PC_SCORE_HEAD, launch_score_head(dt, x_last, m->final_norm, m->embedding, compact, scores, H, c.rms_eps, c.yes_id,
+                                                      c.no_id, st));
+            return HR_OK;
         }
         if (mfma_attn) {
             HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, o, mv, pv, self_prefix ? 0 : l, c.n_q_heads, max_new_len, st));
@@ -276,6 +305,8 @@ int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* w, void* pack
     const char* force = getenv("HR_FORCE_GENERIC");      // A/B switch for tests and benchmarks
     m->force_generic = force && force[0] == '1';
     m->mfma_gemm = !m->force_generic && hr::gemm_mfma_supported(*cfg);
+    const char* nls = getenv("HR_NO_LAST_SHORTCUT");
+    m->no_last_short = nls && nls[0] == '1';
 
     hipStream_t st = (hipStream_t)stream;
     const int dt = cfg->dtype;

@@ -78,8 +78,10 @@ hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st)
 bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len);
 // kv_new_pages: the new tokens' K/V as pages (see GemmArgs::kv_pages)
 hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv,
-                            const PoolView& pv, int layer, int n_q, int max_q_len, hipStream_t st);
+                            const PoolView& pv, int layer, int n_q, int max_q_len, hipStream_t st, bool last_only = false);
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t st);
+// dst[i][:] = src[rows[i]][:] for n rows of `cols` floats (device arrays)
+hipError_t launch_gather_rows_f32(const float* src, const int32_t* rows, float* dst, int n, int cols, hipStream_t st);
 // per-segment top-k by rank counting: idx [n_seg][k] (-1 padded), optional scores [n_seg][k]
 hipError_t launch_segment_topk(const float* scores, const int32_t* seg, int n_seg, int max_cands, int k, int32_t* idx, float* out_scores,
                                hipStream_t st);

@@ -278,7 +278,7 @@ __global__ void __launch_bounds__(256) score_head_kernel(const float* __restrict
                                                          float* __restrict__ scores, int H, float eps, int yes_id, int no_id) {
     __shared__ float red[4];
     int p = blockIdx.x;
-    const float* xr = x + (size_t)out_row[p] * H;
+    const float* xr = x + (size_t)(out_row ? out_row[p] : p) * H;     // no table: row p
     float ssq = 0.f;
     for (int c = threadIdx.x; c < H; c += 256) { float v = xr[c]; ssq += v * v; }
     ssq = block_sum_256(ssq, red);
@@ -495,6 +495,23 @@ hipError_t launch_pack_rows(int dtype, const void* src, void* dst, int rows, int
     return hipGetLastError();
 }
 
+
+// ---- dst[i][:] = src[rows[i]][:]: the rows of the last query tokens, for the last layer's shortened tail
+namespace {
+__global__ void __launch_bounds__(256) gather_rows_f32_kernel(const float* __restrict__ src, const int32_t* __restrict__ rows,
+                                                              float* __restrict__ dst, int cols) {
+    const float4* s = (const float4*)(src + (size_t)rows[blockIdx.x] * cols);
+    float4* d = (float4*)(dst + (size_t)blockIdx.x * cols);
+    for (int c = threadIdx.x; c < cols / 4; c += 256) d[c] = s[c];
+}
+}  // namespace
+
+hipError_t launch_gather_rows_f32(const float* src, const int32_t* rows, float* dst, int n, int cols, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    if (cols % 4 != 0) return hipErrorInvalidValue;
+    gather_rows_f32_kernel<<<dim3((unsigned)n), 256, 0, st>>>(src, rows, dst, cols);
+    return hipGetLastError();
+}
 
 // ---- per-query top-k.  One workgroup per query; the candidates' keys sit in LDS and every candidate counts the
 // candidates that beat it (higher score, or equal score and lower index), which is its rank: O(n^2) compares for
