@@ -279,3 +279,25 @@ def test_topk_selection_on_device():
     # zero queries: nothing is launched
     empty = hb.rerank_topk(torch.zeros(1, device="cuda:0"), np.array([0]), 3)
     assert tuple(empty.shape) == (0, 3)
+
+
+@pytest.mark.parametrize("d,n_q,n_kv,kv", [(64, 14, 2, "bf16"), (128, 8, 2, "fp8")])
+def test_shortened_last_layer_is_bit_identical(d, n_q, n_kv, kv, monkeypatch):
+    """The last layer runs on the pairs' last tokens only; with the switch that makes it run on every token the
+    scores must come out bit for bit the same (same rows, same accumulation order), including pairs with one token."""
+    model = small_model(dtype="bf16", n_layers=3, hidden=256, n_q=n_q, n_kv=n_kv, d=d, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("last_layer", model, 5, 4, (20, 150), (1, 40), kv, seed=21)
+    w = wlmod.SeededWeights(model, seed=22, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(cfg, spare_pages=3)
+    scores = []
+    for flag in ("0", "1"):
+        monkeypatch.setenv("HR_NO_LAST_SHORTCUT", flag)       # read when the model handle is created
+        case = H.Case(wl, w)
+        try:
+            case.fill_from_prefill()
+            scores.append(case.gpu_scores())
+            if flag == "0":
+                H.assert_scores_close(scores[0], case.oracle_scores(), H.TOL["bf16"], "shortened last layer")
+        finally:
+            case.close()
+    np.testing.assert_array_equal(scores[0], scores[1])
