@@ -49,7 +49,7 @@ def main():
                     help="also run a plain device copy of this many MiB (known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        log("bench.py: this build measures ONE GPU only (pairs shard over GPUs with no collective; see DESIGN.md). "
+        log("bench.py: this build measures ONE GPU only (pairs are independent, so they shard over GPUs with no collective). "
             "Run with --gpus 1.")
         sys.exit(2)
 
