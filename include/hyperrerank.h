@@ -139,6 +139,19 @@ int hr_doc_kv_write(hr_pool* pool, int32_t doc_len, const int32_t* page_ids,
                     const void* k_dev, const void* v_dev,
                     const float* k_scales_dev, const float* v_scales_dev, void* stream);
 
+/* Read one document's K/V back from its pages (the inverse of hr_doc_kv_write): what a storage tier would take
+ * from the pool (Section 4.1 keeps the cached KV outside GPU memory), and what makes the pages a prefill wrote
+ * checkable value by value.
+ *   page_ids      host, ceil(doc_len/16) ids of pages that hold a document (written or prefilled)
+ *   k_dev, v_dev  device, logical layout [n_layers][doc_len][n_kv_heads][head_dim] in the pool's own element type:
+ *                 fp32 for HR_F32 pools, IEEE half for HR_BF16 pools (the pool keeps the caller's bf16 values as
+ *                 halves, exactly, and prefilled pages are halves in the first place), E4M3 codes for fp8 pools
+ *   k_scales_dev, v_scales_dev   fp8 only: device fp32 [n_layers][n_pages][n_kv_heads]; else NULL
+ * One gather kernel is enqueued on `stream`.  HR_ERR_PAGE_RANGE for an id out of range, HR_ERR_TABLE_SHORT for a page
+ * that holds nothing, HR_ERR_LEN_RANGE for doc_len <= 0. */
+int hr_doc_kv_read(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids,
+                   void* k_dev, void* v_dev, float* k_scales_dev, float* v_scales_dev, void* stream);
+
 /* Mark pages free again (contents are left as they are). */
 int hr_doc_kv_free(hr_pool* pool, const int32_t* page_ids, int32_t n);
 
@@ -207,7 +220,9 @@ size_t hr_doc_prefill_workspace_bytes(const hr_model* model, int32_t n_docs, int
  *   doc_tokens  host int32, the documents' token ids back to back
  *   doc_lens    host int32 [n_docs], each >= 1
  *   page_table  host int32 [n_docs][pt_stride]; row d names ceil(doc_lens[d]/16) distinct free (or reserved) pages
- * 16-bit pools and MFMA-covered models only (HR_ERR_UNSUPPORTED_SHAPE otherwise); pages are marked used on
+ * 16-bit and fp8 pools, MFMA-covered models only (HR_ERR_UNSUPPORTED_SHAPE otherwise).  For an fp8 pool every page
+ * is quantised as it is stored: per (layer, page, kv head) and separately for K and V, scale = amax / 448 over the page
+ * (1 if amax = 0) in fp32, code = the E4M3 value nearest to x / scale (ties to the even code).  Pages are marked used on
  * success.  Work is enqueued on `stream`. */
 int hr_doc_prefill(hr_model* model, hr_pool* pool, int32_t n_docs, const int32_t* doc_tokens, const int32_t* doc_lens,
                    const int32_t* page_table, int32_t pt_stride, void* workspace_dev, size_t workspace_bytes, void* stream);

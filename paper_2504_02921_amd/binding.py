@@ -55,7 +55,7 @@ class hr_weight_ptrs(C.Structure):
 
 EXPORTS = [
     "hr_status_str", "hr_last_error", "hr_kv_pool_bytes", "hr_kv_pool_create", "hr_kv_pool_destroy", "hr_kv_pool_free_pages",
-    "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_free", "hr_weights_pack_bytes", "hr_weights_load",
+    "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_read", "hr_doc_kv_free", "hr_weights_pack_bytes", "hr_weights_load",
     "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
     "hr_rerank_topk", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
@@ -84,6 +84,7 @@ def _load() -> C.CDLL:
         "hr_kv_pool_free_pages": (C.c_int64, [C.c_void_p]),
         "hr_kv_pool_alloc_pages": (C.c_int, [C.c_void_p, C.c_int32, i32p]),
         "hr_doc_kv_write": (C.c_int, [C.c_void_p, C.c_int32, i32p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+        "hr_doc_kv_read": (C.c_int, [C.c_void_p, C.c_int32, i32p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
         "hr_doc_kv_free": (C.c_int, [C.c_void_p, i32p, C.c_int32]),
         "hr_weights_pack_bytes": (C.c_size_t, [C.POINTER(hr_model_cfg)]),
         "hr_weights_load": (C.c_int, [C.POINTER(hr_model_cfg), C.POINTER(hr_weight_ptrs), C.c_void_p, C.c_size_t,
@@ -216,6 +217,24 @@ class KVPool:
         st = lib.hr_doc_kv_write(self.handle, int(doc_len), _i32p(ids), C.c_void_p(k.data_ptr()), C.c_void_p(v.data_ptr()),
                                  ks, vs, _stream_ptr(stream))
         check(st, "hr_doc_kv_write")
+
+    def read(self, doc_len: int, page_ids, stream=None):
+        """The document's K/V back from its pages: device tensors [L][doc_len][n_kv][d] in the pool's element type
+        (float32, float16 for 16-bit pools, uint8 codes for fp8), plus K / V scales [L][n_pages][n_kv] for fp8."""
+        import torch
+        ids = _i32(page_ids)
+        L, n_kv, d = self.cfg.n_layers, self.cfg.n_kv_heads, self.cfg.head_dim
+        dt = {HR_F32: torch.float32, HR_BF16: torch.float16, HR_FP8_E4M3: torch.uint8}[self.cfg.kv_dtype]
+        k = torch.empty((L, int(doc_len), n_kv, d), dtype=dt, device=self.mem.device)
+        v = torch.empty_like(k)
+        ks = vs = None
+        if self.cfg.kv_dtype == HR_FP8_E4M3:
+            ks = torch.empty((L, len(ids), n_kv), dtype=torch.float32, device=self.mem.device)
+            vs = torch.empty_like(ks)
+        check(lib.hr_doc_kv_read(self.handle, int(doc_len), _i32p(ids), C.c_void_p(k.data_ptr()), C.c_void_p(v.data_ptr()),
+                                 C.c_void_p(ks.data_ptr()) if ks is not None else None,
+                                 C.c_void_p(vs.data_ptr()) if vs is not None else None, _stream_ptr(stream)), "hr_doc_kv_read")
+        return (k, v, ks, vs) if ks is not None else (k, v)
 
     def free(self, page_ids) -> None:
         ids = _i32(page_ids)

@@ -186,9 +186,17 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
         }
         if (fill) {
             // this layer's K/V pages are final: store them, and stop once the last layer's are in
-            char* layer_base = fill->pool->base + (size_t)l * fill->pool->cfg.num_pages * c.n_kv_heads * 2 * kPageTokens * d * 2;
-            HR_TIMED(PC_ELEMENTWISE, launch_pages_to_pool((const char*)k, layer_base, fill->src_page, fill->dst_page, fill->n_pages,
-                                                          c.n_kv_heads * 2 * kPageTokens * d * 2, st));
+            const hr_pool* fp = fill->pool;
+            const size_t pages_all_heads = (size_t)l * fp->cfg.num_pages * c.n_kv_heads;
+            if (fp->cfg.kv_dtype == HR_FP8_E4M3) {
+                float* scales = (float*)(fp->base + fp->lay.data_bytes) + pages_all_heads * 2;
+                HR_TIMED(PC_ELEMENTWISE, launch_pages_to_pool_fp8((const char*)k, fp->base + pages_all_heads * 2 * kPageTokens * d, scales,
+                                                                  fill->src_page, fill->dst_page, fill->n_pages, c.n_kv_heads, d, st));
+            } else {
+                HR_TIMED(PC_ELEMENTWISE, launch_pages_to_pool((const char*)k, fp->base + pages_all_heads * 2 * kPageTokens * d * 2,
+                                                              fill->src_page, fill->dst_page, fill->n_pages,
+                                                              c.n_kv_heads * 2 * kPageTokens * d * 2, st));
+            }
             if (l + 1 == c.n_layers) return HR_OK;
         }
         if (last_short && l + 1 == c.n_layers) {
@@ -358,6 +366,20 @@ int hr_doc_kv_write(hr_pool* pool, int32_t doc_len, const int32_t* page_ids, con
     return HR_OK;
 }
 
+int hr_doc_kv_read(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids, void* k_dev, void* v_dev, float* ks, float* vs,
+                   void* stream) {
+    int rc = hr::pool_check_read(pool, doc_len, page_ids);
+    if (rc != HR_OK) return rc;
+    if (!k_dev || !v_dev) return HR_ERR_INVALID_ARG;
+    if (pool->cfg.kv_dtype == HR_FP8_E4M3 && (!ks || !vs)) return HR_ERR_INVALID_ARG;
+    hipError_t e = hr::launch_kv_gather(pool->lay, pool->base, page_ids, doc_len, k_dev, v_dev, ks, vs, (hipStream_t)stream);
+    if (e != hipSuccess) {
+        note_hip_error(e, "pool gather kernel");
+        return HR_ERR_DEVICE;
+    }
+    return HR_OK;
+}
+
 size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t total_q_tokens, int32_t pt_stride) {
     if (!m || n_pairs < 0 || total_q_tokens < 0 || pt_stride < 0) return 0;
     return hr::make_workspace(m->cfg, n_pairs, total_q_tokens, pt_stride, !m->mfma_gemm).total;
@@ -503,7 +525,7 @@ int hr_doc_prefill(hr_model* m, hr_pool* pool, int32_t n_docs, const int32_t* do
     const hr_model_cfg& c = m->cfg;
     if (pool->cfg.n_layers != c.n_layers || pool->cfg.n_kv_heads != c.n_kv_heads || pool->cfg.head_dim != c.head_dim)
         return HR_ERR_MISMATCH;
-    if (pool->cfg.kv_dtype != HR_BF16 || !chunked_ok(m)) return HR_ERR_UNSUPPORTED_SHAPE;
+    if ((pool->cfg.kv_dtype != HR_BF16 && pool->cfg.kv_dtype != HR_FP8_E4M3) || !chunked_ok(m)) return HR_ERR_UNSUPPORTED_SHAPE;
     int64_t T = 0;
     int max_len = 0;
     std::vector<int32_t> dst;          // flat list of target pages, document after document

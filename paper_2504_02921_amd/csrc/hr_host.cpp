@@ -106,6 +106,20 @@ Workspace make_workspace(const hr_model_cfg& c, int64_t n_seq, int64_t T, int64_
     return w;
 }
 
+int pool_check_read(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids) {
+    if (!pool || !page_ids) return HR_ERR_INVALID_ARG;
+    if (doc_len <= 0) return HR_ERR_LEN_RANGE;
+    int64_t n = ((int64_t)doc_len + kPageTokens - 1) / kPageTokens;
+    if (n > pool->cfg.num_pages) return HR_ERR_LEN_RANGE;
+    for (int64_t i = 0; i < n; ++i) {
+        int32_t p = page_ids[i];
+        if (p < 0 || p >= pool->cfg.num_pages) return HR_ERR_PAGE_RANGE;
+    }
+    for (int64_t i = 0; i < n; ++i)
+        if (pool->state[page_ids[i]] != PAGE_USED) return HR_ERR_TABLE_SHORT;
+    return HR_OK;
+}
+
 int pool_check_write(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids) {
     if (!pool || !page_ids) return HR_ERR_INVALID_ARG;
     if (doc_len <= 0) return HR_ERR_LEN_RANGE;

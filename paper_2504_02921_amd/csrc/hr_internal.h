@@ -82,6 +82,7 @@ struct hr_pool {
 // Host-side validation / bookkeeping (no HIP calls), used by the engine and testable on a CPU.
 namespace hr {
 int pool_check_write(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids);
+int pool_check_read(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids);
 void pool_mark(hr_pool* pool, const int32_t* page_ids, int n, PageState st);
 int score_check_args(const hr_model_cfg& mc, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table,
                      int32_t pt_stride, const int32_t* doc_lens, const int32_t* query_tokens,

@@ -79,6 +79,12 @@ bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len);
 // kv_new_pages: the new tokens' K/V as pages (see GemmArgs::kv_pages)
 hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv,
                             const PoolView& pv, int layer, int n_q, int max_q_len, hipStream_t st, bool last_only = false);
+// fp8 pools: quantising copy of whole pages (amax -> scale -> E4M3 codes per page and kv head) from the half new-KV buffer
+hipError_t launch_pages_to_pool_fp8(const char* kv_new, char* pool_layer_base, float* scales_layer_base, const int32_t* src_page,
+                                    const int32_t* dst_page, int n_pages, int n_kv, int d, hipStream_t st);
+// inverse of launch_kv_scatter: pages -> logical [L][D][n_kv][d] in the pool's element type (+ scales for fp8)
+hipError_t launch_kv_gather(const PoolLayout& lay, const char* pool_base, const int32_t* page_ids_host, int doc_len, void* k, void* v,
+                            float* ks, float* vs, hipStream_t st);
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t st);
 // dst[i][:] = src[rows[i]][:] for n rows of `cols` floats (device arrays)
 hipError_t launch_gather_rows_f32(const float* src, const int32_t* rows, float* dst, int n, int cols, hipStream_t st);

@@ -52,6 +52,16 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
     return r;
 }
 
+__device__ __forceinline__ float block_max_256(float v, float* red) {
+    v = wave_max(v);
+    int w = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float r = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    return r;
+}
+
 template <typename T>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
                                                       T* __restrict__ y, int H, float eps) {
@@ -354,9 +364,115 @@ __global__ void pages_to_pool_kernel(const uint4* __restrict__ src, uint4* __res
     for (int i = threadIdx.x; i < n16; i += blockDim.x) d[i] = s[i];
 }
 
+// Round to the nearest E4M3 value, ties to the even code, saturating at +-448 (bias 7, subnormals m/8 * 2^-6, no
+// infinities).  fp64 in, so that a quotient computed in fp64 is rounded once.
+__device__ __forceinline__ uint8_t e4m3_encode_rne(double q) {
+    const double a = fmin(fabs(q), 448.0);
+    int e;
+    frexp(a, &e);                                   // a = f * 2^e, f in [0.5, 1): floor(log2 a) = e - 1 (a = 0: e = 0)
+    int eb = (a > 0.0 ? e - 1 : -6);
+    eb = eb < -6 ? -6 : eb;                         // the subnormal range shares the spacing of the first binade
+    const double n = rint(ldexp(a, 3 - eb));       // multiples of the spacing 2^(eb - 3); rint = ties to even; 0 .. 16
+    int code;
+    if (n < 8.0) code = (int)n;                     // subnormal (only when eb = -6)
+    else if (n < 16.0) code = ((eb + 7) << 3) | ((int)n - 8);
+    else code = (eb + 8) << 3;                      // rounded up into the next binade (never past 448: a <= 448 = 1.75 * 2^8)
+    return (uint8_t)(code | (q < 0.0 || (q == 0.0 && signbit(q)) ? 0x80 : 0));
+}
+
+// fp8 pools, document prefill: half pages of this pass -> quantised pool pages.  One workgroup per (page, kv head):
+// amax over the page's K block and over its V block (slots past the document's end hold zeros), scale = amax / 448
+// (1 when amax = 0) in fp32, code = encode(x / scale) with the quotient in fp64.
+__global__ void __launch_bounds__(256) pages_to_pool_fp8_kernel(const half_t* __restrict__ src, uint8_t* __restrict__ dst,
+                                                               float* __restrict__ scales, const int32_t* __restrict__ src_page,
+                                                               const int32_t* __restrict__ dst_page, int n_kv, int d) {
+    __shared__ float red[4];
+    const int h = blockIdx.y;
+    const int blk = kPageTokens * d;
+    const half_t* sp = src + ((size_t)src_page[blockIdx.x] * n_kv + h) * (2 * blk);
+    const size_t dpage = (size_t)dst_page[blockIdx.x] * n_kv + h;
+    uint8_t* dp = dst + dpage * (2 * blk);
+    float amax[2];
+    for (int part = 0; part < 2; ++part) {
+        float m = 0.f;
+        for (int e = threadIdx.x; e < blk; e += 256) m = fmaxf(m, fabsf((float)sp[part * blk + e]));
+        amax[part] = block_max_256(m, red);
+    }
+    const float sk = amax[0] > 0.f ? amax[0] / 448.0f : 1.0f, sv = amax[1] > 0.f ? amax[1] / 448.0f : 1.0f;
+    for (int e = threadIdx.x; e < blk; e += 256) {
+        const int t = e / d, c = e - t * d;
+        dp[k_elem(t, c, d, 1)] = e4m3_encode_rne((double)(float)sp[k_elem(t, c, d, 2)] / (double)sk);
+        dp[blk + v_elem(t, c, d)] = e4m3_encode_rne((double)(float)sp[blk + v_elem(t, c, d)] / (double)sv);
+    }
+    if (threadIdx.x == 0) {
+        scales[dpage * 2] = sk;
+        scales[dpage * 2 + 1] = sv;
+    }
+}
+
+// pool read-back: pages in the private arrangement -> logical [L][D][n_kv][d] in the pool's own element type
+// grid: (n_pages, n_layers * n_kv); 256 threads
+template <typename KVT>
+__global__ void __launch_bounds__(256) kv_gather_kernel(const KVT* __restrict__ pool, const float* __restrict__ scales, PageIdChunk page_ids,
+                                                        int pg0, int doc_len, int n_pages, KVT* __restrict__ k, KVT* __restrict__ v,
+                                                        float* __restrict__ ks, float* __restrict__ vs, int num_pages, int n_kv, int d) {
+    const int pg = pg0 + blockIdx.x;
+    const int layer = blockIdx.y / n_kv, h = blockIdx.y % n_kv;
+    const int page = page_ids.ids[blockIdx.x];
+    const size_t blk = (size_t)kPageTokens * d;
+    const size_t bi = (((size_t)layer * num_pages + page) * n_kv + h) * 2;
+    const KVT* kb = pool + bi * blk;
+    const KVT* vb = kb + blk;
+    for (int e = threadIdx.x; e < (int)blk; e += 256) {
+        const int tk = e / d, c = e - tk * d;
+        const int tok = pg * kPageTokens + tk;
+        if (tok >= doc_len) continue;
+        const size_t o = (((size_t)layer * doc_len + tok) * n_kv + h) * d + c;
+        k[o] = kb[k_elem(tk, c, d, (int)sizeof(KVT))];
+        v[o] = vb[v_elem(tk, c, d)];
+    }
+    if (scales && threadIdx.x == 0) {
+        const size_t si = ((size_t)layer * n_pages + pg) * n_kv + h;
+        ks[si] = scales[bi];
+        vs[si] = scales[bi + 1];
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
+hipError_t launch_pages_to_pool_fp8(const char* kv_new, char* pool_layer_base, float* scales_layer_base, const int32_t* src_page,
+                                    const int32_t* dst_page, int n_pages, int n_kv, int d, hipStream_t st) {
+    if (n_pages == 0) return hipSuccess;
+    pages_to_pool_fp8_kernel<<<dim3((unsigned)n_pages, (unsigned)n_kv), 256, 0, st>>>((const half_t*)kv_new, (uint8_t*)pool_layer_base,
+                                                                                     scales_layer_base, src_page, dst_page, n_kv, d);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_gather(const PoolLayout& lay, const char* pool_base, const int32_t* page_ids_host, int doc_len, void* k, void* v,
+                            float* ks, float* vs, hipStream_t st) {
+    const int n_pages = (doc_len + kPageTokens - 1) / kPageTokens;
+    const float* scales = lay.kv_dtype == HR_FP8_E4M3 ? (const float*)(pool_base + lay.data_bytes) : nullptr;
+    for (int pg0 = 0; pg0 < n_pages; pg0 += 256) {
+        const int n = n_pages - pg0 < 256 ? n_pages - pg0 : 256;
+        PageIdChunk ids;
+        for (int i = 0; i < 256; ++i) ids.ids[i] = i < n ? page_ids_host[pg0 + i] : 0;
+        const dim3 grid((unsigned)n, (unsigned)(lay.n_layers * lay.n_kv));
+        if (lay.kv_dtype == HR_F32)
+            kv_gather_kernel<float><<<grid, 256, 0, st>>>((const float*)pool_base, nullptr, ids, pg0, doc_len, n_pages, (float*)k, (float*)v,
+                                                          nullptr, nullptr, lay.num_pages, lay.n_kv, lay.d);
+        else if (lay.kv_dtype == HR_BF16)
+            kv_gather_kernel<half_t><<<grid, 256, 0, st>>>((const half_t*)pool_base, nullptr, ids, pg0, doc_len, n_pages, (half_t*)k,
+                                                           (half_t*)v, nullptr, nullptr, lay.num_pages, lay.n_kv, lay.d);
+        else
+            kv_gather_kernel<uint8_t><<<grid, 256, 0, st>>>((const uint8_t*)pool_base, scales, ids, pg0, doc_len, n_pages, (uint8_t*)k,
+                                                            (uint8_t*)v, ks, vs, lay.num_pages, lay.n_kv, lay.d);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_pages_to_pool(const char* kv_new, char* pool_layer_base, const int32_t* src_page, const int32_t* dst_page,
                                 int n_pages, int page_bytes_all_heads, hipStream_t st) {
     if (n_pages == 0) return hipSuccess;

@@ -49,8 +49,11 @@ int main() {
     CHECK(hr::pool_check_write(pool, 40, ids) == HR_ERR_PAGE_DUP);
     ids[2] = 7;
     CHECK(hr::pool_check_write(pool, 40, ids) == HR_OK);
+    CHECK(hr::pool_check_read(pool, 40, ids) == HR_ERR_TABLE_SHORT);
     hr::pool_mark(pool, ids, 3, hr::PAGE_USED);
     CHECK(hr_kv_pool_free_pages(pool) == 5);
+    CHECK(hr::pool_check_read(pool, 40, ids) == HR_OK);
+    CHECK(hr::pool_check_read(pool, 0, ids) == HR_ERR_LEN_RANGE);
     hr_model_cfg mc{2, 128, 4, 2, 64, 256, 100, 1, 2, HR_BF16, 10000.f, 1e-6f};
     int32_t table[2 * 3] = {1, 5, 7, 1, 5, -1};
     int32_t dls[2] = {40, 32}, qls[2] = {3, 2}, qt[5] = {1, 2, 3, 4, 99};

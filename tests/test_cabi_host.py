@@ -111,6 +111,26 @@ def test_doc_kv_write_validation_leaves_pool_unchanged():
     hb.lib.hr_kv_pool_destroy(h8)
 
 
+def test_doc_kv_read_validation():
+    _, h = make_pool(num_pages=8)
+    fake = C.c_void_p(FAKE_DEV)
+    ids = (C.c_int32 * 2)(0, 1)
+
+    def read(doc_len, pages, k=fake):
+        arr = (C.c_int32 * len(pages))(*pages)
+        return hb.lib.hr_doc_kv_read(h, doc_len, arr, k, fake, None, None, None)
+
+    assert hb.lib.hr_doc_kv_read(None, 16, ids, fake, fake, None, None, None) == hb.HR_ERR_INVALID_ARG
+    assert hb.lib.hr_doc_kv_read(h, 16, None, fake, fake, None, None, None) == hb.HR_ERR_INVALID_ARG
+    assert read(0, [0]) == hb.HR_ERR_LEN_RANGE
+    assert read(20, [0, 8]) == hb.HR_ERR_PAGE_RANGE
+    assert read(20, [0, 1]) == hb.HR_ERR_TABLE_SHORT                        # nothing has been written there
+    got = (C.c_int32 * 2)()
+    assert hb.lib.hr_kv_pool_alloc_pages(h, 2, got) == hb.HR_OK
+    assert read(20, list(got)) == hb.HR_ERR_TABLE_SHORT                     # reserved is not written
+    hb.lib.hr_kv_pool_destroy(h)
+
+
 def test_weights_pack_bytes_and_model_cfg_validation():
     m = wlmod.MODELS["qwen2_0p5b"]
     cfg = hb.make_model_cfg(m)

@@ -301,3 +301,78 @@ def test_shortened_last_layer_is_bit_identical(d, n_q, n_kv, kv, monkeypatch):
         finally:
             case.close()
     np.testing.assert_array_equal(scores[0], scores[1])
+
+
+@pytest.mark.parametrize("kv", ["f32", "bf16", "fp8"])
+def test_pool_read_back_is_the_inverse_of_write(kv):
+    """hr_doc_kv_read returns exactly what hr_doc_kv_write stored (bf16 values come back as the halves the pool keeps),
+    through permuted pages and a ragged last page; free or out-of-range pages are refused."""
+    import torch
+    from paper_2504_02921_amd import binding as hb
+    L, n_kv, d, D = 2, 2, 64, 37
+    pool = hb.KVPool(L, n_kv, d, 9, kv, "cuda:0")
+    pages = np.array([7, 2, 5], np.int32)
+    g = torch.Generator().manual_seed(3)
+    if kv == "fp8":
+        k = torch.randint(0, 0x7F, (L, D, n_kv, d), dtype=torch.uint8, generator=g).cuda()
+        v = torch.randint(0, 0x7F, (L, D, n_kv, d), dtype=torch.uint8, generator=g).cuda()
+        ks = torch.rand((L, 3, n_kv), generator=g).cuda() + 0.01
+        vs = torch.rand((L, 3, n_kv), generator=g).cuda() + 0.01
+        pool.write(D, pages, k, v, ks, vs)
+        rk, rv, rks, rvs = pool.read(D, pages)
+        torch.cuda.synchronize()
+        assert torch.equal(rk, k) and torch.equal(rv, v) and torch.equal(rks, ks) and torch.equal(rvs, vs)
+    else:
+        dt = torch.float32 if kv == "f32" else torch.bfloat16
+        k = torch.randn((L, D, n_kv, d), generator=g).to(dt).cuda()
+        v = torch.randn((L, D, n_kv, d), generator=g).to(dt).cuda()
+        pool.write(D, pages, k, v)
+        rk, rv = pool.read(D, pages)
+        torch.cuda.synchronize()
+        assert rk.dtype == (torch.float32 if kv == "f32" else torch.float16)
+        assert torch.equal(rk.float(), k.float()) and torch.equal(rv.float(), v.float())
+    with pytest.raises(hb.HrError) as e:
+        pool.read(D, np.array([7, 2, 3], np.int32))          # page 3 holds nothing
+    assert e.value.status == hb.HR_ERR_TABLE_SHORT
+    with pytest.raises(hb.HrError) as e:
+        pool.read(D, np.array([7, 2, 9], np.int32))
+    assert e.value.status == hb.HR_ERR_PAGE_RANGE
+    pool.close()
+
+
+@pytest.mark.parametrize("d,n_q,n_kv", [(64, 4, 2), (128, 4, 1)])
+def test_fp8_prefill_quantises_like_the_oracle(d, n_q, n_kv):
+    """Device prefill into an fp8 pool.  The same documents are prefilled into a 16-bit pool too and read back: those
+    halves are exactly what the fp8 path quantised, so the oracle's quantiser applied to them must reproduce every
+    code and every scale bit for bit; and scoring on the fp8 pool must match the oracle on (codes, scales)."""
+    import torch
+    from oracle import fp8 as ofp8
+    from paper_2504_02921_amd import binding as hb
+    model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=n_q, n_kv=n_kv, d=d, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("fp8_prefill", model, 2, 3, (1, 150), (2, 20), "fp8", seed=31 + d)
+    w = wlmod.SeededWeights(model, seed=17, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(cfg, spare_pages=2)
+    case = H.Case(wl, w)                                     # fp8 pool
+    pool16 = hb.KVPool(model.n_layers, model.n_kv_heads, model.head_dim, wl.num_pages, "bf16", "cuda:0")
+    uniq = sorted(set(int(x) for x in wl.pair_doc))
+    toks = [wl.doc_tokens(u) for u in uniq]
+    pages = [wl.pool_doc_pages[u] for u in uniq]
+    case.model.doc_prefill(case.pool, toks, pages)
+    case.model.doc_prefill(pool16, toks, pages)
+    torch.cuda.synchronize()
+    n_diff = 0
+    for u, pg in zip(uniq, pages):
+        D = int(wl.pool_doc_lens[u])
+        k16, v16 = pool16.read(D, pg)
+        kc, vc, ks, vs = case.pool.read(D, pg)
+        torch.cuda.synchronize()
+        for half, codes, scales in ((k16, kc, ks), (v16, vc, vs)):
+            want_c, want_s = ofp8.quantize_doc_kv(half.double().cpu().numpy())
+            np.testing.assert_array_equal(scales.cpu().numpy(), want_s)
+            n_diff += int((codes.cpu().numpy() != want_c).sum())
+        case.opool.write(pg, kc.cpu().numpy(), vc.cpu().numpy(), ks.cpu().numpy(), vs.cpu().numpy())
+        case.oracle_docs.add(u)
+    assert n_diff == 0, f"{n_diff} codes differ from the oracle's quantiser"
+    H.assert_scores_close(case.gpu_scores(), case.oracle_scores(), H.TOL["bf16"], "fp8 prefill + scoring pass")
+    pool16.close()
+    case.close()
