@@ -79,11 +79,17 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
     half_t* sA = (half_t*)smem;                         // [2][BM][BK]
     half_t* sB = sA + 2 * BM * BK;                      // [2][BN][BK]
 
+    // The gate/up launch is persistent: a workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the same
+    // XCD-chunked order) and requests the first k-tile of its next tile before it starts the epilogue of the current
+    // one, so only a workgroup's first tile pays the start-up round trip (3.4k of a 50k-cycle tile at K = 896).  Its
+    // epilogue has no loads that would queue behind that request.  The other launches run one tile per workgroup.
+    constexpr bool PERSIST = EPI == EPI_SWIGLU;
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (a.N + BN - 1) / BN;
-    TileCoord tc = map_tile(blockIdx.x, tiles_m, tiles_n);
+    int vpid = blockIdx.x;
+    TileCoord tc = map_tile(vpid, tiles_m, tiles_n);
     if (!tc.valid) return;
-    const int64_t m0 = (int64_t)tc.tm * BM;
-    const int n0 = tc.tn * BN;
+    int64_t m0;
+    int n0;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
@@ -97,18 +103,23 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
     const int lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
     const half_t* pa[PA];
     const half_t* pb[PB];
+    auto set_tile = [&](const TileCoord& t) {
+        m0 = (int64_t)t.tm * BM;
+        n0 = t.tn * BN;
 #pragma unroll
-    for (int p = 0; p < PA; ++p) {
-        int64_t r = m0 + p * RPP + lrow;
-        r = r < a.M ? r : a.M - 1;
-        pa[p] = A + r * K + lchunk * 8;
-    }
+        for (int p = 0; p < PA; ++p) {
+            int64_t r = m0 + p * RPP + lrow;
+            r = r < a.M ? r : a.M - 1;
+            pa[p] = A + r * K + lchunk * 8;
+        }
 #pragma unroll
-    for (int p = 0; p < PB; ++p) {
-        int r = n0 + p * RPP + lrow;
-        r = r < a.N ? r : a.N - 1;
-        pb[p] = W + (size_t)r * K + lchunk * 8;
-    }
+        for (int p = 0; p < PB; ++p) {
+            int r = n0 + p * RPP + lrow;
+            r = r < a.N ? r : a.N - 1;
+            pb[p] = W + (size_t)r * K + lchunk * 8;
+        }
+    };
+    set_tile(tc);
     auto dma = [&](int kt, int buf) {
         half_t* da = sA + buf * BM * BK + wave * 64 * 8;      // wave-uniform: the hardware adds 16 bytes per lane
         half_t* db = sB + buf * BN * BK + wave * 64 * 8;
@@ -121,12 +132,6 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
     };
 
     floatx16 acc[MI][NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     const int frow = lane & 31, fh = lane >> 5;
     const int a_row0 = wm * TM + frow;
@@ -159,6 +164,14 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
     const int nk = K / BK;
     HR_STAMP();
     dma(0, 0);
+    for (;;) {                                // one tile per pass; a single pass unless PERSIST
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    // k-tile 0 has landed; every wave is done with the previous tile's staging reads (PERSIST)
     __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
     __syncthreads();
     fload(0, sA, sB, 0);
@@ -194,6 +207,18 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
     // ---- epilogue: lane owns output row (lane & 31) of each block; register r holds column 8*(r>>2) + 4*(lane>>5) + (r&3)
     const int64_t row_base = m0 + wm * TM + frow;
     const int col_base = n0 + wn * TN + 4 * fh;
+    const int64_t tile_m0 = m0;               // the epilogue's tile; m0 / n0 move on to the next one below
+    const int tile_n0 = n0;
+    bool has_next = false;
+    if constexpr (PERSIST) {
+        vpid += (int)gridDim.x;
+        const TileCoord nx = map_tile(vpid, tiles_m, tiles_n);
+        has_next = nx.valid;
+        if (has_next) {
+            set_tile(nx);
+            dma(0, 0);                        // stage 0 of A and W: nobody reads LDS behind the loop's last barrier
+        }
+    }
     if constexpr (EPI == EPI_RESID_ADD) {
         // x += C through LDS.  In the accumulator layout a lane holds 16 bytes of one row, so a direct update touches
         // 32 rows per instruction; staged as an fp32 [BM][CW] tile (16-byte chunks XOR-swizzled by the row against
@@ -219,8 +244,8 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
                 for (int it = 0; it < G; ++it) {
                     const int L = (first + it) * NT + tid;
                     const int row = L / CPRW, pch = L % CPRW;
-                    int col = n0 + p * CW + ((pch ^ (row & 15)) << 2);
-                    int64_t grow = m0 + row;
+                    int col = tile_n0 + p * CW + ((pch ^ (row & 15)) << 2);
+                    int64_t grow = tile_m0 + row;
                     grow = grow < a.M ? grow : a.M - 1;
                     col = col < a.N ? col : a.N - 4;
                     xv[it] = *(const float4*)(a.x + grow * a.N + col);
@@ -231,8 +256,8 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
                 for (int it = 0; it < G; ++it) {
                     const int L = (first + it) * NT + tid;
                     const int row = L / CPRW, pch = L % CPRW;
-                    const int col = n0 + p * CW + ((pch ^ (row & 15)) << 2);
-                    const int64_t grow = m0 + row;
+                    const int col = tile_n0 + p * CW + ((pch ^ (row & 15)) << 2);
+                    const int64_t grow = tile_m0 + row;
                     if (grow >= a.M || col >= a.N) continue;        // N is a multiple of 8: whole chunks
                     const float4 c = *(const float4*)(stage + row * CW + (pch << 2));
                     float4 v = xv[it];
@@ -281,7 +306,10 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
         constexpr int ITER = BM * CPRO / NT;
         static_assert(EPI != EPI_SWIGLU || ((CPRO == 16 || CPRO == 8) && (BM * CPRO) % NT == 0), "output tile shape");
         auto swz = [](int r) { return CPRO == 16 ? (r & 15) : ((r >> 1) & 7); };
-        half_t* stage = (half_t*)smem;
+        // staged in the second stages of A and W: the first ones may already be receiving the next tile
+        constexpr int R1 = BM * BK / OW;                 // tile rows that fit the A stage
+        static_assert(EPI != EPI_SWIGLU || (R1 <= BM && (BM - R1) * OW <= BN * BK), "staging fits the second stages");
+        auto stage_row = [&](int r) { return r < R1 ? sA + BM * BK + r * OW : sB + BN * BK + (r - R1) * OW; };
         half_t* out = (half_t*)a.out0;
         const int F = a.N / 2;
 #pragma unroll
@@ -299,18 +327,19 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
                         const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
                         w[e] = from_float<half_t>(g * sg * u);
                     }
-                    *(halfx4*)(stage + lr * OW + ((ch ^ swz(lr)) << 3) + 4 * fh) = w;
+                    *(halfx4*)(stage_row(lr) + ((ch ^ swz(lr)) << 3) + 4 * fh) = w;
                 }
         }
-        __syncthreads();
+        // LDS-only barrier: __syncthreads() would also wait for the next tile's loads, which were just requested
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #pragma unroll
         for (int it = 0; it < ITER; ++it) {
             const int L = it * NT + tid;
             const int row = L / CPRO, pch = L % CPRO;
-            const int col = n0 / 2 + ((pch ^ swz(row)) << 3);
-            const int64_t grow = m0 + row;
+            const int col = tile_n0 / 2 + ((pch ^ swz(row)) << 3);
+            const int64_t grow = tile_m0 + row;
             if (grow >= a.M || col >= F) continue;          // F is a multiple of 32: whole chunks
-            *(uint4v*)(out + grow * F + col) = *(const uint4v*)(stage + row * OW + (pch << 3));
+            *(uint4v*)(out + grow * F + col) = *(const uint4v*)(stage_row(row) + (pch << 3));
         }
     } else {   // EPI_QKV_ROPE
         constexpr int hb = HB;                                  // 32-wide blocks per half head: head_dim = 64 * HB
@@ -330,7 +359,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
             for (int base = 0; base < BM * CPR; base += NT) {
                 const int L = base + tid;
                 const int row = L / CPR, pc = L % CPR;
-                int64_t gr = m0 + row;
+                int64_t gr = tile_m0 + row;
                 gr = gr < a.M ? gr : a.M - 1;
                 const char* g = rope_bytes + (gr * half) * (int64_t)sizeof(float2) + ((pc ^ (row & 15)) << 4);
                 __builtin_amdgcn_global_load_lds((gbl_ptr_t)g, (lds_ptr_t)(smem + (size_t)(base + wave * 64) * 16), 16, 0, 0);
@@ -403,13 +432,25 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
         }
     }
     HR_STAMP();
+    if (!has_next) break;
+    }
 }
+
+int cu_count();
+int tuning_variant();
 
 template <int EPI, int BM, int BN, int WM, int WN, int HB>
 hipError_t launch_tile(const GemmArgs& a, hipStream_t st) {
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (a.N + BN - 1) / BN;
     const int n_tiles = tiles_m * tiles_n;
     const int per_xcd = (n_tiles + kXcds - 1) / kXcds;
+    int grid = per_xcd * kXcds;
+    if (EPI == EPI_SWIGLU && tuning_variant() != 5) {
+        // persistent launch: as many workgroups as are resident at once (one big or two small tiles per CU), a multiple
+        // of the XCD count so that the walk blockIdx.x + k * gridDim.x stays on its XCD
+        const int resident = cu_count() * (BM >= 256 ? 1 : 2) / kXcds * kXcds;
+        if (resident >= kXcds && grid > resident) grid = resident;
+    }
     const size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(half_t);
     static bool attr_set = false;
     if (!attr_set) {
@@ -418,7 +459,7 @@ hipError_t launch_tile(const GemmArgs& a, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    gemm_mfma_kernel<EPI, BM, BN, WM, WN, HB><<<dim3((unsigned)(per_xcd * kXcds)), WM * WN * 64, lds, st>>>(a);
+    gemm_mfma_kernel<EPI, BM, BN, WM, WN, HB><<<dim3((unsigned)grid), WM * WN * 64, lds, st>>>(a);
     return hipGetLastError();
 }
 
