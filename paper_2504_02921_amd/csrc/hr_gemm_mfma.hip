@@ -18,6 +18,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
+#include <type_traits>
 
 #include "hr_device_types.h"
 #include "hr_kernels.h"
@@ -56,169 +57,24 @@ __device__ __forceinline__ TileCoord map_tile(int pid, int tiles_m, int tiles_n)
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
-// BM x BN x 64 macro tile, WM x WN wavefronts, each wave (BM/WM) x (BN/WN) = MI x NI blocks of 32 x 32.
-//
-// Data path: global_load_lds_dwordx4 (HBM/L2 -> LDS without passing through VGPRs; lane l of a wave
-// writes LDS bytes [base + 16 l, base + 16 l + 16)), two LDS stages.  The loads of k-tile kt + 1 are
-// issued at the top of iteration kt and waited for just before the last k-step of the iteration,
-// where the only workgroup barrier of the iteration sits; the fragments of the next k-step are read
-// one step ahead and the scheduler is pinned to alternate one ds_read with one MFMA.
-// Accumulation is transposed (D = W_frag * A_frag^T): a lane owns ONE output row (lane & 31) and
-// 4 consecutive columns per register quad, so the epilogues address one row pointer per block and
-// store 8 / 16 bytes at a time.
+// Epilogues on transposed accumulators: a lane owns output row (lane & 31) of each 32 x 32 block, register r holds
+// column 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3).  `smem` is the kernel's LDS (two stages of A, then two of W), free
+// behind the main loop's last barrier except that, in a persistent launch, stage 0 may be receiving the next tile.
 template <int EPI, int BM, int BN, int WM, int WN, int HB>
-__global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
+__device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BM / WM / 32][BN / WN / 32], const GemmArgs& a, char* smem,
+                                              int64_t tile_m0, int tile_n0) {
     constexpr int NT = WM * WN * 64;
-    constexpr int TM = BM / WM, TN = BN / WN;      // wave tile
+    constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 32, NI = TN / 32;
-    constexpr int RPP = NT / 8;                     // rows per loader pass (8 lanes cover one 128-byte k row)
-    constexpr int PA = BM / RPP, PB = BN / RPP;
-    constexpr int KS = BK / 16;
-    static_assert(RPP % 16 == 0 && BM % RPP == 0 && BN % RPP == 0, "loader shape");
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    half_t* sA = (half_t*)smem;                         // [2][BM][BK]
-    half_t* sB = sA + 2 * BM * BK;                      // [2][BN][BK]
-
-    // The gate/up launch is persistent: a workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the same
-    // XCD-chunked order) and requests the first k-tile of its next tile before it starts the epilogue of the current
-    // one, so only a workgroup's first tile pays the start-up round trip (3.4k of a 50k-cycle tile at K = 896).  Its
-    // epilogue has no loads that would queue behind that request.  The other launches run one tile per workgroup.
-    constexpr bool PERSIST = EPI == EPI_SWIGLU;
-    const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (a.N + BN - 1) / BN;
-    int vpid = blockIdx.x;
-    TileCoord tc = map_tile(vpid, tiles_m, tiles_n);
-    if (!tc.valid) return;
-    int64_t m0;
-    int n0;
+    half_t* sA = (half_t*)smem;
+    half_t* sB = sA + 2 * BM * BK;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int K = a.K;
-    const half_t* A = (const half_t*)a.A;
-    const half_t* W = (const half_t*)a.W;
-
-    // loader: lane -> LDS chunk (row lrow of the pass, physical 16-byte chunk tid & 7); it fetches the logical
-    // chunk that the row-pair swizzle maps there
-    const int lrow = tid >> 3;
-    const int lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
-    const half_t* pa[PA];
-    const half_t* pb[PB];
-    auto set_tile = [&](const TileCoord& t) {
-        m0 = (int64_t)t.tm * BM;
-        n0 = t.tn * BN;
-#pragma unroll
-        for (int p = 0; p < PA; ++p) {
-            int64_t r = m0 + p * RPP + lrow;
-            r = r < a.M ? r : a.M - 1;
-            pa[p] = A + r * K + lchunk * 8;
-        }
-#pragma unroll
-        for (int p = 0; p < PB; ++p) {
-            int r = n0 + p * RPP + lrow;
-            r = r < a.N ? r : a.N - 1;
-            pb[p] = W + (size_t)r * K + lchunk * 8;
-        }
-    };
-    set_tile(tc);
-    auto dma = [&](int kt, int buf) {
-        half_t* da = sA + buf * BM * BK + wave * 64 * 8;      // wave-uniform: the hardware adds 16 bytes per lane
-        half_t* db = sB + buf * BN * BK + wave * 64 * 8;
-#pragma unroll
-        for (int p = 0; p < PA; ++p)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pa[p] + kt * BK), (lds_ptr_t)(da + p * NT * 8), 16, 0, 0);
-#pragma unroll
-        for (int p = 0; p < PB; ++p)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pb[p] + kt * BK), (lds_ptr_t)(db + p * NT * 8), 16, 0, 0);
-    };
-
-    floatx16 acc[MI][NI];
-
     const int frow = lane & 31, fh = lane >> 5;
-    const int a_row0 = wm * TM + frow;
-    const int b_row0 = wn * TN + frow;
-    const int sw = (frow >> 1) & 7;           // row pair index: rows are 128 bytes, the bank window 256
-
-    halfx8 af[2][MI], bfr[2][NI];             // fragment double buffer
-    auto fload = [&](int slot, const half_t* cA, const half_t* cB, int kk) {
-        const int pch = ((kk * 2 + fh) ^ sw) * 8;
-#pragma unroll
-        for (int i = 0; i < MI; ++i) af[slot][i] = *(const halfx8*)(cA + (a_row0 + i * 32) * BK + pch);
-#pragma unroll
-        for (int j = 0; j < NI; ++j) bfr[slot][j] = *(const halfx8*)(cB + (b_row0 + j * 32) * BK + pch);
-    };
-    auto mfmas = [&](int slot) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bfr[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
-    };
-
-#ifdef HR_GEMM_TRACE
-    long long* trace = (blockIdx.x == 8 && tid == 0) ? (long long*)a.out2 : nullptr;   // out2 is unused outside the QKV epilogue
-    int tp = 0;
-#define HR_STAMP() do { if (trace) trace[tp++] = __builtin_readcyclecounter(); } while (0)
-#else
-#define HR_STAMP() do { } while (0)
-#endif
-    const int nk = K / BK;
-    HR_STAMP();
-    dma(0, 0);
-    for (;;) {                                // one tile per pass; a single pass unless PERSIST
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    // k-tile 0 has landed; every wave is done with the previous tile's staging reads (PERSIST)
-    __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
-    __syncthreads();
-    fload(0, sA, sB, 0);
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < nk;
-        HR_STAMP();
-        if (more) dma(kt + 1, cur ^ 1);
-        const half_t* cA = sA + cur * BM * BK;
-        const half_t* cB = sB + cur * BN * BK;
-#pragma unroll
-        for (int kk = 0; kk < KS - 1; ++kk) {
-            fload((kk + 1) & 1, cA, cB, kk + 1);
-            mfmas(kk & 1);
-#pragma unroll
-            for (int n = 0; n < MI + NI; ++n) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI), 0);
-        }
-        HR_STAMP();
-        // the next k-tile has landed (own loads) and every wave is past its last read of the other stage
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        HR_STAMP();
-        if (more) fload(KS & 1, sA + (cur ^ 1) * BM * BK, sB + (cur ^ 1) * BN * BK, 0);
-        mfmas((KS - 1) & 1);
-        static_assert(KS % 2 == 0, "slot parity of the first fragment of a tile");
-    }
-
-    HR_STAMP();
-    // ---- epilogue: lane owns output row (lane & 31) of each block; register r holds column 8*(r>>2) + 4*(lane>>5) + (r&3)
-    const int64_t row_base = m0 + wm * TM + frow;
-    const int col_base = n0 + wn * TN + 4 * fh;
-    const int64_t tile_m0 = m0;               // the epilogue's tile; m0 / n0 move on to the next one below
-    const int tile_n0 = n0;
-    bool has_next = false;
-    if constexpr (PERSIST) {
-        vpid += (int)gridDim.x;
-        const TileCoord nx = map_tile(vpid, tiles_m, tiles_n);
-        has_next = nx.valid;
-        if (has_next) {
-            set_tile(nx);
-            dma(0, 0);                        // stage 0 of A and W: nobody reads LDS behind the loop's last barrier
-        }
-    }
+    const int64_t row_base = tile_m0 + wm * TM + frow;
+    const int col_base = tile_n0 + wn * TN + 4 * fh;
+    (void)sA; (void)sB; (void)row_base; (void)col_base; (void)NT; (void)MI; (void)NI;
     if constexpr (EPI == EPI_RESID_ADD) {
         // x += C through LDS.  In the accumulator layout a lane holds 16 bytes of one row, so a direct update touches
         // 32 rows per instruction; staged as an fp32 [BM][CW] tile (16-byte chunks XOR-swizzled by the row against
@@ -431,6 +287,170 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
                 }
         }
     }
+}
+
+// BM x BN x 64 macro tile, WM x WN wavefronts, each wave (BM/WM) x (BN/WN) = MI x NI blocks of 32 x 32.
+//
+// Data path: global_load_lds_dwordx4 (HBM/L2 -> LDS without passing through VGPRs; lane l of a wave
+// writes LDS bytes [base + 16 l, base + 16 l + 16)), two LDS stages.  The loads of k-tile kt + 1 are
+// issued at the top of iteration kt and waited for just before the last k-step of the iteration,
+// where the only workgroup barrier of the iteration sits; the fragments of the next k-step are read
+// one step ahead and the scheduler is pinned to alternate one ds_read with one MFMA.
+// Accumulation is transposed (D = W_frag * A_frag^T): a lane owns ONE output row (lane & 31) and
+// 4 consecutive columns per register quad, so the epilogues address one row pointer per block and
+// store 8 / 16 bytes at a time.
+template <int EPI, int BM, int BN, int WM, int WN, int HB>
+__global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM, TN = BN / WN;      // wave tile
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int RPP = NT / 8;                     // rows per loader pass (8 lanes cover one 128-byte k row)
+    constexpr int PA = BM / RPP, PB = BN / RPP;
+    constexpr int KS = BK / 16;
+    static_assert(RPP % 16 == 0 && BM % RPP == 0 && BN % RPP == 0, "loader shape");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    half_t* sA = (half_t*)smem;                         // [2][BM][BK]
+    half_t* sB = sA + 2 * BM * BK;                      // [2][BN][BK]
+
+    // The gate/up launch is persistent: a workgroup walks tiles blockIdx.x, blockIdx.x + gridDim.x, ... (the same
+    // XCD-chunked order) and requests the first k-tile of its next tile before it starts the epilogue of the current
+    // one, so only a workgroup's first tile pays the start-up round trip (3.4k of a 50k-cycle tile at K = 896).  Its
+    // epilogue has no loads that would queue behind that request.  The other launches run one tile per workgroup.
+    constexpr bool PERSIST = EPI == EPI_SWIGLU;
+    const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (a.N + BN - 1) / BN;
+    int vpid = blockIdx.x;
+    TileCoord tc = map_tile(vpid, tiles_m, tiles_n);
+    if (!tc.valid) return;
+    int64_t m0;
+    int n0;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int K = a.K;
+    const half_t* A = (const half_t*)a.A;
+    const half_t* W = (const half_t*)a.W;
+
+    // loader: lane -> LDS chunk (row lrow of the pass, physical 16-byte chunk tid & 7); it fetches the logical
+    // chunk that the row-pair swizzle maps there
+    const int lrow = tid >> 3;
+    const int lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
+    const half_t* pa[PA];
+    const half_t* pb[PB];
+    auto set_tile = [&](const TileCoord& t) {
+        m0 = (int64_t)t.tm * BM;
+        n0 = t.tn * BN;
+#pragma unroll
+        for (int p = 0; p < PA; ++p) {
+            int64_t r = m0 + p * RPP + lrow;
+            r = r < a.M ? r : a.M - 1;
+            pa[p] = A + r * K + lchunk * 8;
+        }
+#pragma unroll
+        for (int p = 0; p < PB; ++p) {
+            int r = n0 + p * RPP + lrow;
+            r = r < a.N ? r : a.N - 1;
+            pb[p] = W + (size_t)r * K + lchunk * 8;
+        }
+    };
+    set_tile(tc);
+    auto dma = [&](int kt, int buf) {
+        half_t* da = sA + buf * BM * BK + wave * 64 * 8;      // wave-uniform: the hardware adds 16 bytes per lane
+        half_t* db = sB + buf * BN * BK + wave * 64 * 8;
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pa[p] + kt * BK), (lds_ptr_t)(da + p * NT * 8), 16, 0, 0);
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pb[p] + kt * BK), (lds_ptr_t)(db + p * NT * 8), 16, 0, 0);
+    };
+
+    floatx16 acc[MI][NI];
+
+    const int frow = lane & 31, fh = lane >> 5;
+    const int a_row0 = wm * TM + frow;
+    const int b_row0 = wn * TN + frow;
+    const int sw = (frow >> 1) & 7;           // row pair index: rows are 128 bytes, the bank window 256
+
+    halfx8 af[2][MI], bfr[2][NI];             // fragment double buffer
+    auto fload = [&](int slot, const half_t* cA, const half_t* cB, int kk) {
+        const int pch = ((kk * 2 + fh) ^ sw) * 8;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[slot][i] = *(const halfx8*)(cA + (a_row0 + i * 32) * BK + pch);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) bfr[slot][j] = *(const halfx8*)(cB + (b_row0 + j * 32) * BK + pch);
+    };
+    auto mfmas = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bfr[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
+    };
+
+#ifdef HR_GEMM_TRACE
+    long long* trace = (blockIdx.x == 8 && tid == 0) ? (long long*)a.out2 : nullptr;   // out2 is unused outside the QKV epilogue
+    int tp = 0;
+#define HR_STAMP() do { if (trace) trace[tp++] = __builtin_readcyclecounter(); } while (0)
+#else
+#define HR_STAMP() do { } while (0)
+#endif
+    const int nk = K / BK;
+    HR_STAMP();
+    dma(0, 0);
+    for (;;) {                                // one tile per pass; a single pass unless PERSIST
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    // k-tile 0 has landed; every wave is done with the previous tile's staging reads (PERSIST)
+    __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
+    __syncthreads();
+    fload(0, sA, sB, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nk;
+        HR_STAMP();
+        if (more) dma(kt + 1, cur ^ 1);
+        const half_t* cA = sA + cur * BM * BK;
+        const half_t* cB = sB + cur * BN * BK;
+#pragma unroll
+        for (int kk = 0; kk < KS - 1; ++kk) {
+            fload((kk + 1) & 1, cA, cB, kk + 1);
+            mfmas(kk & 1);
+#pragma unroll
+            for (int n = 0; n < MI + NI; ++n) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI), 0);
+        }
+        HR_STAMP();
+        // the next k-tile has landed (own loads) and every wave is past its last read of the other stage
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        HR_STAMP();
+        if (more) fload(KS & 1, sA + (cur ^ 1) * BM * BK, sB + (cur ^ 1) * BN * BK, 0);
+        mfmas((KS - 1) & 1);
+        static_assert(KS % 2 == 0, "slot parity of the first fragment of a tile");
+    }
+
+    HR_STAMP();
+    // ---- epilogue: lane owns output row (lane & 31) of each block; register r holds column 8*(r>>2) + 4*(lane>>5) + (r&3)
+    const int64_t tile_m0 = m0;               // the epilogue's tile; m0 / n0 move on to the next one below
+    const int tile_n0 = n0;
+    bool has_next = false;
+    if constexpr (PERSIST) {
+        vpid += (int)gridDim.x;
+        const TileCoord nx = map_tile(vpid, tiles_m, tiles_n);
+        has_next = nx.valid;
+        if (has_next) {
+            set_tile(nx);
+            dma(0, 0);                        // stage 0 of A and W: nobody reads LDS behind the loop's last barrier
+        }
+    }
+    gemm_epilogue<EPI, BM, BN, WM, WN, HB>(acc, a, smem, tile_m0, tile_n0);
     HR_STAMP();
     if (!has_next) break;
     }
