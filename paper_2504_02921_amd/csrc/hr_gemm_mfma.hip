@@ -229,34 +229,28 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BM / WM / 32][BN /
         }
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        // store one quad (4 consecutive columns of one row), already rotated and rounded
-        auto store_quad = [&](int i, int64_t row, int col, halfx4 w) {
-            if (col < nq) {
-                *(halfx4*)((half_t*)a.out0 + row * nq + col) = w;
-                return;
-            }
-            const bool is_v = col >= nq + nkv;
-            const int c_all = col - nq - (is_v ? nkv : 0);
+        // q and K quads are kept (rotated and rounded) until the table is no longer needed, then staged in LDS as a
+        // half [BM][BN] tile and stored in whole row segments; V quads go straight to their pages: a lane's 32 tokens
+        // fall into two pages, where each channel's keys are adjacent, which is as coalesced as V gets.
+        halfx4 res[MI][NI][4];
+        auto store_v_quad = [&](int i, int64_t row, int col, halfx4 w) {
+            const int c_all = col - nq - nkv;
             if (!a.kv_pages) {
-                *(halfx4*)((half_t*)(is_v ? a.out2 : a.out1) + row * nkv + c_all) = w;
+                *(halfx4*)((half_t*)a.out2 + row * nkv + c_all) = w;
                 return;
             }
             // 16-slot pages in the pool arrangement: [page][kv head][K block | V block]
             const int kv_head = c_all / d, kv_c = c_all - kv_head * d;
             const int slot = slot_i[i];
-            half_t* blk0 = (half_t*)a.kv_pages + ((size_t)(slot >> 4) * a.n_kv + kv_head) * (2 * kPageTokens * d);
+            half_t* vb = (half_t*)a.kv_pages + ((size_t)(slot >> 4) * a.n_kv + kv_head) * (2 * kPageTokens * d) + kPageTokens * d;
             const int t = slot & 15;
-            if (!is_v) *(halfx4*)(blk0 + k_elem(t, kv_c, d, 2)) = w;
-            else {
-                half_t* vb = blk0 + kPageTokens * d;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) vb[v_elem(t, kv_c + e, d)] = w[e];
-            }
+            for (int e = 0; e < 4; ++e) vb[v_elem(t, kv_c + e, d)] = w[e];
         };
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             const int64_t row = row_base + i * 32;
-            if (row >= a.M) continue;
+            const bool row_ok = row < a.M;
             const int lrow = wm * TM + i * 32 + frow;              // row inside the tile
             const char* trow = smem + (size_t)lrow * (CPR * 16);
 #pragma unroll
@@ -272,7 +266,6 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BM / WM / 32][BN /
                     for (int hd = 0; hd < NI / (2 * hb); ++hd) {
                         const int jl = hd * 2 * hb + hbi, jh = jl + hb;       // low / high half of the head: same lane, same register
                         const int col_l = col_base + jl * 32 + 8 * r4, col_h = col_base + jh * 32 + 8 * r4;
-                        if (col_l >= a.N) continue;                             // N is a multiple of the head size
                         const bool rot = col_l < nq + nkv;                      // q and k rotate, v does not
                         halfx4 wl, wh;
 #pragma unroll
@@ -281,10 +274,49 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BM / WM / 32][BN /
                             wl[e] = from_float<half_t>(rot ? lo * cs_c[e] - hi * cs_s[e] : lo);
                             wh[e] = from_float<half_t>(rot ? hi * cs_c[e] + lo * cs_s[e] : hi);
                         }
-                        store_quad(i, row, col_l, wl);
-                        store_quad(i, row, col_h, wh);
+                        res[i][jl][r4] = wl;
+                        res[i][jh][r4] = wh;
+                        if (!rot && row_ok && col_l < a.N) {                  // N is a multiple of the head size
+                            store_v_quad(i, row, col_l, wl);
+                            store_v_quad(i, row, col_h, wh);
+                        }
                     }
                 }
+        }
+        __syncthreads();                                            // every lane is done with the table
+        constexpr int CPT = BN / 8;                                 // 16-byte chunks per tile row (16 or 32)
+        static_assert(EPI != EPI_QKV_ROPE || (CPT % 16 == 0 && (BM * CPT) % NT == 0), "output tile shape");
+        half_t* stage = (half_t*)smem;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int lr = wm * TM + i * 32 + frow;
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int ch = (wn * TN + j * 32) / 8 + r4;
+                    *(halfx4*)(stage + lr * BN + ((ch ^ (lr & 15)) << 3) + 4 * fh) = res[i][j][r4];
+                }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < BM * CPT / NT; ++it) {
+            const int L = it * NT + tid;
+            const int row = L / CPT, pch = L % CPT;
+            const int col = tile_n0 + ((pch ^ (row & 15)) << 3);
+            const int64_t grow = tile_m0 + row;
+            if (grow >= a.M || col >= nq + nkv) continue;           // past the matrix, or V (stored above)
+            const uint4v w = *(const uint4v*)(stage + row * BN + (pch << 3));
+            if (col < nq) {
+                *(uint4v*)((half_t*)a.out0 + grow * nq + col) = w;
+            } else if (!a.kv_pages) {
+                *(uint4v*)((half_t*)a.out1 + grow * nkv + (col - nq)) = w;
+            } else {
+                const int c_all = col - nq, kv_head = c_all / d, kv_c = c_all - kv_head * d;
+                const int slot = a.new_slot[grow];
+                half_t* blk0 = (half_t*)a.kv_pages + ((size_t)(slot >> 4) * a.n_kv + kv_head) * (2 * kPageTokens * d);
+                *(uint4v*)(blk0 + k_elem(slot & 15, kv_c, d, 2)) = w;   // 8 channels = one swizzled 16-byte chunk
+            }
         }
     }
 }
