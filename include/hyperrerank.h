@@ -185,7 +185,10 @@ size_t hr_rerank_workspace_bytes(const hr_model* model, int32_t n_pairs, int64_t
  *   workspace_dev device scratch, >= hr_rerank_workspace_bytes, 256-byte aligned, private to this
  *                 call until `stream` has drained
  *   scores_dev    device fp32 [n_pairs]
- * The pool is only read.  Host arrays may be reused as soon as the call returns. */
+ * The pool is only read.  Host arrays may be reused as soon as the call returns.
+ * Pairs of one call whose doc_lens and page-table rows are identical (the same cached document: Section 3.3,
+ * pairwise independence makes a document's KV reusable for every query) share one pass over its pages in the
+ * attention kernels; the scores are bit for bit those of the pairs scored alone. */
 int hr_rerank_score(hr_model* model, const hr_pool* pool, int32_t n_pairs,
                     const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
                     const int32_t* query_tokens, const int32_t* query_lens,

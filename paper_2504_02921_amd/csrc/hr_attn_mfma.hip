@@ -1,12 +1,14 @@
 // Paged grouped-query prefix attention on MFMA (gfx950): the KV-streaming kernel of the scoring pass.
 //
-// One workgroup per (pair, kv head).  Its query rows are the g * q_len rows (token i, head a of the
-// group) that share this kv head; wave w owns 32-row blocks w, w + NW, ...  The document's pages are
+// One work item per (pair, kv head), or per (group of pairs that share a document, kv head).  Its query
+// rows are the g * q_len rows (token i, head a of the group) of every pair in it that share this kv
+// head, cut into 32-row blocks (a pair starts a new block); wave w owns blocks w, w + NW, ...  The document's pages are
 // streamed HBM -> LDS in 32 KiB stages (double buffered, every page is one contiguous burst and is
 // copied verbatim: the pool already holds the LDS-friendly arrangement), all keys of the document are
-// visible to every row; then the pair's own query keys, which the QKV projection wrote as pages of the
-// same arrangement, follow in the same stream and are processed with the causal mask.  Softmax is the
-// online form in fp32.
+// visible to every row; then each pair's own query keys, which the QKV projection wrote as pages of the
+// same arrangement, follow in the same stream and are processed with the causal mask by the blocks of
+// that pair.  Softmax is the online form in fp32.  A row's arithmetic does not depend on which block or
+// work item carries it: grouped and ungrouped runs give the same bits.
 //
 // MFMA orientation (v_mfma_f32_32x32x16_f16): scores are computed transposed, S^T = K * Q^T, so a
 // lane owns ONE query row (column lane & 31) and 16 of the 32 keys of a sub-tile.  Row maxima and
@@ -85,12 +87,13 @@ __device__ __forceinline__ halfx2 fp8_expand_factor(float scale) {
     return halfx2{f, f};
 }
 
-// What a workgroup needs to know about one work item = (pair, kv head)
+// What a workgroup needs to know about one work item = (pair or group of pairs with one document, kv head)
 struct ItemCtx {
-    int p, h, t0, qn, D, n_pages, n_tiles, nq_pages, n_new_tiles;
+    int p0, h, D, n_pages, n_tiles;
+    int blk0, n_blk;              // 32-row blocks (grouped: a range of the plan's block arrays)
+    int sub0, n_sub, n_new_tiles; // 32-key sub-tiles of the pairs' own keys, and the stages they fill
     const int32_t* pt;        // page-table row
     const char* layer_base;   // pool address of page 0 for this (layer, kv head)
-    const char* new_base;     // first page of the pair's own K/V
 };
 
 template <int HD, int NW, int R, bool FP8>
@@ -98,7 +101,11 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                                                            half_t* __restrict__ o, MetaView mv, PoolView pv, int layer, int n_q,
                                                            const int32_t* __restrict__ m_cu, const int32_t* __restrict__ m_prefix,
                                                            const int32_t* __restrict__ m_pt, const int32_t* __restrict__ m_new_cu,
-                                                           const float* __restrict__ p_scales, int last_only) {
+                                                           const float* __restrict__ p_scales, int last_only, int n_groups,
+                                                           const int32_t* __restrict__ g_p0, const int32_t* __restrict__ g_blk_cu,
+                                                           const int32_t* __restrict__ g_sub_cu, const int32_t* __restrict__ g_blk_seq,
+                                                           const int32_t* __restrict__ g_blk_row0, const int32_t* __restrict__ g_sub_page,
+                                                           const int32_t* __restrict__ g_sub_seq, const int32_t* __restrict__ g_sub_key0) {
     // The metadata arrays come as separate read-only, non-aliased parameters so that the per-item lookups (uniform
     // over the workgroup) compile to scalar loads: a vector load that is used right away makes the wave wait for
     // everything it has in flight, including the stage it requested a moment earlier, because vector memory
@@ -134,23 +141,57 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     const float c_log2 = 1.4426950408889634f / sqrtf((float)HD);
     const size_t page_stride = (size_t)n_kv * G::PAGE_BYTES;                         // between consecutive page ids
-    const int n_items = mv.n_seq * n_kv;
+    const bool grouped = n_groups > 0;
+    const int n_items = (grouped ? n_groups : mv.n_seq) * n_kv;
+    constexpr int SUBS = GN::TK / 32;                // sub-tiles of the pairs' own keys per stage
 
     auto load_ctx = [&](int item) {
         ItemCtx c;
-        c.p = item / n_kv;
-        c.h = item - c.p * n_kv;
-        c.t0 = m_cu[c.p];
-        c.qn = m_cu[c.p + 1] - c.t0;
-        c.D = m_prefix[c.p];
+        const int gi = item / n_kv;
+        c.h = item - gi * n_kv;
+        if (grouped) {
+            c.p0 = g_p0[gi];
+            c.blk0 = g_blk_cu[gi];
+            c.n_blk = g_blk_cu[gi + 1] - c.blk0;
+            c.sub0 = g_sub_cu[gi];
+            c.n_sub = g_sub_cu[gi + 1] - c.sub0;
+        } else {
+            c.p0 = gi;
+            const int qn = m_cu[gi + 1] - m_cu[gi];
+            c.blk0 = 0;
+            c.n_blk = ((last_only ? g : qn * g) + 31) / 32;
+            c.sub0 = 0;
+            c.n_sub = (qn + 31) / 32;
+        }
+        c.D = m_prefix[c.p0];
         c.n_pages = (c.D + kPageTokens - 1) / kPageTokens;
         c.n_tiles = (c.n_pages + G::PPS - 1) / G::PPS;
-        c.nq_pages = ((c.qn + 31) / 32) * 2;                    // whole 32-key sub-tiles
-        c.n_new_tiles = (c.nq_pages + GN::PPS - 1) / GN::PPS;
-        c.pt = m_pt + (size_t)c.p * mv.pt_stride;
+        c.n_new_tiles = (c.n_sub + SUBS - 1) / SUBS;
+        c.pt = m_pt + (size_t)c.p0 * mv.pt_stride;
         c.layer_base = pv.data + ((size_t)layer * pv.num_pages * n_kv + c.h) * G::PAGE_BYTES;
-        c.new_base = kv_new + ((size_t)(m_new_cu[c.p] >> 4) * n_kv + c.h) * GN::PAGE_BYTES;
         return c;
+    };
+    // block b of an item: whose rows, and which of them (uniform over the wave)
+    auto blk_lookup = [&](const ItemCtx& c, int b, int& seq, int& row0) {
+        if (grouped) {
+            seq = g_blk_seq[c.blk0 + b];
+            row0 = g_blk_row0[c.blk0 + b];
+        } else {
+            seq = c.p0;
+            row0 = b * 32;
+        }
+    };
+    // sub-tile s of an item's own keys: first of its two pages in the new-KV buffer, the pair, its first key
+    auto sub_lookup = [&](const ItemCtx& c, int s, int& page, int& seq, int& key0) {
+        if (grouped) {
+            page = g_sub_page[c.sub0 + s];
+            seq = g_sub_seq[c.sub0 + s];
+            key0 = g_sub_key0[c.sub0 + s];
+        } else {
+            page = (m_new_cu[c.p0] >> 4) + 2 * s;
+            seq = c.p0;
+            key0 = 32 * s;
+        }
     };
 
     // ---- KV stream: the document's pages, then the pair's own (causal) keys, which the QKV projection has already
@@ -193,9 +234,11 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
         for (int ps = 0; ps < NPASS; ++ps) {
             const int off = ps * NT * 16 + wave_u * 1024;      // whole waves stay inside one page
             const int slot = off / GN::PAGE_BYTES, within = off - slot * GN::PAGE_BYTES + lane * 16;
-            const int pgi = nt * GN::PPS + slot;
-            if (pgi < c.nq_pages) {                            // wave-uniform
-                const char* src = c.new_base + (size_t)pgi * n_kv * GN::PAGE_BYTES + within;
+            const int s = nt * SUBS + (slot >> 1);
+            if (s < c.n_sub) {                                 // wave-uniform
+                int page, seq, key0;
+                sub_lookup(c, s, page, seq, key0);
+                const char* src = kv_new + ((size_t)(page + (slot & 1)) * n_kv + c.h) * GN::PAGE_BYTES + within;
                 __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(dst + ps * NT * 16), 16, 0, 0);
             }
         }
@@ -232,7 +275,9 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     bool row_ok[R];
     floatx16 oacc[R][MB];
     float m_run[R], l_run[R];
-    int M = 0;             // query rows of the current work item
+    bool blk_on[R];        // the wave's block rb exists in the current work item   (these three: uniform over the wave)
+    int blk_seq[R];        // ... and belongs to this pair
+    int blk_qn[R];         // ... which has this many query tokens
 
     // fp8 pools: the stage that has just landed is expanded to half pages once, by all threads together (8 codes
     // per step and thread), instead of by every wave for its own fragments: the conversions are the largest
@@ -262,7 +307,8 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     // Order: K fragments -> S = K Q^T for all row blocks -> V^T fragments (K registers are dead by then, the
     // LDS latency hides under the softmax) -> softmax -> O^T += V^T P^T.
     // `sb` holds half pages; scaled_tag: they were expanded from fp8 codes and `sc` carries the pages' scales.
-    auto process = [&](auto scaled_tag, auto causal_tag, const char* sb, int st, int key0, int n_valid, const float* sc) {
+    // on[rb]: the wave's block rb takes part; nv[rb]: keys of the sub-tile that exist for it.
+    auto process = [&](auto scaled_tag, auto causal_tag, const char* sb, int st, const bool (&on)[R], const int (&nv)[R], const float* sc) {
 #ifdef HR_ATTN_SKIP_COMPUTE
         return;      // memory-structure probe: stream the pages, do no arithmetic
 #endif
@@ -284,7 +330,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             for (int rb = 0; rb < R; ++rb) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) s[rb][r] = 0.f;
-                if ((wave + rb * NW) * 32 >= M) continue;          // wave-uniform
+                if (!on[rb]) continue;                             // wave-uniform
 #pragma unroll
                 for (int kk = 0; kk < KC; ++kk) s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[kk], qf[rb][kk], s[rb], 0, 0, 0);
             }
@@ -313,10 +359,10 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
         }
 #pragma unroll
         for (int rb = 0; rb < R; ++rb) {
-            if ((wave + rb * NW) * 32 >= M) continue;          // wave-uniform
+            if (!on[rb]) continue;                             // wave-uniform
             floatx16& sr = s[rb];
-            // lane holds keys key0 + 8*(r>>2) + 4*hh + (r&3) of query row ln
-            const int limit = CAUSAL ? min(n_valid, row_i[rb] + 1) : n_valid;     // keys [0, limit) visible (sub-tile relative)
+            // lane holds keys 8*(r>>2) + 4*hh + (r&3) of the sub-tile for query row ln
+            const int limit = CAUSAL ? min(nv[rb], row_i[rb] + 1) : nv[rb];       // keys [0, limit) visible (sub-tile relative)
             if (limit < 32) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -376,15 +422,22 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     // last_only: only the last query token of every pair is computed (g rows per item, all of the pair's own keys
     // visible) and its output goes to row `pair` of a compact [n_pairs][n_q][d] buffer: what the last layer needs.
     auto setup_rows = [&](const ItemCtx& c) {
-        M = last_only ? g : c.qn * g;
 #pragma unroll
         for (int rb = 0; rb < R; ++rb) {
-            int row = (wave + rb * NW) * 32 + ln;
-            row_ok[rb] = row < M;
-            int rc = row < M ? row : M - 1;
-            int i = last_only ? c.qn - 1 : rc / g, a = last_only ? rc : rc - i * g;
+            const int b = wave_u + rb * NW;
+            blk_on[rb] = b < c.n_blk;
+            int seq = c.p0, row0 = 0;
+            if (blk_on[rb]) blk_lookup(c, b, seq, row0);
+            const int t0 = m_cu[seq], qn = m_cu[seq + 1] - t0;
+            blk_seq[rb] = seq;
+            blk_qn[rb] = qn;
+            const int M = last_only ? g : qn * g;                  // rows of this pair
+            const int row = row0 + ln;
+            row_ok[rb] = blk_on[rb] && row < M;
+            const int rc = row < M ? row : M - 1;
+            const int i = last_only ? qn - 1 : rc / g, a = last_only ? rc : rc - i * g;
             row_i[rb] = i;
-            row_off[rb] = ((size_t)(c.t0 + i) * n_q + c.h * g + a) * HD;
+            row_off[rb] = ((size_t)(t0 + i) * n_q + c.h * g + a) * HD;
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) qf[rb][kk] = *(const halfx8*)(q + row_off[rb] + (2 * kk + hh) * 8);
         }
@@ -458,7 +511,10 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             for (int st = 0; st < G::TK / 32; ++st) {
                 const int key0 = tile * G::TK + st * 32;
                 if (key0 >= cur.D) break;
-                process(std::integral_constant<bool, FP8>{}, std::false_type{}, sb, st, key0, cur.D - key0, sc);
+                int nv[R];
+#pragma unroll
+                for (int rb = 0; rb < R; ++rb) nv[rb] = cur.D - key0;
+                process(std::integral_constant<bool, FP8>{}, std::false_type{}, sb, st, blk_on, nv, sc);
             }
             HR_ASTAMP();
             if (tile + 1 < cur.n_tiles) scale_store(stage ^ 1);
@@ -476,13 +532,25 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             }
             const char* sb = smem + stage * kStageBytes;
 #pragma unroll 1
-            for (int st = 0; st < GN::TK / 32; ++st) {
-                const int key0 = nt * GN::TK + st * 32;
-                if (key0 >= cur.qn) break;
-                // row i sees new keys 0..i: the sub-tile relative limit is i + 1 - key0
+            for (int st = 0; st < SUBS; ++st) {
+                const int s = nt * SUBS + st;
+                if (s >= cur.n_sub) break;
+                int page, seq, key0;
+                sub_lookup(cur, s, page, seq, key0);
+                // only the blocks of the pair these keys belong to; row i sees new keys 0..i: the sub-tile relative
+                // limit is i + 1 - key0
+                bool on[R], any = false;
+                int nv[R];
+#pragma unroll
+                for (int rb = 0; rb < R; ++rb) {
+                    on[rb] = blk_on[rb] && blk_seq[rb] == seq;
+                    nv[rb] = blk_qn[rb] - key0;
+                    any = any || on[rb];
+                }
+                if (!any) continue;                                // wave-uniform
 #pragma unroll
                 for (int rb = 0; rb < R; ++rb) row_i[rb] -= key0;
-                process(std::false_type{}, std::true_type{}, sb, st, key0, cur.qn - key0, nullptr);
+                process(std::false_type{}, std::true_type{}, sb, st, on, nv, nullptr);
 #pragma unroll
                 for (int rb = 0; rb < R; ++rb) row_i[rb] += key0;
             }
@@ -501,9 +569,9 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
         for (int rb = 0; rb < R; ++rb) {
             const float l = l_run[rb] + __shfl_xor(l_run[rb], 32, 64);
             const float inv = 1.0f / l;
-            if (last_only) {
+            if (last_only) {                                   // ungrouped: block b holds rows 32 b .. of the pair
                 const int row = (wave + rb * NW) * 32 + ln;
-                out_off[rb] = ((size_t)cur.p * n_q + cur.h * g + (row < g ? row : g - 1)) * HD;
+                out_off[rb] = ((size_t)blk_seq[rb] * n_q + cur.h * g + (row < g ? row : g - 1)) * HD;
             } else {
                 out_off[rb] = row_off[rb];
             }
@@ -534,7 +602,7 @@ int attn_wgs_override() {
 
 template <int HD, int NW, int R, bool FP8>
 hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const MetaView& mv, const PoolView& pv, int layer, int n_q,
-                      int last_only, hipStream_t st) {
+                      int last_only, const GroupView& gv, hipStream_t st) {
     constexpr int SB = stage_bytes(FP8);
     const size_t lds = 2 * SB + 2 * Geo<HD, FP8, SB>::PPS * 2 * sizeof(float) + (FP8 ? 2 * SB : 0);
     static bool attr_set = false;
@@ -557,11 +625,13 @@ hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const Meta
             per_cu = 1;
         max_wgs = prop.multiProcessorCount * per_cu;
     }
-    const int n_items = mv.n_seq * pv.n_kv;
+    const int n_items = (gv.n_groups > 0 ? gv.n_groups : mv.n_seq) * pv.n_kv;
     const int env_wgs = attn_wgs_override();
     const int grid = std::min(n_items, env_wgs > 0 ? env_wgs : max_wgs);
     attn_mfma_kernel<HD, NW, R, FP8><<<dim3((unsigned)grid), NW * 64, lds, st>>>(q, kv_new, o, mv, pv, layer, n_q, mv.cu, mv.prefix_len, mv.page_table,
-                                                                             mv.new_cu, pv.scales, last_only);
+                                                                             mv.new_cu, pv.scales, last_only, gv.n_groups, gv.p0,
+                                                                             gv.blk_cu, gv.sub_cu, gv.blk_seq, gv.blk_row0, gv.sub_page,
+                                                                             gv.sub_seq, gv.sub_key0);
     return hipGetLastError();
 }
 
@@ -581,16 +651,18 @@ bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len) {
 }
 
 hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv, const PoolView& pv, int layer,
-                            int n_q, int max_q_len, hipStream_t st, bool last_only) {
+                            int n_q, int max_q_len, hipStream_t st, bool last_only, const GroupView* groups) {
     if (mv.n_seq == 0) return hipSuccess;
-    const int rows = n_q / pv.n_kv * (last_only ? 1 : max_q_len);
+    const GroupView gv = groups && !last_only ? *groups : GroupView{};
+    const int rows = gv.n_groups > 0 ? gv.max_blocks * 32 : n_q / pv.n_kv * (last_only ? 1 : max_q_len);
+    if (rows > kMaxRowsPerWg) return hipErrorInvalidValue;
     const half_t* qh = (const half_t*)q;
     const char* kvn = (const char*)kv_new_pages;
     half_t* oh = (half_t*)o;
     const bool fp8 = pv.kv_dtype == HR_FP8_E4M3;
 #define HR_ATTN_CASE(HD, NW, R)                                                                       \
-    return fp8 ? launch_one<HD, NW, R, true>(qh, kvn, oh, mv, pv, layer, n_q, last_only ? 1 : 0, st)   \
-               : launch_one<HD, NW, R, false>(qh, kvn, oh, mv, pv, layer, n_q, last_only ? 1 : 0, st)
+    return fp8 ? launch_one<HD, NW, R, true>(qh, kvn, oh, mv, pv, layer, n_q, last_only ? 1 : 0, gv, st)   \
+               : launch_one<HD, NW, R, false>(qh, kvn, oh, mv, pv, layer, n_q, last_only ? 1 : 0, gv, st)
     static int var = -1;
     if (var < 0) {
         const char* e = getenv("HR_ATTN_VARIANT");

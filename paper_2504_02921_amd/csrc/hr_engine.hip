@@ -24,6 +24,7 @@ struct hr_model {
     // optional per-kernel timing with HIP events (benchmarks)
     bool prof_on = false;
     bool no_last_short = false;           // HR_NO_LAST_SHORTCUT=1: run the last layer on every token (A/B runs)
+    bool no_doc_groups = false;           // HR_NO_DOC_GROUPS=1: pairs that share a document are not batched (A/B runs)
     uint32_t prof_mask = 0xFFFFFFFFu;     // kernel classes that are timed while prof_on
     std::vector<hipEvent_t> prof_events;          // pool, two per timed launch
     std::vector<int> prof_class;                  // class of each recorded launch
@@ -127,8 +128,10 @@ struct PrefillTarget {
 //                own new-KV buffer (no-reuse pass, document prefill)
 //   fill         if set, every layer's K/V pages are copied into that pool and the pass stops after the last
 //                layer's K/V (no scores)
+//   groups       if set, the attention work items are these groups of sequences with one shared document
 int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaView& mv, const Workspace& ws, char* wsb,
-               int max_keys, int max_new_len, float* scores, hipStream_t st, const PrefillTarget* fill = nullptr) {
+               int max_keys, int max_new_len, float* scores, hipStream_t st, const PrefillTarget* fill = nullptr,
+               const GroupView* groups = nullptr) {
     const hr_model_cfg& c = m->cfg;
     const int dt = c.dtype;
     const int H = c.hidden, d = c.head_dim, F = c.ffn;
@@ -224,7 +227,7 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
             return HR_OK;
         }
         if (mfma_attn) {
-            HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, o, mv, pv, self_prefix ? 0 : l, c.n_q_heads, max_new_len, st));
+            HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, o, mv, pv, self_prefix ? 0 : l, c.n_q_heads, max_new_len, st, false, groups));
         } else {
             HR_TIMED(PC_ATTENTION, launch_attn_generic(dt, q, k, v, o, mv, pv, l, c.n_q_heads, max_keys, st));
         }
@@ -315,6 +318,8 @@ int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* w, void* pack
     m->mfma_gemm = !m->force_generic && hr::gemm_mfma_supported(*cfg);
     const char* nls = getenv("HR_NO_LAST_SHORTCUT");
     m->no_last_short = nls && nls[0] == '1';
+    const char* ndg = getenv("HR_NO_DOC_GROUPS");
+    m->no_doc_groups = ndg && ndg[0] == '1';
 
     hipStream_t st = (hipStream_t)stream;
     const int dt = cfg->dtype;
@@ -382,7 +387,9 @@ int hr_doc_kv_read(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids
 
 size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t total_q_tokens, int32_t pt_stride) {
     if (!m || n_pairs < 0 || total_q_tokens < 0 || pt_stride < 0) return 0;
-    return hr::make_workspace(m->cfg, n_pairs, total_q_tokens, pt_stride, !m->mfma_gemm).total;
+    return hr::make_workspace(m->cfg, n_pairs, total_q_tokens, pt_stride, !m->mfma_gemm, -1, 0,
+                              (int64_t)hr::group_plan_ints_bound(n_pairs, total_q_tokens, m->cfg.n_q_heads / m->cfg.n_kv_heads))
+        .total;
 }
 
 int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride,
@@ -400,14 +407,36 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     if (n_pairs == 0) return HR_OK;
     if (!workspace_dev || !scores_dev) return HR_ERR_INVALID_ARG;
     if ((uintptr_t)workspace_dev % hr::kAlign != 0) return HR_ERR_INVALID_ARG;
-    hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm);
+    const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
+    const int64_t grp_ints = (int64_t)hr::group_plan_ints_bound(n_pairs, T, g);
+    hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints);
     if (workspace_bytes < ws.total) return HR_ERR_WORKSPACE_SMALL;
 
     hipStream_t st = (hipStream_t)stream;
-    hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, pt_stride);
+    hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, pt_stride, -1, 0, grp_ints);
     rc = stage_reserve(m, ml.total);
     if (rc != HR_OK) return rc;
     hr::fill_meta(m->stage, ml, n_pairs, doc_lens, query_lens, query_tokens, page_table, pt_stride);
+    // Pairs that share a document become one attention work item per kv head (up to 16 row blocks at 64-wide heads,
+    // 8 at 128-wide heads, where two blocks per wave do not fit the register file at two waves per SIMD).
+    hr::GroupView gv{};
+    if (mfma_attn && !m->no_doc_groups && pt_stride > 0) {
+        const hr::GroupPlan plan = hr::make_group_plan(n_pairs, doc_lens, query_lens, page_table, pt_stride, g, m->cfg.head_dim == 64 ? 16 : 8);
+        if (plan.shared && plan.ints() <= (size_t)grp_ints) {
+            hr::store_group_plan(plan, m->stage + ml.grp);
+            const int32_t* dv = (const int32_t*)((char*)workspace_dev + ws.off_meta) + ml.grp;
+            gv.n_groups = plan.n_groups;
+            gv.max_blocks = plan.max_blocks;
+            gv.p0 = dv;                              dv += plan.p0.size();
+            gv.blk_cu = dv;                          dv += plan.blk_cu.size();
+            gv.sub_cu = dv;                          dv += plan.sub_cu.size();
+            gv.blk_seq = dv;                         dv += plan.blk_seq.size();
+            gv.blk_row0 = dv;                        dv += plan.blk_row0.size();
+            gv.sub_page = dv;                        dv += plan.sub_page.size();
+            gv.sub_seq = dv;                         dv += plan.sub_seq.size();
+            gv.sub_key0 = dv;
+        }
+    }
     char* wsb = (char*)workspace_dev;
     HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, m->stage, ml.total * sizeof(int32_t), hipMemcpyHostToDevice, st));
     HR_HIP(hipEventRecord(m->stage_ev, st));
@@ -416,7 +445,7 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     int max_keys = 0;
     for (int32_t p = 0; p < n_pairs; ++p) max_keys = std::max(max_keys, doc_lens[p] + query_lens[p]);
     hr::MetaView mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, n_pairs, T, pt_stride);
-    return run_layers(m, pool, false, mv, ws, wsb, max_keys, max_q, scores_dev, st);
+    return run_layers(m, pool, false, mv, ws, wsb, max_keys, max_q, scores_dev, st, nullptr, gv.n_groups > 0 ? &gv : nullptr);
 }
 
 int hr_rerank_validate(const hr_model_cfg* cfg, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table,

@@ -3,6 +3,7 @@
 // No HIP calls here, so every error path can be exercised on a machine without a GPU.
 #include <algorithm>
 #include <cstring>
+#include <initializer_list>
 #include <new>
 
 #include "hr_internal.h"
@@ -59,7 +60,7 @@ PackLayout make_pack_layout(const hr_model_cfg& c) {
     return p;
 }
 
-MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t n_out, int64_t dst_ints) {
+MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t n_out, int64_t dst_ints, int64_t grp_ints) {
     if (n_out < 0) n_out = n_seq;
     MetaLayout m;
     auto up = [](size_t e) { return (e + 63) / 64 * 64; };
@@ -74,18 +75,19 @@ MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t
     m.new_cu = o;      o = up(o + (size_t)n_seq + 1);
     m.out_row = o;     o = up(o + (size_t)n_out);
     m.dst_table = o;   o = up(o + (size_t)dst_ints);
+    m.grp = o;         o = up(o + (size_t)grp_ints);
     m.total = o;
     return m;
 }
 
 Workspace make_workspace(const hr_model_cfg& c, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch,
-                         int64_t n_out, int64_t dst_ints) {
+                         int64_t n_out, int64_t dst_ints, int64_t grp_ints) {
     Workspace w;
     size_t asz = dtype_size(c.dtype);
     size_t H = c.hidden, d = c.head_dim, F = c.ffn;
     size_t nq = (size_t)c.n_q_heads * d, nkv = (size_t)c.n_kv_heads * d;
     size_t t = (size_t)T;
-    MetaLayout ml = make_meta_layout(n_seq, T, pt_stride, n_out, dst_ints);
+    MetaLayout ml = make_meta_layout(n_seq, T, pt_stride, n_out, dst_ints, grp_ints);
     w.meta_ints = ml.total;
     size_t o = 0;
     w.off_meta = o; o = align_up(o + ml.total * sizeof(int32_t));
@@ -244,6 +246,95 @@ ChunkPlan make_chunk_plan(int64_t n_seq, const int32_t* lens, int chunk) {
     }
     cp.T = row;
     return cp;
+}
+
+size_t group_plan_ints_bound(int64_t n_seq, int64_t T, int g) {
+    // every sequence adds at most one partial block and one partial sub-tile
+    const size_t nb = (size_t)(T * g / 32 + n_seq), ns = (size_t)(T / 32 + n_seq);
+    return (size_t)n_seq + 2 * ((size_t)n_seq + 1) + 2 * nb + 3 * ns;
+}
+
+GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* page_table,
+                          int64_t pt_stride, int g, int cap_blocks) {
+    GroupPlan gp;
+    auto blocks_of = [&](int64_t p) { return (int)(((int64_t)new_lens[p] * g + 31) / 32); };
+    auto pages_of = [&](int64_t p) { return ((int64_t)prefix_lens[p] + kPageTokens - 1) / kPageTokens; };
+    const int32_t* pt = page_table;
+    // sequences with the same document next to each other: by first page, then length, then index
+    std::vector<int32_t> order((size_t)n_seq);
+    for (int64_t p = 0; p < n_seq; ++p) order[p] = (int32_t)p;
+    auto first_page = [&](int32_t p) { return prefix_lens[p] > 0 && pt ? pt[(int64_t)p * pt_stride] : -1; };
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        const int32_t fa = first_page(a), fb = first_page(b);
+        if (fa != fb) return fa < fb;
+        if (prefix_lens[a] != prefix_lens[b]) return prefix_lens[a] < prefix_lens[b];
+        return a < b;
+    });
+    struct Grp { std::vector<int32_t> seqs; int blocks; int64_t cost; };
+    std::vector<Grp> groups;
+    for (int64_t i = 0; i < n_seq;) {
+        // run of sequences whose rows equal the first one's (a sequence without a document is a run of its own)
+        const int32_t lead = order[i];
+        int64_t j = i + 1;
+        if (prefix_lens[lead] > 0)
+            while (j < n_seq && first_page(order[j]) == first_page(lead) && prefix_lens[order[j]] == prefix_lens[lead] &&
+                   std::memcmp(pt + (int64_t)order[j] * pt_stride, pt + (int64_t)lead * pt_stride,
+                               sizeof(int32_t) * (size_t)pages_of(lead)) == 0)
+                ++j;
+        // first fit over the run's groups, sequences in index order
+        const size_t run_first = groups.size();
+        for (int64_t k = i; k < j; ++k) {
+            const int32_t p = order[k];
+            const int nb = blocks_of(p);
+            size_t gi = run_first;
+            while (gi < groups.size() && groups[gi].blocks + nb > cap_blocks) ++gi;
+            if (gi == groups.size()) groups.push_back(Grp{{}, 0, 0});
+            groups[gi].seqs.push_back(p);
+            groups[gi].blocks += nb;
+        }
+        for (size_t gi = run_first; gi < groups.size(); ++gi)
+            groups[gi].cost = ((int64_t)prefix_lens[lead] + 64) * groups[gi].blocks;
+        i = j;
+    }
+    std::stable_sort(groups.begin(), groups.end(), [](const Grp& a, const Grp& b) { return a.cost > b.cost; });
+
+    // start of every sequence's pages in the new-KV buffer: each sequence begins on a 32-slot boundary (fill_meta)
+    std::vector<int64_t> new_page((size_t)n_seq);
+    int64_t slot0 = 0;
+    for (int64_t p = 0; p < n_seq; ++p) {
+        new_page[p] = slot0 / kPageTokens;
+        slot0 += ((int64_t)new_lens[p] + 31) / 32 * 32;
+    }
+    gp.n_groups = (int32_t)groups.size();
+    gp.blk_cu.push_back(0);
+    gp.sub_cu.push_back(0);
+    for (const Grp& gr : groups) {
+        gp.p0.push_back(gr.seqs[0]);
+        gp.shared = gp.shared || gr.seqs.size() > 1;
+        gp.max_blocks = std::max(gp.max_blocks, gr.blocks);
+        for (int32_t p : gr.seqs) {
+            for (int b = 0; b < blocks_of(p); ++b) {
+                gp.blk_seq.push_back(p);
+                gp.blk_row0.push_back(b * 32);
+            }
+            for (int32_t k0 = 0; k0 < new_lens[p]; k0 += 32) {
+                gp.sub_page.push_back((int32_t)(new_page[p] + k0 / kPageTokens));
+                gp.sub_seq.push_back(p);
+                gp.sub_key0.push_back(k0);
+            }
+        }
+        gp.blk_cu.push_back((int32_t)gp.blk_seq.size());
+        gp.sub_cu.push_back((int32_t)gp.sub_page.size());
+    }
+    return gp;
+}
+
+void store_group_plan(const GroupPlan& gp, int32_t* dst) {
+    for (const std::vector<int32_t>* v : {&gp.p0, &gp.blk_cu, &gp.sub_cu, &gp.blk_seq, &gp.blk_row0, &gp.sub_page, &gp.sub_seq,
+                                          &gp.sub_key0}) {
+        std::memcpy(dst, v->data(), sizeof(int32_t) * v->size());
+        dst += v->size();
+    }
 }
 
 }  // namespace hr

@@ -57,17 +57,19 @@ struct Workspace {
 };
 // full_path: sequences carry their own document tokens (no page table).
 Workspace make_workspace(const hr_model_cfg& cfg, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch,
-                         int64_t n_out = -1, int64_t dst_ints = 0);
+                         int64_t n_out = -1, int64_t dst_ints = 0, int64_t grp_ints = 0);
 
 // Metadata block layout (int32 offsets inside the block), uploaded once per call.
 // new_slot[t] / new_cu[p]: where the K/V of new token t goes when the new keys are kept as 16-token
 // pages per sequence (each sequence starts on a 32-slot boundary so that MFMA sub-tiles are whole).
 struct MetaLayout {
     size_t cu = 0, tok_id = 0, tok_pos = 0, tok_seq = 0, prefix_len = 0, page_table = 0, new_slot = 0, new_cu = 0, out_row = 0,
-           dst_table = 0, total = 0;
+           dst_table = 0, grp = 0, total = 0;
 };
-// n_out: rows whose score is read (one per pair); dst_ints: extra table for the prefill target pages
-MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t n_out = -1, int64_t dst_ints = 0);
+// n_out: rows whose score is read (one per pair); dst_ints: extra table for the prefill target pages; grp_ints: room
+// for a group plan (group_plan_ints_bound)
+MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t n_out = -1, int64_t dst_ints = 0,
+                            int64_t grp_ints = 0);
 
 }  // namespace hr
 
@@ -105,4 +107,30 @@ struct ChunkPlan {
     int64_t pt_stride = 0, n_chunks = 0, T = 0;
 };
 ChunkPlan make_chunk_plan(int64_t n_seq, const int32_t* lens, int chunk);
+
+// Sequences that attend to the same cached document (same prefix length, identical page-table rows) share one
+// pass over its pages: a group is one work item per kv head of the MFMA attention.  Its query rows are cut into
+// blocks of 32 (the rows of a sequence are token-major, g heads per token; every sequence starts a new block), its
+// own keys into sub-tiles of 32 (one sequence per sub-tile).  All arrays are int32 and go to the device as they are.
+struct GroupPlan {
+    std::vector<int32_t> p0;                 // [n_groups] a sequence of the group (its page-table row is followed)
+    std::vector<int32_t> blk_cu, sub_cu;     // [n_groups + 1] ranges into blk_* / sub_*
+    std::vector<int32_t> blk_seq, blk_row0;  // per block: sequence, first row of the block within the sequence
+    std::vector<int32_t> sub_page, sub_seq, sub_key0;   // per sub-tile: first of its two pages in the new-KV buffer,
+                                                         // sequence, first new-key index
+    int32_t n_groups = 0, max_blocks = 0;
+    bool shared = false;                     // some group holds more than one sequence
+    size_t ints() const {
+        return p0.size() + blk_cu.size() + sub_cu.size() + 2 * blk_seq.size() + 3 * sub_page.size();
+    }
+};
+// g: query heads per kv head; cap_blocks: most blocks a group may hold (a sequence with more is a group of its own).
+// Groups come in order of decreasing work (document keys x blocks), so that a round-robin walk starts the long ones
+// first.
+GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* page_table,
+                          int64_t pt_stride, int g, int cap_blocks);
+size_t group_plan_ints_bound(int64_t n_seq, int64_t T, int g);
+// Writes the plan at dst (>= plan.ints() entries) in the order p0, blk_cu, sub_cu, blk_seq, blk_row0, sub_page, sub_seq,
+// sub_key0.
+void store_group_plan(const GroupPlan& plan, int32_t* dst);
 }  // namespace hr

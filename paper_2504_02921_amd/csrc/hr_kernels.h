@@ -76,9 +76,16 @@ struct GemmArgs {
 hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st);
 
 bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len);
-// kv_new_pages: the new tokens' K/V as pages (see GemmArgs::kv_pages)
+// Device-side view of a group plan (GroupPlan): sequences that share a cached document are one work item per kv head.
+struct GroupView {
+    int32_t n_groups = 0, max_blocks = 0;
+    const int32_t *p0 = nullptr, *blk_cu = nullptr, *sub_cu = nullptr, *blk_seq = nullptr, *blk_row0 = nullptr, *sub_page = nullptr,
+                  *sub_seq = nullptr, *sub_key0 = nullptr;
+};
+// kv_new_pages: the new tokens' K/V as pages (see GemmArgs::kv_pages).  groups: nullptr = every sequence on its own.
 hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv,
-                            const PoolView& pv, int layer, int n_q, int max_q_len, hipStream_t st, bool last_only = false);
+                            const PoolView& pv, int layer, int n_q, int max_q_len, hipStream_t st, bool last_only = false,
+                            const GroupView* groups = nullptr);
 // fp8 pools: quantising copy of whole pages (amax -> scale -> E4M3 codes per page and kv head) from the half new-KV buffer
 hipError_t launch_pages_to_pool_fp8(const char* kv_new, char* pool_layer_base, float* scales_layer_base, const int32_t* src_page,
                                     const int32_t* dst_page, int n_pages, int n_kv, int d, hipStream_t st);

@@ -1,6 +1,7 @@
 // Host-only logic of the library (layouts, chunk plan, metadata builder, validation) run on exact-size buffers
 // under AddressSanitizer / UBSan.  Built and run by tests/test_host_asan.py; no GPU involved.
 #include <cstdio>
+#include <cstdint>
 #include <cstdlib>
 #include <vector>
 
@@ -41,6 +42,67 @@ int main() {
     CHECK(meta2[m2.tok_pos + 0] == 100 && meta2[m2.tok_pos + 4] == 104 && meta2[m2.tok_pos + 5] == 0 && meta2[m2.tok_pos + 6] == 17);
     CHECK(meta2[m2.new_cu + 0] == 0 && meta2[m2.new_cu + 1] == 32 && meta2[m2.new_cu + 2] == 64 && meta2[m2.new_cu + 3] == 128);
     CHECK(meta2[m2.out_row + 0] == 4 && meta2[m2.out_row + 1] == 5 && meta2[m2.out_row + 2] == 38);
+    // group plan: pairs with identical page-table rows and lengths share a group up to the block capacity; every
+    // block and every 32-key sub-tile of every pair appears exactly once; groups come heaviest first
+    {
+        const int g = 7, cap = 16, stride = 4;
+        // docs: A = pages {3, 9}, len 30; B = pages {5}, len 16; pair 6 has A's first page but another second page
+        std::vector<int32_t> gd = {30, 16, 30, 0, 30, 16, 30, 0, 30}, gq = {40, 8, 33, 5, 64, 1, 9, 5, 20};
+        std::vector<int32_t> gpt = {3, 9, -1, -1, 5, -1, -1, -1, 3, 9, -1, -1, -1, -1, -1, -1, 3, 9, -1, -1, 5, -1, -1, -1,
+                                    3, 8, -1, -1, -1, -1, -1, -1, 3, 9, -1, -1};
+        const int64_t n = (int64_t)gd.size();
+        int64_t Tq = 0;
+        for (int32_t v : gq) Tq += v;
+        hr::GroupPlan gp = hr::make_group_plan(n, gd.data(), gq.data(), gpt.data(), stride, g, cap);
+        CHECK(gp.ints() <= hr::group_plan_ints_bound(n, Tq, g));
+        std::vector<int32_t> flat(gp.ints(), -7);
+        hr::store_group_plan(gp, flat.data());
+        CHECK(flat[0] == gp.p0[0] && flat.back() == gp.sub_key0.back());
+        CHECK(gp.shared && gp.max_blocks <= cap);
+        CHECK((int)gp.blk_cu.size() == gp.n_groups + 1 && (int)gp.sub_cu.size() == gp.n_groups + 1);
+        std::vector<int> blocks_seen(n, 0), subs_seen(n, 0), group_of(n, -1);
+        int64_t prev_cost = INT64_MAX;
+        std::vector<int64_t> new_page(n);
+        int64_t slot = 0;
+        for (int64_t p = 0; p < n; ++p) { new_page[p] = slot / 16; slot += (gq[p] + 31) / 32 * 32; }
+        for (int gi = 0; gi < gp.n_groups; ++gi) {
+            const int32_t lead = gp.p0[gi];
+            const int nb = gp.blk_cu[gi + 1] - gp.blk_cu[gi];
+            CHECK(nb >= 1 && nb <= cap);
+            const int64_t cost = ((int64_t)gd[lead] + 64) * nb;
+            CHECK(cost <= prev_cost);
+            prev_cost = cost;
+            for (int b = gp.blk_cu[gi]; b < gp.blk_cu[gi + 1]; ++b) {
+                const int32_t p = gp.blk_seq[b];
+                CHECK(p >= 0 && p < n && gd[p] == gd[lead]);
+                for (int pg = 0; pg < (gd[p] + 15) / 16; ++pg) CHECK(gpt[p * stride + pg] == gpt[lead * stride + pg]);
+                CHECK(group_of[p] == -1 || group_of[p] == gi);
+                group_of[p] = gi;
+                CHECK(gp.blk_row0[b] == 32 * blocks_seen[p]);              // a pair's blocks in order, back to back
+                CHECK(b == gp.blk_cu[gi] || gp.blk_seq[b - 1] == p || blocks_seen[p] == 0);
+                ++blocks_seen[p];
+            }
+            for (int s = gp.sub_cu[gi]; s < gp.sub_cu[gi + 1]; ++s) {
+                const int32_t p = gp.sub_seq[s];
+                CHECK(group_of[p] == gi);
+                CHECK(gp.sub_key0[s] == 32 * subs_seen[p] && gp.sub_page[s] == new_page[p] + 2 * subs_seen[p]);
+                ++subs_seen[p];
+            }
+        }
+        for (int64_t p = 0; p < n; ++p) {
+            CHECK(blocks_seen[p] == (gq[p] * g + 31) / 32 && subs_seen[p] == (gq[p] + 31) / 32);
+            if (gd[p] == 0) CHECK(gp.blk_cu[group_of[p] + 1] - gp.blk_cu[group_of[p]] == blocks_seen[p]);   // no document: alone
+        }
+        // A is shared by pairs 0, 2, 4, 8 (9 + 8 + 14 + 5 blocks): at least two groups; pair 6 is not with them
+        CHECK(group_of[6] != group_of[0] && group_of[6] != group_of[2] && group_of[6] != group_of[4] && group_of[6] != group_of[8]);
+        CHECK(group_of[1] == group_of[5]);
+        CHECK(group_of[3] != group_of[7]);
+        // nothing shared: every pair alone
+        std::vector<int32_t> upt = {1, 2, 3};
+        std::vector<int32_t> ud = {16, 16, 16}, uq = {4, 4, 4};
+        hr::GroupPlan up = hr::make_group_plan(3, ud.data(), uq.data(), upt.data(), 1, g, cap);
+        CHECK(!up.shared && up.n_groups == 3 && up.max_blocks == 1);
+    }
     // pool bookkeeping and validation paths
     hr_pool_cfg pc{2, 2, 64, 16, 8, HR_BF16};
     hr_pool* pool = nullptr;

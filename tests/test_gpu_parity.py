@@ -303,6 +303,30 @@ def test_shortened_last_layer_is_bit_identical(d, n_q, n_kv, kv, monkeypatch):
     np.testing.assert_array_equal(scores[0], scores[1])
 
 
+@pytest.mark.parametrize("d,n_q,n_kv,kv,qlen", [(64, 14, 2, "bf16", (1, 40)), (64, 4, 2, "bf16", (30, 64)), (128, 8, 2, "fp8", (1, 40))])
+def test_pairs_sharing_a_document_are_batched_bit_identically(d, n_q, n_kv, kv, qlen, monkeypatch):
+    """Pairs whose candidates are the same pool document share one pass over its pages.  Few documents and many
+    queries make groups of several pairs (and groups that fill up and spill into a second one); the scores must match
+    the oracle and be bit for bit those of the run with the batching switched off."""
+    model = small_model(dtype="bf16", n_layers=3, hidden=256, n_q=n_q, n_kv=n_kv, d=d, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("shared_docs", model, 12, 5, (5, 200), qlen, kv, pool_docs=7, zipf_a=1.1, seed=31)
+    w = wlmod.SeededWeights(model, seed=32, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(cfg, spare_pages=3)
+    assert len(set(int(x) for x in wl.pair_doc)) < wl.n_pairs // 3
+    scores = []
+    for flag in ("0", "1"):
+        monkeypatch.setenv("HR_NO_DOC_GROUPS", flag)          # read when the model handle is created
+        case = H.Case(wl, w)
+        try:
+            case.fill_from_prefill()
+            scores.append(case.gpu_scores())
+            if flag == "0":
+                H.assert_scores_close(scores[0], case.oracle_scores(), H.TOL["bf16"], "pairs sharing a document")
+        finally:
+            case.close()
+    np.testing.assert_array_equal(scores[0], scores[1])
+
+
 @pytest.mark.parametrize("kv", ["f32", "bf16", "fp8"])
 def test_pool_read_back_is_the_inverse_of_write(kv):
     """hr_doc_kv_read returns exactly what hr_doc_kv_write stored (bf16 values come back as the halves the pool keeps),
