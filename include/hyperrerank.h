@@ -155,6 +155,29 @@ int hr_doc_kv_read(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids
 /* Mark pages free again (contents are left as they are). */
 int hr_doc_kv_free(hr_pool* pool, const int32_t* page_ids, int32_t n);
 
+/* ---- host tier (Sections 4.1 and 4.3: the documents' KV lives in a storage backend behind the GPU and is loaded for
+ * the retrieved candidates; here the backend is the caller's memory, normally pinned host memory, and a page moves
+ * as one record) ---- */
+
+/* Bytes of one page record: the page's K and V blocks of every layer and kv head in the pool's own arrangement
+ * ([n_layers][n_kv_heads][K block | V block]), followed for fp8 pools by its scales ([n_layers][n_kv_heads][K, V] fp32).
+ * A multiple of 16; 0 if pool is NULL.  Records are opaque: only a pool of the same configuration reads them. */
+size_t hr_kv_page_record_bytes(const hr_pool* pool);
+
+/* Copy n_pages pages out of the pool: record i at dst + i * hr_kv_page_record_bytes is page page_ids[i].
+ *   page_ids  host, ids of pages that hold a document (HR_ERR_PAGE_RANGE / HR_ERR_TABLE_SHORT otherwise)
+ *   dst       n_pages records of memory the GPU can address: device memory, or host memory pinned by the HIP runtime
+ *             (hipHostMalloc); 16-byte aligned.  Pageable host memory is refused with HR_ERR_INVALID_ARG.
+ * Copy kernels are enqueued on `stream` (they write pinned host memory over the bus directly: no staging buffer);
+ * dst is complete when the stream has drained.  The pool is unchanged. */
+int hr_kv_pages_out(const hr_pool* pool, int32_t n_pages, const int32_t* page_ids, void* dst, void* stream);
+
+/* The inverse: page page_ids[i] <- record i of src (same kinds of memory as dst above).  The pages must be distinct
+ * and free or reserved (HR_ERR_PAGE_DUP / HR_ERR_PAGE_IN_USE) and are marked used on success; they may be scored as
+ * soon as work enqueued after this call on the same stream runs, or after an event recorded behind it.  Issued on
+ * a second stream it overlaps with hr_rerank_score calls that read other pages of the same pool. */
+int hr_kv_pages_in(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, const void* src, void* stream);
+
 /* ---- weights ---- */
 
 /* Bytes of device memory for the library's packed copy of the layer weights

@@ -385,6 +385,45 @@ int hr_doc_kv_read(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids
     return HR_OK;
 }
 
+// Address the GPU uses for caller memory that must be device memory or host memory pinned by the runtime; nullptr for
+// anything else (pageable host memory would fault in a kernel).
+static char* device_view(const void* p) {
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeHost) return nullptr;
+    return (char*)attr.devicePointer;
+}
+
+static int pages_move(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, const void* records, bool to_pool, void* stream) {
+    int rc = hr::pool_check_pages(pool, n_pages, page_ids, !to_pool);
+    if (rc != HR_OK) return rc;
+    if (n_pages == 0) return HR_OK;
+    if (!records || (uintptr_t)records % 16 != 0) return HR_ERR_INVALID_ARG;
+    char* rec = device_view(records);
+    if (!rec || (uintptr_t)rec % 16 != 0) {
+        snprintf(g_last_error, sizeof(g_last_error), "page records must be device memory or host memory pinned by the HIP runtime");
+        return HR_ERR_INVALID_ARG;
+    }
+    hipError_t e = hr::launch_pages_move(pool->lay, pool->base, page_ids, n_pages, rec, to_pool, (hipStream_t)stream);
+    if (e != hipSuccess) {
+        note_hip_error(e, "page move kernel");
+        return HR_ERR_DEVICE;
+    }
+    if (to_pool) hr::pool_mark(pool, page_ids, n_pages, hr::PAGE_USED);
+    return HR_OK;
+}
+
+int hr_kv_pages_out(const hr_pool* pool, int32_t n_pages, const int32_t* page_ids, void* dst, void* stream) {
+    return pages_move(const_cast<hr_pool*>(pool), n_pages, page_ids, dst, false, stream);
+}
+
+int hr_kv_pages_in(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, const void* src, void* stream) {
+    return pages_move(pool, n_pages, page_ids, src, true, stream);
+}
+
 size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t total_q_tokens, int32_t pt_stride) {
     if (!m || n_pairs < 0 || total_q_tokens < 0 || pt_stride < 0) return 0;
     return hr::make_workspace(m->cfg, n_pairs, total_q_tokens, pt_stride, !m->mfma_gemm, -1, 0,

@@ -140,6 +140,30 @@ int pool_check_write(const hr_pool* pool, int32_t doc_len, const int32_t* page_i
     return HR_OK;
 }
 
+int pool_check_pages(const hr_pool* pool, int64_t n, const int32_t* page_ids, bool want_used) {
+    if (!pool || n < 0 || (n > 0 && !page_ids)) return HR_ERR_INVALID_ARG;
+    if (!want_used && n > pool->cfg.num_pages) return HR_ERR_PAGE_DUP;      // more ids than pages: some id repeats
+    for (int64_t i = 0; i < n; ++i)
+        if (page_ids[i] < 0 || page_ids[i] >= pool->cfg.num_pages) return HR_ERR_PAGE_RANGE;
+    if (want_used) {
+        for (int64_t i = 0; i < n; ++i)
+            if (pool->state[page_ids[i]] != PAGE_USED) return HR_ERR_TABLE_SHORT;
+        return HR_OK;
+    }
+    for (int64_t i = 0; i < n; ++i)
+        if (pool->state[page_ids[i]] == PAGE_USED) return HR_ERR_PAGE_IN_USE;
+    std::vector<int32_t> s(page_ids, page_ids + n);
+    std::sort(s.begin(), s.end());
+    if (std::adjacent_find(s.begin(), s.end()) != s.end()) return HR_ERR_PAGE_DUP;
+    return HR_OK;
+}
+
+size_t page_record_bytes(const PoolLayout& lay) {
+    const size_t data = (size_t)lay.n_layers * lay.n_kv * 2 * lay.block_elems * lay.esz;
+    const size_t scales = lay.kv_dtype == HR_FP8_E4M3 ? (size_t)lay.n_layers * lay.n_kv * 2 * sizeof(float) : 0;
+    return (data + scales + 15) / 16 * 16;
+}
+
 void pool_mark(hr_pool* pool, const int32_t* page_ids, int n, PageState st) {
     for (int i = 0; i < n; ++i) {
         uint8_t& cur = pool->state[page_ids[i]];
@@ -363,6 +387,8 @@ const char* hr_status_str(int s) {
         default: return "unknown status";
     }
 }
+
+size_t hr_kv_page_record_bytes(const hr_pool* pool) { return pool ? hr::page_record_bytes(pool->lay) : 0; }
 
 size_t hr_kv_pool_bytes(const hr_pool_cfg* cfg) {
     if (!hr::pool_cfg_valid(cfg)) return 0;

@@ -92,6 +92,9 @@ hipError_t launch_pages_to_pool_fp8(const char* kv_new, char* pool_layer_base, f
 // inverse of launch_kv_scatter: pages -> logical [L][D][n_kv][d] in the pool's element type (+ scales for fp8)
 hipError_t launch_kv_gather(const PoolLayout& lay, const char* pool_base, const int32_t* page_ids_host, int doc_len, void* k, void* v,
                             float* ks, float* vs, hipStream_t st);
+// whole pages between the pool and page records ([layer][kv head][K | V], then the fp8 scales): to_pool picks the direction
+hipError_t launch_pages_move(const PoolLayout& lay, char* pool_base, const int32_t* page_ids_host, int64_t n_pages, char* records,
+                             bool to_pool, hipStream_t st);
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t st);
 // dst[i][:] = src[rows[i]][:] for n rows of `cols` floats (device arrays)
 hipError_t launch_gather_rows_f32(const float* src, const int32_t* rows, float* dst, int n, int cols, hipStream_t st);

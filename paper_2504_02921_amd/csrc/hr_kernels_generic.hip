@@ -612,6 +612,61 @@ hipError_t launch_pack_rows(int dtype, const void* src, void* dst, int rows, int
 }
 
 
+// ---- host tier: whole pages between the pool and page records.  One workgroup per (page, layer) moves the layer's
+// n_kv * (K block + V block) bytes, contiguous on both sides, as 16-byte words, four loads in flight per thread (the
+// record side may be pinned host memory behind the bus: many small workgroups keep enough reads outstanding); the first
+// 2 * n_kv threads also move the layer's fp8 scales.
+namespace {
+template <bool TO_POOL>
+__global__ void __launch_bounds__(256) pages_move_kernel(char* __restrict__ pool, float* __restrict__ scales, PageIdChunk page_ids,
+                                                         char* __restrict__ records, size_t record_bytes, int layer_bytes, int n_layers,
+                                                         int num_pages, int n_kv) {
+    const int page = page_ids.ids[blockIdx.x], layer = blockIdx.y;
+    char* rec = records + (size_t)blockIdx.x * record_bytes;
+    uint4* pw = (uint4*)(pool + ((size_t)layer * num_pages + page) * layer_bytes);
+    uint4* rw = (uint4*)(rec + (size_t)layer * layer_bytes);
+    const uint4* src = TO_POOL ? rw : pw;
+    uint4* dst = TO_POOL ? pw : rw;
+    const int n = layer_bytes / 16;
+    for (int i0 = threadIdx.x; i0 < n; i0 += 4 * 256) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i0 + u * 256 < n) v[u] = src[i0 + u * 256];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i0 + u * 256 < n) dst[i0 + u * 256] = v[u];
+    }
+    if (scales && (int)threadIdx.x < 2 * n_kv) {
+        float* ps = scales + ((size_t)layer * num_pages + page) * n_kv * 2 + threadIdx.x;
+        float* rs = (float*)(rec + (size_t)n_layers * layer_bytes) + (size_t)layer * n_kv * 2 + threadIdx.x;
+        if (TO_POOL) *ps = *rs;
+        else *rs = *ps;
+    }
+}
+}  // namespace
+
+hipError_t launch_pages_move(const PoolLayout& lay, char* pool_base, const int32_t* page_ids_host, int64_t n_pages, char* records,
+                             bool to_pool, hipStream_t st) {
+    float* scales = lay.kv_dtype == HR_FP8_E4M3 ? (float*)(pool_base + lay.data_bytes) : nullptr;
+    const size_t rec = page_record_bytes(lay);
+    const int layer_bytes = (int)((size_t)lay.n_kv * 2 * lay.block_elems * lay.esz);
+    for (int64_t pg0 = 0; pg0 < n_pages; pg0 += 256) {
+        const int n = (int)(n_pages - pg0 < 256 ? n_pages - pg0 : 256);
+        PageIdChunk ids;
+        for (int i = 0; i < 256; ++i) ids.ids[i] = i < n ? page_ids_host[pg0 + i] : 0;
+        const dim3 grid((unsigned)n, (unsigned)lay.n_layers);
+        char* r = records + (size_t)pg0 * rec;
+        if (to_pool)
+            pages_move_kernel<true><<<grid, 256, 0, st>>>(pool_base, scales, ids, r, rec, layer_bytes, lay.n_layers, lay.num_pages, lay.n_kv);
+        else
+            pages_move_kernel<false><<<grid, 256, 0, st>>>(pool_base, scales, ids, r, rec, layer_bytes, lay.n_layers, lay.num_pages, lay.n_kv);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 // ---- dst[i][:] = src[rows[i]][:]: the rows of the last query tokens, for the last layer's shortened tail
 namespace {
 __global__ void __launch_bounds__(256) gather_rows_f32_kernel(const float* __restrict__ src, const int32_t* __restrict__ rows,

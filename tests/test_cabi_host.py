@@ -131,6 +131,39 @@ def test_doc_kv_read_validation():
     hb.lib.hr_kv_pool_destroy(h)
 
 
+def test_page_record_size_and_host_tier_validation():
+    """Record size is the page's blocks over all layers and kv heads (+ fp8 scales); every argument error of the page
+    move calls is reported before any device work (the record pointer itself is only examined after these)."""
+    cfg, h = make_pool(num_pages=8)
+    rec = hb.lib.hr_kv_page_record_bytes(h)
+    esz = {hb.HR_F32: 4, hb.HR_BF16: 2, hb.HR_FP8_E4M3: 1}[cfg.kv_dtype]
+    want = cfg.n_layers * cfg.n_kv_heads * 2 * 16 * cfg.head_dim * esz
+    if cfg.kv_dtype == hb.HR_FP8_E4M3:
+        want += cfg.n_layers * cfg.n_kv_heads * 2 * 4
+    assert rec == (want + 15) // 16 * 16
+    assert hb.lib.hr_kv_page_record_bytes(None) == 0
+    fake = C.c_void_p(FAKE_DEV)
+
+    def move(fn, pages, pool=h):
+        arr = (C.c_int32 * max(len(pages), 1))(*pages)
+        return fn(pool, len(pages), arr, fake, None)
+
+    for fn in (hb.lib.hr_kv_pages_out, hb.lib.hr_kv_pages_in):
+        assert move(fn, [0], pool=None) == hb.HR_ERR_INVALID_ARG
+        assert fn(h, 1, None, fake, None) == hb.HR_ERR_INVALID_ARG
+        assert fn(h, -1, (C.c_int32 * 1)(0), fake, None) == hb.HR_ERR_INVALID_ARG
+        assert move(fn, [0, 8]) == hb.HR_ERR_PAGE_RANGE
+        assert move(fn, [-1]) == hb.HR_ERR_PAGE_RANGE
+        assert move(fn, []) == hb.HR_OK                                       # nothing to move
+    assert move(hb.lib.hr_kv_pages_out, [0, 1]) == hb.HR_ERR_TABLE_SHORT      # nothing has been written there
+    assert move(hb.lib.hr_kv_pages_in, [2, 5, 2]) == hb.HR_ERR_PAGE_DUP
+    assert move(hb.lib.hr_kv_pages_in, list(range(8)) + [0]) == hb.HR_ERR_PAGE_DUP
+    assert hb.lib.hr_kv_pages_in(h, 1, (C.c_int32 * 1)(3), None, None) == hb.HR_ERR_INVALID_ARG
+    assert hb.lib.hr_kv_pages_in(h, 1, (C.c_int32 * 1)(3), C.c_void_p(FAKE_DEV + 4), None) == hb.HR_ERR_INVALID_ARG   # alignment
+    assert hb.lib.hr_kv_pool_free_pages(h) == 8                               # nothing was marked by the refused calls
+    hb.lib.hr_kv_pool_destroy(h)
+
+
 def test_weights_pack_bytes_and_model_cfg_validation():
     m = wlmod.MODELS["qwen2_0p5b"]
     cfg = hb.make_model_cfg(m)

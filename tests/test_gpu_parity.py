@@ -3,6 +3,7 @@ on the same seeded inputs.  Tolerances are the stated bar: 1e-4 absolute on fp32
 bf16 scores, same per-query ranking except for ties inside the tolerance."""
 
 import ctypes as C
+import dataclasses
 
 import numpy as np
 import pytest
@@ -325,6 +326,75 @@ def test_pairs_sharing_a_document_are_batched_bit_identically(d, n_q, n_kv, kv, 
         finally:
             case.close()
     np.testing.assert_array_equal(scores[0], scores[1])
+
+
+@pytest.mark.parametrize("kv", ["f32", "bf16", "fp8"])
+def test_host_tier_round_trip_keeps_pages_and_scores(kv):
+    """Documents are evicted to pinned host memory as page records, their pages freed, and paged in again at other
+    physical pages on a second stream: the pool reads back the same K/V bit for bit, the scores through the new page
+    table are bit for bit the scores before the eviction, and records written to device memory are the same bytes.
+    Pageable host memory is refused before any kernel runs."""
+    import torch
+    from paper_2504_02921_amd import binding as hb
+    dtype = "f32" if kv == "f32" else "bf16"
+    model = small_model(dtype=dtype, n_layers=2, hidden=128, n_q=4, n_kv=2, d=64, ffn=192, vocab=300)
+    cfg = wlmod.WorkloadCfg("host_tier", model, 3, 4, (5, 90), (2, 20), kv, pool_docs=6, zipf_a=0.5, seed=41)
+    w = wlmod.SeededWeights(model, seed=42, std=0.05)
+    wl = wlmod.make_workload(cfg, spare_pages=40)
+    case = H.Case(wl, w)
+    try:
+        case.fill_from_prefill()
+        before = case.gpu_scores()
+        H.assert_scores_close(before, case.oracle_scores(), H.TOL[dtype], "before eviction")
+        pool = case.pool
+        docs = sorted(set(int(d) for d in wl.pair_doc))
+        old_pages = np.concatenate([wl.pool_doc_pages[d] for d in docs]).astype(np.int32)
+        kv_before = {d: pool.read(int(wl.pool_doc_lens[d]), wl.pool_doc_pages[d]) for d in docs}
+        rec = pool.page_record_bytes
+        host = torch.empty(len(old_pages) * rec, dtype=torch.uint8, pin_memory=True)
+        dev = torch.empty(len(old_pages) * rec, dtype=torch.uint8, device="cuda:0")
+        pool.pages_out(old_pages, host)
+        pool.pages_out(old_pages, dev)
+        torch.cuda.synchronize()
+        assert torch.equal(host, dev.cpu())
+        with pytest.raises(hb.HrError) as ei:                       # pageable memory: refused on the host
+            pool.pages_out(old_pages, torch.empty(len(old_pages) * rec, dtype=torch.uint8))
+        assert ei.value.status == -1
+        with pytest.raises(hb.HrError) as ei:                       # the pages still hold documents
+            pool.pages_in(old_pages, host)
+        assert ei.value.status == -4
+        free0 = pool.free_pages
+        pool.free(old_pages)
+        assert pool.free_pages == free0 + len(old_pages)
+        # new placement: the spare pages first, then some of the old ones, shuffled
+        rng = np.random.default_rng(7)
+        used_elsewhere = set(int(p) for d in range(wl.n_docs) if d not in docs for p in wl.pool_doc_pages[d])
+        candidates = np.array([p for p in range(wl.num_pages) if p not in used_elsewhere], np.int32)
+        new_pages = rng.permutation(candidates)[:len(old_pages)].astype(np.int32)
+        assert not np.array_equal(new_pages, old_pages)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            pool.pages_in(new_pages, host)
+            done = torch.cuda.Event()
+            done.record()
+        torch.cuda.current_stream().wait_event(done)
+        # page table rows through the old -> new map
+        remap = {int(o): int(n) for o, n in zip(old_pages, new_pages)}
+        pt = wl.page_table.copy()
+        for i in range(pt.shape[0]):
+            for j in range(pt.shape[1]):
+                if pt[i, j] >= 0:
+                    pt[i, j] = remap[int(pt[i, j])]
+        moved = dataclasses.replace(wl, page_table=pt)
+        after = case.gpu_scores(moved)
+        np.testing.assert_array_equal(before, after)
+        for d in docs:
+            got = pool.read(int(wl.pool_doc_lens[d]), np.array([remap[int(p)] for p in wl.pool_doc_pages[d]], np.int32))
+            torch.cuda.synchronize()
+            for a_t, b_t in zip(kv_before[d], got):
+                assert torch.equal(a_t, b_t)
+    finally:
+        case.close()
 
 
 @pytest.mark.parametrize("kv", ["f32", "bf16", "fp8"])
