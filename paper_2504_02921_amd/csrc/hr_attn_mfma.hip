@@ -48,6 +48,7 @@ namespace {
 constexpr int kStageBytesHalf = 32768;
 constexpr int stage_bytes(bool fp8) { return fp8 ? kStageBytesHalf / 2 : kStageBytesHalf; }
 constexpr int kMaxRowsPerWg = 512;
+constexpr float kLazyMax = 8.0f;
 
 template <int HD, bool FP8, int kStageBytes>
 struct Geo {
@@ -77,6 +78,18 @@ __device__ __forceinline__ halfx8 fp8x8_to_half(uint2 w, halfx2 pow2) {
     halfx8 r;
     r[0] = a[0]; r[1] = a[1]; r[2] = b[0]; r[3] = b[1]; r[4] = c[0]; r[5] = c[1]; r[6] = d[0]; r[7] = d[1];
     return r;
+}
+
+// Reductions over lanes l and l ^ 32 (the two lanes that share a query row) through the VALU lane-swap instruction instead of an
+// LDS round trip: v_permlane32_swap exchanges the upper half of its first operand with the lower half of its second, so
+// with the same value in both the first result holds lanes 0..31 twice and the second lanes 32..63 twice.
+__device__ __forceinline__ float row_max2(float x) {       // max over the two lanes of a row, in both
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float row_sum2(float x) {       // sum over the two lanes of a row, in both (same bits in both)
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 // 2^8 times the power of two of a positive scale, as a pair of halves (clamped to the normal range of half)
@@ -378,9 +391,16 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                 mx1 = fmaxf(mx1, sr[8 + r]);
             }
             float mx = fmaxf(mx0 * cs0, mx1 * cs1);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[rb], mx);
-            const float alpha = m_run[rb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[rb] - m_new);
+            mx = row_max2(mx);
+            // The running maximum only follows the scores when they exceed it by more than kLazyMax (log2 units): below
+            // that the probabilities of this sub-tile are at most 2^kLazyMax (no overflow in half, and the final division
+            // by the row sum cancels the factor), and the rescale of O and of the row sum, 32-64 multiplications
+            // per block, is skipped for the whole wavefront unless one of its rows moves.  Decided per row, so a row's
+            // arithmetic does not depend on its neighbours.
+            const float m_cand = fmaxf(m_run[rb], mx);
+            const bool move = m_cand > m_run[rb] + kLazyMax;       // false while everything so far is masked (-inf)
+            const float m_new = move ? m_cand : m_run[rb];
+            const float alpha = !move ? 1.0f : (m_run[rb] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run[rb] - m_new));
             const float m_use = m_new == -INFINITY ? 0.f : m_new;   // a row with nothing visible yet keeps p = 0
             float lsum = 0.f;
 #pragma unroll
@@ -567,7 +587,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
         // The next item's Q fragments are requested now so their latency hides as well.
 #pragma unroll
         for (int rb = 0; rb < R; ++rb) {
-            const float l = l_run[rb] + __shfl_xor(l_run[rb], 32, 64);
+            const float l = row_sum2(l_run[rb]);
             const float inv = 1.0f / l;
             if (last_only) {                                   // ungrouped: block b holds rows 32 b .. of the pair
                 const int row = (wave + rb * NW) * 32 + ln;
