@@ -211,11 +211,21 @@ size_t hr_rerank_workspace_bytes(const hr_model* model, int32_t n_pairs, int64_t
  * The pool is only read.  Host arrays may be reused as soon as the call returns.
  * Pairs of one call whose doc_lens and page-table rows are identical (the same cached document: Section 3.3,
  * pairwise independence makes a document's KV reusable for every query) share one pass over its pages in the
- * attention kernels; the scores are bit for bit those of the pairs scored alone. */
+ * attention kernels; the scores are bit for bit those of the pairs scored alone.
+ * A call with at least 8192 query tokens on the MFMA path runs as two halves of the pairs, the first on `stream`,
+ * the second on a stream of the library's own that starts behind the work already enqueued on `stream` and that
+ * `stream` waits for before anything enqueued after the call (see hr_rerank_set_streams); to the caller the call
+ * is ordered on `stream` as if it were one piece of work. */
 int hr_rerank_score(hr_model* model, const hr_pool* pool, int32_t n_pairs,
                     const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
                     const int32_t* query_tokens, const int32_t* query_lens,
                     void* workspace_dev, size_t workspace_bytes, float* scores_dev, void* stream);
+
+/* 1: scoring calls use the caller's stream only; 2 (the default): large calls are cut in two halves that run on
+ * two streams, so that one half's kernels fill the compute units that the last, partly filled round of the other
+ * half's GEMM tiles leaves idle (pairs are independent, Section 3.3: the scores do not change by a bit).
+ * HR_ERR_INVALID_ARG for other values. */
+int hr_rerank_set_streams(hr_model* model, int n_streams);
 
 /* The host-side checks hr_rerank_score performs before it enqueues anything, on their own: no
  * device work, no model handle needed.  Returns HR_OK or the status hr_rerank_score would return

@@ -25,6 +25,9 @@ struct hr_model {
     bool prof_on = false;
     bool no_last_short = false;           // HR_NO_LAST_SHORTCUT=1: run the last layer on every token (A/B runs)
     bool no_doc_groups = false;           // HR_NO_DOC_GROUPS=1: pairs that share a document are not batched (A/B runs)
+    int n_streams = 2;                    // a large scoring call runs as two halves on two streams (hr_rerank_set_streams)
+    hipStream_t aux_stream = nullptr;     // the second one, created on first use
+    hipEvent_t fork_ev = nullptr, join_ev = nullptr;
     uint32_t prof_mask = 0xFFFFFFFFu;     // kernel classes that are timed while prof_on
     std::vector<hipEvent_t> prof_events;          // pool, two per timed launch
     std::vector<int> prof_class;                  // class of each recorded launch
@@ -42,6 +45,7 @@ using namespace hr;
 
 constexpr int64_t kGenericMaxKeys = 15000;     // scores of one row live in LDS in the generic attention
 constexpr int64_t kMfmaMaxKeys = 1 << 20;
+constexpr int64_t kSplitMinTokens = 8192;      // query tokens from which a scoring call is cut in two halves
 
 thread_local char g_last_error[256] = "";
 
@@ -320,6 +324,8 @@ int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* w, void* pack
     m->no_last_short = nls && nls[0] == '1';
     const char* ndg = getenv("HR_NO_DOC_GROUPS");
     m->no_doc_groups = ndg && ndg[0] == '1';
+    const char* ns = getenv("HR_STREAMS");               // "1": scoring calls stay on the caller's stream (profiling runs)
+    if (ns && ns[0] == '1') m->n_streams = 1;
 
     hipStream_t st = (hipStream_t)stream;
     const int dt = cfg->dtype;
@@ -350,6 +356,12 @@ void hr_model_destroy(hr_model* m) {
     if (!m) return;
     if (m->stage_pending) (void)hipEventSynchronize(m->stage_ev);
     if (m->stage_ev) (void)hipEventDestroy(m->stage_ev);
+    if (m->aux_stream) {
+        (void)hipStreamSynchronize(m->aux_stream);
+        (void)hipStreamDestroy(m->aux_stream);
+    }
+    if (m->fork_ev) (void)hipEventDestroy(m->fork_ev);
+    if (m->join_ev) (void)hipEventDestroy(m->join_ev);
     if (m->stage) (void)hipHostFree(m->stage);
     for (hipEvent_t e : m->prof_events) (void)hipEventDestroy(e);
     delete m;
@@ -426,9 +438,56 @@ int hr_kv_pages_in(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, cons
 
 size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t total_q_tokens, int32_t pt_stride) {
     if (!m || n_pairs < 0 || total_q_tokens < 0 || pt_stride < 0) return 0;
+    // + room for the per-part alignment when the call runs as two halves (each with its own carving)
     return hr::make_workspace(m->cfg, n_pairs, total_q_tokens, pt_stride, !m->mfma_gemm, -1, 0,
                               (int64_t)hr::group_plan_ints_bound(n_pairs, total_q_tokens, m->cfg.n_q_heads / m->cfg.n_kv_heads))
-        .total;
+               .total + (m->mfma_gemm ? (size_t)256 * 1024 : 0);
+}
+
+// One contiguous part of a scoring call.  prepare: its metadata (already validated) is built at `stage` and its upload to the
+// head of `wsb` is enqueued on `st`; run: the layers are enqueued (on any stream ordered behind the upload).  ws / ml are
+// the part's own carving.
+struct ScorePart {
+    hr::MetaView mv{};
+    hr::GroupView gv{};
+    int max_keys = 0;
+};
+
+static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
+                              const int32_t* query_tokens, const int32_t* query_lens, int64_t T, bool mfma_attn, const hr::Workspace& ws,
+                              const hr::MetaLayout& ml, int64_t grp_ints, int32_t* stage, char* wsb, hipStream_t st, ScorePart* out) {
+    hr::fill_meta(stage, ml, n_pairs, doc_lens, query_lens, query_tokens, page_table, pt_stride);
+    // Pairs that share a document become one attention work item per kv head (up to 16 row blocks at 64-wide heads,
+    // 8 at 128-wide heads, where two blocks per wave do not fit the register file at two waves per SIMD).
+    const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
+    hr::GroupView& gv = out->gv;
+    if (mfma_attn && !m->no_doc_groups && pt_stride > 0) {
+        const hr::GroupPlan plan = hr::make_group_plan(n_pairs, doc_lens, query_lens, page_table, pt_stride, g, m->cfg.head_dim == 64 ? 16 : 8);
+        if (plan.shared && plan.ints() <= (size_t)grp_ints) {
+            hr::store_group_plan(plan, stage + ml.grp);
+            const int32_t* dv = (const int32_t*)(wsb + ws.off_meta) + ml.grp;
+            gv.n_groups = plan.n_groups;
+            gv.max_blocks = plan.max_blocks;
+            gv.p0 = dv;                              dv += plan.p0.size();
+            gv.blk_cu = dv;                          dv += plan.blk_cu.size();
+            gv.sub_cu = dv;                          dv += plan.sub_cu.size();
+            gv.blk_seq = dv;                         dv += plan.blk_seq.size();
+            gv.blk_row0 = dv;                        dv += plan.blk_row0.size();
+            gv.sub_page = dv;                        dv += plan.sub_page.size();
+            gv.sub_seq = dv;                         dv += plan.sub_seq.size();
+            gv.sub_key0 = dv;
+        }
+    }
+    HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, stage, ml.total * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    for (int32_t p = 0; p < n_pairs; ++p) out->max_keys = std::max(out->max_keys, doc_lens[p] + query_lens[p]);
+    out->mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, n_pairs, T, pt_stride);
+    return HR_OK;
+}
+
+static int run_score_part(hr_model* m, const hr_pool* pool, const ScorePart& part, const hr::Workspace& ws, char* wsb, int max_q,
+                          float* scores_dev, hipStream_t st) {
+    return run_layers(m, pool, false, part.mv, ws, wsb, part.max_keys, max_q, scores_dev, st, nullptr,
+                      part.gv.n_groups > 0 ? &part.gv : nullptr);
 }
 
 int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride,
@@ -448,43 +507,81 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     if ((uintptr_t)workspace_dev % hr::kAlign != 0) return HR_ERR_INVALID_ARG;
     const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     const int64_t grp_ints = (int64_t)hr::group_plan_ints_bound(n_pairs, T, g);
-    hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints);
+    const hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints);
     if (workspace_bytes < ws.total) return HR_ERR_WORKSPACE_SMALL;
-
     hipStream_t st = (hipStream_t)stream;
-    hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, pt_stride, -1, 0, grp_ints);
-    rc = stage_reserve(m, ml.total);
-    if (rc != HR_OK) return rc;
-    hr::fill_meta(m->stage, ml, n_pairs, doc_lens, query_lens, query_tokens, page_table, pt_stride);
-    // Pairs that share a document become one attention work item per kv head (up to 16 row blocks at 64-wide heads,
-    // 8 at 128-wide heads, where two blocks per wave do not fit the register file at two waves per SIMD).
-    hr::GroupView gv{};
-    if (mfma_attn && !m->no_doc_groups && pt_stride > 0) {
-        const hr::GroupPlan plan = hr::make_group_plan(n_pairs, doc_lens, query_lens, page_table, pt_stride, g, m->cfg.head_dim == 64 ? 16 : 8);
-        if (plan.shared && plan.ints() <= (size_t)grp_ints) {
-            hr::store_group_plan(plan, m->stage + ml.grp);
-            const int32_t* dv = (const int32_t*)((char*)workspace_dev + ws.off_meta) + ml.grp;
-            gv.n_groups = plan.n_groups;
-            gv.max_blocks = plan.max_blocks;
-            gv.p0 = dv;                              dv += plan.p0.size();
-            gv.blk_cu = dv;                          dv += plan.blk_cu.size();
-            gv.sub_cu = dv;                          dv += plan.sub_cu.size();
-            gv.blk_seq = dv;                         dv += plan.blk_seq.size();
-            gv.blk_row0 = dv;                        dv += plan.blk_row0.size();
-            gv.sub_page = dv;                        dv += plan.sub_page.size();
-            gv.sub_seq = dv;                         dv += plan.sub_seq.size();
-            gv.sub_key0 = dv;
+    char* wsb = (char*)workspace_dev;
+
+    // Two halves on two streams.  Every GEMM of a call ends with a round of tiles that fills only part of the chip (e.g.
+    // 1120 tiles on 512 resident workgroups), and the next kernel of the same stream cannot start before it is over; with
+    // the pairs cut in two halves that run on two streams, one half's kernels start on the CUs the other half's last
+    // round leaves idle.  A pair's arithmetic does not depend on the batch around it, so the scores are bit for bit the
+    // same.  Only when both halves still fill the chip on their own, and only on the MFMA path.
+    int32_t n_a = n_pairs;
+    int64_t T_a = T;
+    if (m->n_streams >= 2 && m->mfma_gemm && mfma_attn && n_pairs >= 2 && T >= kSplitMinTokens) {
+        int64_t t = 0;
+        int32_t p = 0;
+        while (p < n_pairs - 1 && t < T / 2) t += query_lens[p++];
+        if (p >= 1 && t >= kSplitMinTokens / 4 && T - t >= kSplitMinTokens / 4) {
+            n_a = p;
+            T_a = t;
         }
     }
-    char* wsb = (char*)workspace_dev;
-    HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, m->stage, ml.total * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    if (n_a < n_pairs) {
+        const int32_t n_b = n_pairs - n_a;
+        const int64_t T_b = T - T_a;
+        const int64_t gi_a = (int64_t)hr::group_plan_ints_bound(n_a, T_a, g), gi_b = (int64_t)hr::group_plan_ints_bound(n_b, T_b, g);
+        const hr::Workspace ws_a = hr::make_workspace(m->cfg, n_a, T_a, pt_stride, false, -1, 0, gi_a);
+        const hr::Workspace ws_b = hr::make_workspace(m->cfg, n_b, T_b, pt_stride, false, -1, 0, gi_b);
+        if (ws_a.total + ws_b.total <= workspace_bytes) {
+            const hr::MetaLayout ml_a = hr::make_meta_layout(n_a, T_a, pt_stride, -1, 0, gi_a);
+            const hr::MetaLayout ml_b = hr::make_meta_layout(n_b, T_b, pt_stride, -1, 0, gi_b);
+            rc = stage_reserve(m, ml_a.total + ml_b.total);
+            if (rc != HR_OK) return rc;
+            if (!m->aux_stream) {
+                HR_HIP(hipStreamCreateWithFlags(&m->aux_stream, hipStreamNonBlocking));
+                HR_HIP(hipEventCreateWithFlags(&m->fork_ev, hipEventDisableTiming));
+                HR_HIP(hipEventCreateWithFlags(&m->join_ev, hipEventDisableTiming));
+            }
+            // both parts' metadata go up on the caller's stream (the host may then reuse the staging buffer and run ahead
+            // of the device); the second stream starts behind them, and the caller's stream ends behind the second half
+            ScorePart pa, pb;
+            char* wsb_b = wsb + ws_a.total;
+            rc = prepare_score_part(m, n_a, page_table, pt_stride, doc_lens, query_tokens, query_lens, T_a, mfma_attn, ws_a, ml_a, gi_a,
+                                    m->stage, wsb, st, &pa);
+            if (rc == HR_OK)
+                rc = prepare_score_part(m, n_b, page_table ? page_table + (size_t)n_a * pt_stride : nullptr, pt_stride, doc_lens + n_a,
+                                        query_tokens + T_a, query_lens + n_a, T_b, mfma_attn, ws_b, ml_b, gi_b, m->stage + ml_a.total,
+                                        wsb_b, st, &pb);
+            HR_HIP(hipEventRecord(m->stage_ev, st));
+            m->stage_pending = true;
+            if (rc != HR_OK) return rc;
+            HR_HIP(hipEventRecord(m->fork_ev, st));
+            HR_HIP(hipStreamWaitEvent(m->aux_stream, m->fork_ev, 0));
+            const int rc_a = run_score_part(m, pool, pa, ws_a, wsb, max_q, scores_dev, st);
+            const int rc_b = run_score_part(m, pool, pb, ws_b, wsb_b, max_q, scores_dev + n_a, m->aux_stream);
+            HR_HIP(hipEventRecord(m->join_ev, m->aux_stream));
+            HR_HIP(hipStreamWaitEvent(st, m->join_ev, 0));
+            return rc_a != HR_OK ? rc_a : rc_b;
+        }
+    }
+    const hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, pt_stride, -1, 0, grp_ints);
+    rc = stage_reserve(m, ml.total);
+    if (rc != HR_OK) return rc;
+    ScorePart part;
+    rc = prepare_score_part(m, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens, T, mfma_attn, ws, ml, grp_ints,
+                            m->stage, wsb, st, &part);
     HR_HIP(hipEventRecord(m->stage_ev, st));
     m->stage_pending = true;
+    if (rc != HR_OK) return rc;
+    return run_score_part(m, pool, part, ws, wsb, max_q, scores_dev, st);
+}
 
-    int max_keys = 0;
-    for (int32_t p = 0; p < n_pairs; ++p) max_keys = std::max(max_keys, doc_lens[p] + query_lens[p]);
-    hr::MetaView mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, n_pairs, T, pt_stride);
-    return run_layers(m, pool, false, mv, ws, wsb, max_keys, max_q, scores_dev, st, nullptr, gv.n_groups > 0 ? &gv : nullptr);
+int hr_rerank_set_streams(hr_model* m, int n_streams) {
+    if (!m || n_streams < 1 || n_streams > 2) return HR_ERR_INVALID_ARG;
+    m->n_streams = n_streams;
+    return HR_OK;
 }
 
 int hr_rerank_validate(const hr_model_cfg* cfg, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table,

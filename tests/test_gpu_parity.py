@@ -328,6 +328,45 @@ def test_pairs_sharing_a_document_are_batched_bit_identically(d, n_q, n_kv, kv, 
     np.testing.assert_array_equal(scores[0], scores[1])
 
 
+def test_two_stream_halves_are_bit_identical_and_ordered_on_the_callers_stream():
+    """A call with more than 8192 query tokens runs as two halves on two streams.  Scores must equal the single-stream
+    run bit for bit and the oracle within the bar, work enqueued behind the call on the caller's stream (here the
+    per-query top-k) must see both halves' scores, and the per-kernel timing must survive launches on two streams."""
+    import torch
+    from paper_2504_02921_amd import binding as hb
+    model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=4, n_kv=2, d=64, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("two_streams", model, 24, 12, (5, 120), (20, 44), "bf16", pool_docs=40, zipf_a=0.8, seed=51)
+    w = wlmod.SeededWeights(model, seed=52, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(cfg, spare_pages=3)
+    assert wl.total_q_tokens >= 8192
+    case = H.Case(wl, w)
+    try:
+        case.fill_from_prefill()
+        seg = np.arange(0, wl.n_pairs + 1, cfg.n_cands)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):                         # a stream of the caller's own, not the default one
+            s2 = case.model.score(case.pool, wl.page_table, wl.doc_lens, wl.query_tokens, wl.query_lens)
+            top2 = hb.rerank_topk(s2, seg, 3)
+        side.synchronize()
+        case.model.set_streams(1)
+        s1 = case.gpu_scores()
+        np.testing.assert_array_equal(s2.cpu().numpy().astype(np.float64), s1)
+        np.testing.assert_array_equal(top2.cpu().numpy(), orr.topk(s1, seg, 3))
+        idx = np.random.default_rng(3).choice(wl.n_pairs, 24, replace=False)
+        H.assert_scores_close(s1[idx], case.oracle_scores(wl.subset(idx)), H.TOL["bf16"], "two-stream halves")
+        case.model.set_streams(2)
+        case.model.profile_enable(True)
+        s3 = case.gpu_scores()
+        prof = case.model.profile_read()
+        case.model.profile_enable(False)
+        np.testing.assert_array_equal(s3, s1)
+        assert prof["attention"]["launches"] == 2 * model.n_layers and prof["attention"]["ms"] > 0
+        with pytest.raises(hb.HrError):
+            case.model.set_streams(3)
+    finally:
+        case.close()
+
+
 @pytest.mark.parametrize("kv", ["f32", "bf16", "fp8"])
 def test_host_tier_round_trip_keeps_pages_and_scores(kv):
     """Documents are evicted to pinned host memory as page records, their pages freed, and paged in again at other
