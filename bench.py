@@ -123,6 +123,10 @@ def main():
         model.set_streams(streams)
         step()
         torch.cuda.synchronize()
+    # no collector pause inside a timed region (a full collection over the workload's arrays takes ~45 ms, two steps)
+    import gc
+    gc.collect()
+    gc.disable()
     t1 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -153,6 +157,7 @@ def main():
         model.set_streams(streams)
     model.profile_enable(False)
     model.profile_select(None)
+    gc.enable()
 
     # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (recorded summary, see profiles/)
     traffic = {}

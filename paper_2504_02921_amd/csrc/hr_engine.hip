@@ -133,9 +133,10 @@ struct PrefillTarget {
 //   fill         if set, every layer's K/V pages are copied into that pool and the pass stops after the last
 //                layer's K/V (no scores)
 //   groups       if set, the attention work items are these groups of sequences with one shared document
+//   after_qkv0   if set, recorded on `st` behind the first layer's QKV projection
 int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaView& mv, const Workspace& ws, char* wsb,
                int max_keys, int max_new_len, float* scores, hipStream_t st, const PrefillTarget* fill = nullptr,
-               const GroupView* groups = nullptr) {
+               const GroupView* groups = nullptr, hipEvent_t after_qkv0 = nullptr) {
     const hr_model_cfg& c = m->cfg;
     const int dt = c.dtype;
     const int H = c.hidden, d = c.head_dim, F = c.ffn;
@@ -191,6 +192,7 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
             HR_TIMED(PC_GEMM_QKV, launch_gemm_generic(dt, y, layer_w(m, l, m->pack.wqkv), f32, T, nqkv, H, false, st));
             HR_TIMED(PC_ELEMENTWISE, launch_rope_split(dt, f32, rope, q, k, v, T, c.n_q_heads, c.n_kv_heads, d, st));
         }
+        if (l == 0 && after_qkv0) HR_HIP(hipEventRecord(after_qkv0, st));
         if (fill) {
             // this layer's K/V pages are final: store them, and stop once the last layer's are in
             const hr_pool* fp = fill->pool;
@@ -485,9 +487,9 @@ static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_
 }
 
 static int run_score_part(hr_model* m, const hr_pool* pool, const ScorePart& part, const hr::Workspace& ws, char* wsb, int max_q,
-                          float* scores_dev, hipStream_t st) {
+                          float* scores_dev, hipStream_t st, hipEvent_t after_qkv0 = nullptr) {
     return run_layers(m, pool, false, part.mv, ws, wsb, part.max_keys, max_q, scores_dev, st, nullptr,
-                      part.gv.n_groups > 0 ? &part.gv : nullptr);
+                      part.gv.n_groups > 0 ? &part.gv : nullptr, after_qkv0);
 }
 
 int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride,
@@ -516,10 +518,17 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     // 1120 tiles on 512 resident workgroups), and the next kernel of the same stream cannot start before it is over; with
     // the pairs cut in two halves that run on two streams, one half's kernels start on the CUs the other half's last
     // round leaves idle.  A pair's arithmetic does not depend on the batch around it, so the scores are bit for bit the
-    // same.  Only when both halves still fill the chip on their own, and only on the MFMA path.
+    // same.  Only when both halves still fill the chip on their own, only on the MFMA path, and only for calls small
+    // enough for the last rounds to matter.
     int32_t n_a = n_pairs;
     int64_t T_a = T;
-    if (m->n_streams >= 2 && m->mfma_gemm && mfma_attn && n_pairs >= 2 && T >= kSplitMinTokens) {
+    // Measured: the halves gain while the narrowest GEMMs of a layer (O and down projection, N = hidden) have few
+    // rounds of 256 x 256 tiles, where the partly filled last round is a large share (0.5B shape: -7.7 % at 1.25
+    // rounds, -2.4 % at 2.5, +0.6 % at 5; 8B shape: -6.7 % at 3.1 rounds, +0.5 % at 4.0, +7 % at 4.75 and 6.25: there two
+    // kernels that share the chip cost each other more than the rounds they fill).
+    const int64_t tiles_h = ((T + 255) / 256) * ((m->cfg.hidden + 255) / 256);
+    if (m->n_streams >= 2 && m->mfma_gemm && mfma_attn && n_pairs >= 2 && T >= kSplitMinTokens &&
+        2 * tiles_h <= 7 * (int64_t)hr::device_cu_count()) {
         int64_t t = 0;
         int32_t p = 0;
         while (p < n_pairs - 1 && t < T / 2) t += query_lens[p++];
@@ -544,8 +553,10 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
                 HR_HIP(hipEventCreateWithFlags(&m->fork_ev, hipEventDisableTiming));
                 HR_HIP(hipEventCreateWithFlags(&m->join_ev, hipEventDisableTiming));
             }
-            // both parts' metadata go up on the caller's stream (the host may then reuse the staging buffer and run ahead
-            // of the device); the second stream starts behind them, and the caller's stream ends behind the second half
+            // Both parts' metadata go up on the caller's stream (the host may then reuse the staging buffer and run ahead
+            // of the device).  The second stream starts behind the first half's first QKV projection, so that the halves
+            // run one kernel apart, each kernel starting on the CUs the other half's kernel is leaving, rather than as
+            // twin kernels side by side whose last rounds coincide; the caller's stream ends behind the second half.
             ScorePart pa, pb;
             char* wsb_b = wsb + ws_a.total;
             rc = prepare_score_part(m, n_a, page_table, pt_stride, doc_lens, query_tokens, query_lens, T_a, mfma_attn, ws_a, ml_a, gi_a,
@@ -557,9 +568,9 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
             HR_HIP(hipEventRecord(m->stage_ev, st));
             m->stage_pending = true;
             if (rc != HR_OK) return rc;
-            HR_HIP(hipEventRecord(m->fork_ev, st));
+            const int rc_a = run_score_part(m, pool, pa, ws_a, wsb, max_q, scores_dev, st, m->fork_ev);
+            if (rc_a != HR_OK) return rc_a;
             HR_HIP(hipStreamWaitEvent(m->aux_stream, m->fork_ev, 0));
-            const int rc_a = run_score_part(m, pool, pa, ws_a, wsb, max_q, scores_dev, st);
             const int rc_b = run_score_part(m, pool, pb, ws_b, wsb_b, max_q, scores_dev + n_a, m->aux_stream);
             HR_HIP(hipEventRecord(m->join_ev, m->aux_stream));
             HR_HIP(hipStreamWaitEvent(st, m->join_ev, 0));

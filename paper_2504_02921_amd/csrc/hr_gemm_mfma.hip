@@ -551,6 +551,8 @@ bool prefer_big(int64_t M, int N, int small_bn) {
 
 }  // namespace
 
+int device_cu_count() { return cu_count(); }
+
 bool gemm_mfma_supported(const hr_model_cfg& c) {
     if (c.dtype != HR_BF16) return false;
     if (c.head_dim != 64 && c.head_dim != 128) return false;

@@ -55,6 +55,7 @@ hipError_t launch_pack_rows(int dtype, const void* src, void* dst, int rows, int
 
 // ---- MFMA paths (bf16) ----
 bool gemm_mfma_supported(const hr_model_cfg& c);
+int device_cu_count();      // compute units of the current device (256 if it cannot be asked)
 enum GemmEpilogue { EPI_QKV_ROPE = 0, EPI_RESID_ADD = 1, EPI_SWIGLU = 2 };
 struct GemmArgs {
     const void* A;      // [M][K] bf16
