@@ -36,11 +36,6 @@ typedef __attribute__((ext_vector_type(2))) float floatx2;
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* gbl_ptr_t;
 
-#ifdef HR_ATTN_TRACE
-__device__ long long* g_attn_trace_dev = nullptr;
-long long* g_attn_trace = nullptr;
-#endif
-
 namespace {
 
 // LDS stage: 32 KiB of half pages; an fp8 pool streams the same number of keys per stage in 16 KiB and spends the
@@ -134,19 +129,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     float* s_scale = (float*)(smem + 2 * kStageBytes);              // [2][PPS][2]  (fp8 only)
     char* hbuf = smem + 2 * kStageBytes + 2 * G::PPS * 2 * sizeof(float);   // fp8 only: the current stage as half pages
 
-#ifdef HR_ATTN_TRACE
-    long long* trace = (blockIdx.x == 100 && threadIdx.x == 0) ? g_attn_trace_dev : nullptr;
-    int tp = 0;
-#define HR_ASTAMP() do { if (trace && tp < 900) trace[tp++] = __builtin_readcyclecounter(); } while (0)
-#ifdef HR_ATTN_TRACE2
-#define HR_PSTAMP() HR_ASTAMP()
-#else
-#define HR_PSTAMP() do { } while (0)
-#endif
-#else
-#define HR_PSTAMP() do { } while (0)
-#define HR_ASTAMP() do { } while (0)
-#endif
     const int n_kv = pv.n_kv;
     const int g = n_q / n_kv;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -310,9 +292,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             } else {
                 *(halfx8*)(dpage + GN::BLOCK_BYTES + (w - KU) * 16) = fp8x8_to_half(src, fp8_expand_factor(sc[page * 2 + 1]));
             }
-#ifdef HR_ATTN_TRACE3
-            HR_PSTAMP();
-#endif
         }
     };
 
@@ -322,9 +301,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     // `sb` holds half pages; scaled_tag: they were expanded from fp8 codes and `sc` carries the pages' scales.
     // on[rb]: the wave's block rb takes part; nv[rb]: keys of the sub-tile that exist for it.
     auto process = [&](auto scaled_tag, auto causal_tag, const char* sb, int st, const bool (&on)[R], const int (&nv)[R], const float* sc) {
-#ifdef HR_ATTN_SKIP_COMPUTE
-        return;      // memory-structure probe: stream the pages, do no arithmetic
-#endif
         constexpr bool KV8 = decltype(scaled_tag)::value;
         constexpr bool CAUSAL = decltype(causal_tag)::value;
         using GG = GN;
@@ -351,7 +327,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
         // fp8 pages: K scale goes into the softmax exponent (fp32).  The V scale is split into its power of two,
         // applied exactly while the codes were expanded, and its mantissa in [1, 2), applied to the probabilities:
         // folding the whole scale (~1e-2) into P would push probabilities into the subnormal range of half.
-        HR_PSTAMP();
         float cs0 = c_log2, cs1 = c_log2, vs0 = 1.f, vs1 = 1.f;
         if constexpr (KV8) {
             cs0 *= sc[(st * 2) * 2];
@@ -411,7 +386,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             }
             l_run[rb] = l_run[rb] * alpha + lsum;
             m_run[rb] = m_new;
-            HR_PSTAMP();
             if (__any(alpha != 1.0f)) {
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
@@ -432,7 +406,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                 oacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[mb][0], pf[0], oacc[rb][mb], 0, 0, 0);
                 oacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[mb][1], pf[1], oacc[rb][mb], 0, 0, 0);
             }
-            HR_PSTAMP();
         }
     };
 
@@ -483,7 +456,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
 
     int stage = 0;                                  // LDS stage that holds (or will hold) the current item's next tile
     ItemCtx cur = load_ctx(blockIdx.x);
-    HR_ASTAMP();
     if (cur.n_tiles > 0) ids_load(cur, 0);
     dma_first(cur, 0);
     ids_after(cur, 0, (int)blockIdx.x);
@@ -507,17 +479,13 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
         flush_out();                              // previous item's output: completes under this item's first stage
 
         for (int tile = 0; tile < cur.n_tiles; ++tile) {
-            HR_ASTAMP();
             const char* sb = smem + stage * kStageBytes;
             const float* sc = s_scale + stage * G::PPS * 2;
             if constexpr (FP8) {
                 // Before the next stage is requested: LDS accesses that follow a direct-to-LDS load in program order
                 // can be made to wait for it, and these would wait for a load that has just been issued.
-                HR_PSTAMP();
                 expand_stage(sb, sc);
-                HR_PSTAMP();
                 __syncthreads();
-                HR_PSTAMP();
                 sb = hbuf;
             }
             // every wave is past its reads of the other stage (barrier at the end of the previous iteration)
@@ -536,14 +504,12 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                 for (int rb = 0; rb < R; ++rb) nv[rb] = cur.D - key0;
                 process(std::integral_constant<bool, FP8>{}, std::false_type{}, sb, st, blk_on, nv, sc);
             }
-            HR_ASTAMP();
             if (tile + 1 < cur.n_tiles) scale_store(stage ^ 1);
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __syncthreads();
             stage ^= 1;
         }
         for (int nt = 0; nt < cur.n_new_tiles; ++nt) {
-            HR_ASTAMP();
             const bool last = nt + 1 == cur.n_new_tiles;
             if (!last) dma_new(cur, nt + 1, stage ^ 1);
             else if (has_next) {
@@ -574,7 +540,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
 #pragma unroll
                 for (int rb = 0; rb < R; ++rb) row_i[rb] += key0;
             }
-            HR_ASTAMP();
             if (!last) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);
                 __syncthreads();
@@ -605,7 +570,6 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
         }
         out_pending = true;
         if (has_next) setup_rows(nxt);
-        HR_ASTAMP();
         cur = nxt;
     }
     flush_out();
@@ -632,9 +596,6 @@ hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const Meta
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-#ifdef HR_ATTN_TRACE
-    (void)hipMemcpyToSymbolAsync(HIP_SYMBOL(g_attn_trace_dev), &g_attn_trace, sizeof(long long*), 0, hipMemcpyHostToDevice, st);
-#endif
     // persistent grid: as many workgroups as can be resident (LDS: two per CU), each loops over work items
     static int max_wgs = 0;
     if (max_wgs == 0) {

@@ -465,7 +465,9 @@ static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_
     hr::GroupView& gv = out->gv;
     if (mfma_attn && !m->no_doc_groups && pt_stride > 0) {
         const hr::GroupPlan plan = hr::make_group_plan(n_pairs, doc_lens, query_lens, page_table, pt_stride, g, m->cfg.head_dim == 64 ? 16 : 8);
-        if (plan.shared && plan.ints() <= (size_t)grp_ints) {
+        // also without a shared document when the pairs differ in length: the plan's heaviest-first order keeps the
+        // persistent workgroups' last items short
+        if ((plan.shared || plan.uneven) && plan.ints() <= (size_t)grp_ints) {
             hr::store_group_plan(plan, stage + ml.grp);
             const int32_t* dv = (const int32_t*)(wsb + ws.off_meta) + ml.grp;
             gv.n_groups = plan.n_groups;

@@ -419,15 +419,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bfr[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
     };
 
-#ifdef HR_GEMM_TRACE
-    long long* trace = (blockIdx.x == 8 && tid == 0) ? (long long*)a.out2 : nullptr;   // out2 is unused outside the QKV epilogue
-    int tp = 0;
-#define HR_STAMP() do { if (trace) trace[tp++] = __builtin_readcyclecounter(); } while (0)
-#else
-#define HR_STAMP() do { } while (0)
-#endif
     const int nk = K / BK;
-    HR_STAMP();
     dma(0, 0);
     for (;;) {                                // one tile per pass; a single pass unless PERSIST
 #pragma unroll
@@ -443,7 +435,6 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
         const bool more = kt + 1 < nk;
-        HR_STAMP();
         if (more) dma(kt + 1, cur ^ 1);
         const half_t* cA = sA + cur * BM * BK;
         const half_t* cB = sB + cur * BN * BK;
@@ -458,17 +449,14 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
             }
             __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - (MI + NI), 0);
         }
-        HR_STAMP();
         // the next k-tile has landed (own loads) and every wave is past its last read of the other stage
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        HR_STAMP();
         if (more) fload(KS & 1, sA + (cur ^ 1) * BM * BK, sB + (cur ^ 1) * BN * BK, 0);
         mfmas((KS - 1) & 1);
         static_assert(KS % 2 == 0, "slot parity of the first fragment of a tile");
     }
 
-    HR_STAMP();
     // ---- epilogue: lane owns output row (lane & 31) of each block; register r holds column 8*(r>>2) + 4*(lane>>5) + (r&3)
     const int64_t tile_m0 = m0;               // the epilogue's tile; m0 / n0 move on to the next one below
     const int tile_n0 = n0;
@@ -483,7 +471,6 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
         }
     }
     gemm_epilogue<EPI, BM, BN, WM, WN, HB>(acc, a, smem, tile_m0, tile_n0);
-    HR_STAMP();
     if (!has_next) break;
     }
 }

@@ -320,6 +320,7 @@ GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32
             groups[gi].cost = ((int64_t)prefix_lens[lead] + 64) * groups[gi].blocks;
         i = j;
     }
+    for (const Grp& gr : groups) gp.uneven = gp.uneven || gr.cost != groups[0].cost;
     std::stable_sort(groups.begin(), groups.end(), [](const Grp& a, const Grp& b) { return a.cost > b.cost; });
 
     // start of every sequence's pages in the new-KV buffer: each sequence begins on a 32-slot boundary (fill_meta)

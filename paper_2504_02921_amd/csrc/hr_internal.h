@@ -123,6 +123,7 @@ struct GroupPlan {
                                                          // sequence, first new-key index
     int32_t n_groups = 0, max_blocks = 0;
     bool shared = false;                     // some group holds more than one sequence
+    bool uneven = false;                     // the groups differ in work: the heaviest-first order is worth having
     size_t ints() const {
         return p0.size() + blk_cu.size() + sub_cu.size() + 2 * blk_seq.size() + 3 * sub_page.size();
     }

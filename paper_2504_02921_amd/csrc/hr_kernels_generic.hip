@@ -347,6 +347,7 @@ __global__ void __launch_bounds__(256) kv_scatter_kernel(KVT* __restrict__ pool,
 template <typename S, typename D>
 __global__ void pack_rows_kernel(const S* __restrict__ src, D* __restrict__ dst, int rows, int cols, int ib, int mul, int sel) {
     int r = blockIdx.x;
+    if (r >= rows) return;
     size_t drow = ((size_t)(r / ib) * mul + sel) * ib + r % ib;
     for (int c = threadIdx.x; c < cols; c += blockDim.x) dst[drow * cols + c] = from_float<D>(to_float<S>(src[(size_t)r * cols + c]));
 }

@@ -102,6 +102,10 @@ int main() {
         std::vector<int32_t> ud = {16, 16, 16}, uq = {4, 4, 4};
         hr::GroupPlan up = hr::make_group_plan(3, ud.data(), uq.data(), upt.data(), 1, g, cap);
         CHECK(!up.shared && up.n_groups == 3 && up.max_blocks == 1);
+        CHECK(!up.uneven && gp.uneven);
+        std::vector<int32_t> rd = {16, 48, 32};                   // nothing shared, lengths differ: heaviest first
+        hr::GroupPlan rp = hr::make_group_plan(3, rd.data(), uq.data(), upt.data(), 1, g, cap);
+        CHECK(!rp.shared && rp.uneven && rp.p0[0] == 1 && rp.p0[1] == 2 && rp.p0[2] == 0);
     }
     // pool bookkeeping and validation paths
     hr_pool_cfg pc{2, 2, 64, 16, 8, HR_BF16};
