@@ -475,6 +475,124 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
     }
 }
 
+// Small-M variant: the same tile arithmetic with a ring of NS LDS stages.  With fewer tiles than CUs a tile has its
+// CU to itself and the two-stage loop above is bound by latency (one load round trip, ~1 us, per k-tile: the down
+// projection's 76 k-tiles alone are 77 us for 640 rows); with NS - 1 k-tiles in flight the loop runs at the rate the
+// direct-to-LDS path delivers.  Vector memory operations complete in order, so "k-tile kt has landed" is a wait
+// until at most the loads of the NS - 2 younger k-tiles are outstanding; the one barrier per k-tile also tells that
+// every wave is done with the stage of k-tile kt - 1, which is where k-tile kt + NS - 1 goes.  Same operand order and
+// same k order as the kernel above: an output element gets the same bits from either.
+template <int EPI, int BM, int BN, int WM, int WN, int HB, int NS>
+__global__ void __launch_bounds__(WM * WN * 64) gemm_ring_kernel(GemmArgs a) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int RPP = NT / 8;
+    constexpr int PA = BM / RPP, PB = BN / RPP;
+    constexpr int KS = BK / 16;
+    constexpr int LPT = PA + PB;                    // loads per thread and k-tile
+    constexpr int AHEAD = (NS - 2) * LPT;           // loads that may still be outstanding when a k-tile is consumed
+    static_assert(RPP % 16 == 0 && BM % RPP == 0 && BN % RPP == 0, "loader shape");
+    static_assert(NS >= 3 && AHEAD < 64, "the load counter has six bits");
+    constexpr int kWaitAhead = (AHEAD & 15) | ((AHEAD >> 4) << 14) | 0x0F70;     // s_waitcnt vmcnt(AHEAD) only
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    half_t* sA = (half_t*)smem;                         // [NS][BM][BK]
+    half_t* sB = sA + NS * BM * BK;                     // [NS][BN][BK]
+
+    const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (a.N + BN - 1) / BN;
+    const TileCoord tc = map_tile(blockIdx.x, tiles_m, tiles_n);
+    if (!tc.valid) return;
+    const int64_t m0 = (int64_t)tc.tm * BM;
+    const int n0 = tc.tn * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int K = a.K;
+    const half_t* A = (const half_t*)a.A;
+    const half_t* W = (const half_t*)a.W;
+
+    const int lrow = tid >> 3;
+    const int lchunk = (tid & 7) ^ ((lrow >> 1) & 7);
+    const half_t* pa[PA];
+    const half_t* pb[PB];
+#pragma unroll
+    for (int p = 0; p < PA; ++p) {
+        int64_t r = m0 + p * RPP + lrow;
+        r = r < a.M ? r : a.M - 1;
+        pa[p] = A + r * K + lchunk * 8;
+    }
+#pragma unroll
+    for (int p = 0; p < PB; ++p) {
+        int r = n0 + p * RPP + lrow;
+        r = r < a.N ? r : a.N - 1;
+        pb[p] = W + (size_t)r * K + lchunk * 8;
+    }
+    auto dma = [&](int kt, int buf) {
+        half_t* da = sA + buf * BM * BK + wave * 64 * 8;
+        half_t* db = sB + buf * BN * BK + wave * 64 * 8;
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pa[p] + kt * BK), (lds_ptr_t)(da + p * NT * 8), 16, 0, 0);
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pb[p] + kt * BK), (lds_ptr_t)(db + p * NT * 8), 16, 0, 0);
+    };
+
+    floatx16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    const int frow = lane & 31, fh = lane >> 5;
+    const int a_row0 = wm * TM + frow;
+    const int b_row0 = wn * TN + frow;
+    const int sw = (frow >> 1) & 7;
+    halfx8 af[2][MI], bfr[2][NI];
+    auto fload = [&](int slot, const half_t* cA, const half_t* cB, int kk) {
+        const int pch = ((kk * 2 + fh) ^ sw) * 8;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) af[slot][i] = *(const halfx8*)(cA + (a_row0 + i * 32) * BK + pch);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) bfr[slot][j] = *(const halfx8*)(cB + (b_row0 + j * 32) * BK + pch);
+    };
+    auto mfmas = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(bfr[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
+    };
+
+    const int nk = K / BK;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nk) dma(s, s);
+    int cur = 0;                                   // stage of k-tile kt
+    for (int kt = 0; kt < nk; ++kt) {
+        // own loads of k-tile kt have landed: in the steady state the NS - 2 younger k-tiles may be outstanding; once no
+        // new loads are issued everything is simply waited for
+        if (kt + NS - 2 < nk) __builtin_amdgcn_s_waitcnt(kWaitAhead);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        // LDS-only barrier (a __syncthreads() would wait for the loads in flight as well)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        const int nxt = kt + NS - 1;
+        if (nxt < nk) dma(nxt, cur == 0 ? NS - 1 : cur - 1);       // the stage k-tile kt - 1 was read from
+        const half_t* cA = sA + cur * BM * BK;
+        const half_t* cB = sB + cur * BN * BK;
+        fload(0, cA, cB, 0);
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            if (kk + 1 < KS) fload((kk + 1) & 1, cA, cB, kk + 1);
+            mfmas(kk & 1);
+        }
+        cur = cur + 1 == NS ? 0 : cur + 1;
+    }
+    __syncthreads();                               // every wave is done reading the stages before the epilogue reuses them
+    gemm_epilogue<EPI, BM, BN, WM, WN, HB>(acc, a, smem, m0, n0);
+}
+
 int cu_count();
 int tuning_variant();
 
@@ -499,6 +617,22 @@ hipError_t launch_tile(const GemmArgs& a, hipStream_t st) {
         attr_set = true;
     }
     gemm_mfma_kernel<EPI, BM, BN, WM, WN, HB><<<dim3((unsigned)grid), WM * WN * 64, lds, st>>>(a);
+    return hipGetLastError();
+}
+
+template <int EPI, int BM, int BN, int WM, int WN, int HB, int NS>
+hipError_t launch_ring(const GemmArgs& a, hipStream_t st) {
+    const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (a.N + BN - 1) / BN;
+    const int grid = (tiles_m * tiles_n + kXcds - 1) / kXcds * kXcds;
+    const size_t lds = (size_t)NS * (BM + BN) * BK * sizeof(half_t);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_ring_kernel<EPI, BM, BN, WM, WN, HB, NS>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    gemm_ring_kernel<EPI, BM, BN, WM, WN, HB, NS><<<dim3((unsigned)grid), WM * WN * 64, lds, st>>>(a);
     return hipGetLastError();
 }
 
@@ -554,6 +688,25 @@ hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st)
     if (a.K % BK != 0) return hipErrorInvalidValue;
     const int var = tuning_variant();
     const bool wide_head = epi == EPI_QKV_ROPE && a.d == 128;       // a wave must span a whole 128-wide head
+    // Few rows: when even 128 x 128 tiles do not give every CU one, the ring variants take over.  64-row tiles double
+    // the tile count; they pay when that still fits one round of the chip (a ring workgroup has its CU to itself),
+    // otherwise 128-row tiles with fewer, larger k-steps do (modelled as rounds x bytes per k-tile).
+    const int64_t tiles128 = ((a.M + 127) / 128) * ((a.N + (wide_head ? 255 : 127)) / (wide_head ? 256 : 128));
+    if (var < 0 && tiles128 < cu_count()) {
+        const int64_t cus = cu_count();
+        const int64_t t64 = ((a.M + 63) / 64) * ((a.N + (wide_head ? 255 : 127)) / (wide_head ? 256 : 128));
+        if (wide_head) return launch_ring<EPI_QKV_ROPE, 64, 256, 2, 2, 2, 3>(a, st);
+        const int64_t cost64 = ((t64 + cus - 1) / cus) * (64 + 128), cost128 = ((tiles128 + cus - 1) / cus) * (128 + 128);
+        const bool r64 = cost64 <= cost128;
+        switch (epi) {
+            case EPI_QKV_ROPE:
+                return r64 ? launch_ring<EPI_QKV_ROPE, 64, 128, 2, 2, 1, 5>(a, st) : launch_ring<EPI_QKV_ROPE, 128, 128, 2, 2, 1, 4>(a, st);
+            case EPI_RESID_ADD:
+                return r64 ? launch_ring<EPI_RESID_ADD, 64, 128, 2, 2, 1, 5>(a, st) : launch_ring<EPI_RESID_ADD, 128, 128, 2, 2, 1, 4>(a, st);
+            case EPI_SWIGLU:
+                return r64 ? launch_ring<EPI_SWIGLU, 64, 128, 2, 2, 1, 5>(a, st) : launch_ring<EPI_SWIGLU, 128, 128, 2, 2, 1, 4>(a, st);
+        }
+    }
     bool big = prefer_big(a.M, a.N, wide_head ? 256 : 128);
     if (var == 0) big = true;
     if (var == 2) big = false;
