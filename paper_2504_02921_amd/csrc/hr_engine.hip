@@ -463,12 +463,18 @@ static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_
     // 8 at 128-wide heads, where two blocks per wave do not fit the register file at two waves per SIMD).
     const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     hr::GroupView& gv = out->gv;
+    size_t plan_ints = 0;                                    // of the room reserved for a plan, what this call uses
     if (mfma_attn && !m->no_doc_groups && pt_stride > 0) {
-        const hr::GroupPlan plan = hr::make_group_plan(n_pairs, doc_lens, query_lens, page_table, pt_stride, g, m->cfg.head_dim == 64 ? 16 : 8);
+        // few work items (less than half the CUs would get one): a pair's row blocks are spread over several work items
+        // of at most four, one per wave of the smallest kernel, each streaming the document for its share of the rows
+        const bool scarce = n_pairs <= hr::kGroupCutMaxSeqs && (int64_t)n_pairs * m->cfg.n_kv_heads * 2 <= hr::device_cu_count();
+        const int cap = scarce ? 4 : (m->cfg.head_dim == 64 ? 16 : 8);
+        const hr::GroupPlan plan = hr::make_group_plan(n_pairs, doc_lens, query_lens, page_table, pt_stride, g, cap, scarce);
         // also without a shared document when the pairs differ in length: the plan's heaviest-first order keeps the
         // persistent workgroups' last items short
-        if ((plan.shared || plan.uneven) && plan.ints() <= (size_t)grp_ints) {
+        if ((plan.shared || plan.uneven || plan.cut) && plan.ints() <= (size_t)grp_ints) {
             hr::store_group_plan(plan, stage + ml.grp);
+            plan_ints = plan.ints();
             const int32_t* dv = (const int32_t*)(wsb + ws.off_meta) + ml.grp;
             gv.n_groups = plan.n_groups;
             gv.max_blocks = plan.max_blocks;
@@ -482,7 +488,7 @@ static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_
             gv.sub_key0 = dv;
         }
     }
-    HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, stage, ml.total * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, stage, (ml.grp + plan_ints) * sizeof(int32_t), hipMemcpyHostToDevice, st));
     for (int32_t p = 0; p < n_pairs; ++p) out->max_keys = std::max(out->max_keys, doc_lens[p] + query_lens[p]);
     out->mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, n_pairs, T, pt_stride);
     return HR_OK;

@@ -273,13 +273,15 @@ ChunkPlan make_chunk_plan(int64_t n_seq, const int32_t* lens, int chunk) {
 }
 
 size_t group_plan_ints_bound(int64_t n_seq, int64_t T, int g) {
-    // every sequence adds at most one partial block and one partial sub-tile
-    const size_t nb = (size_t)(T * g / 32 + n_seq), ns = (size_t)(T / 32 + n_seq);
-    return (size_t)n_seq + 2 * ((size_t)n_seq + 1) + 2 * nb + 3 * ns;
+    // every sequence adds at most one partial block and one partial sub-tile; a call of few sequences may cut each of
+    // them into up to 16 groups (one per block), each of which lists the sequence's sub-tiles
+    const size_t cut = n_seq <= kGroupCutMaxSeqs ? 16 : 1;
+    const size_t nb = (size_t)(T * g / 32 + n_seq), ns = (size_t)(T / 32 + n_seq) * cut, ng = (size_t)n_seq * cut;
+    return ng + 2 * (ng + 1) + 2 * nb + 3 * ns;
 }
 
 GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* page_table,
-                          int64_t pt_stride, int g, int cap_blocks) {
+                          int64_t pt_stride, int g, int cap_blocks, bool cut_long) {
     GroupPlan gp;
     auto blocks_of = [&](int64_t p) { return (int)(((int64_t)new_lens[p] * g + 31) / 32); };
     auto pages_of = [&](int64_t p) { return ((int64_t)prefix_lens[p] + kPageTokens - 1) / kPageTokens; };
@@ -294,7 +296,8 @@ GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32
         if (prefix_lens[a] != prefix_lens[b]) return prefix_lens[a] < prefix_lens[b];
         return a < b;
     });
-    struct Grp { std::vector<int32_t> seqs; int blocks; int64_t cost; };
+    struct Piece { int32_t seq; int b0, nb; };               // blocks b0 .. b0 + nb - 1 of a sequence
+    struct Grp { std::vector<Piece> pieces; int blocks; int64_t cost; };
     std::vector<Grp> groups;
     for (int64_t i = 0; i < n_seq;) {
         // run of sequences whose rows equal the first one's (a sequence without a document is a run of its own)
@@ -305,16 +308,22 @@ GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32
                    std::memcmp(pt + (int64_t)order[j] * pt_stride, pt + (int64_t)lead * pt_stride,
                                sizeof(int32_t) * (size_t)pages_of(lead)) == 0)
                 ++j;
-        // first fit over the run's groups, sequences in index order
+        // first fit over the run's groups, sequences in index order; a sequence with more blocks than a group holds is a
+        // group of its own, or (cut_long) is cut into pieces of at most cap_blocks
         const size_t run_first = groups.size();
         for (int64_t k = i; k < j; ++k) {
             const int32_t p = order[k];
-            const int nb = blocks_of(p);
-            size_t gi = run_first;
-            while (gi < groups.size() && groups[gi].blocks + nb > cap_blocks) ++gi;
-            if (gi == groups.size()) groups.push_back(Grp{{}, 0, 0});
-            groups[gi].seqs.push_back(p);
-            groups[gi].blocks += nb;
+            const int nb_all = blocks_of(p);
+            const int step = cut_long ? cap_blocks : nb_all;
+            for (int b0 = 0; b0 < nb_all; b0 += step) {
+                const int nb = std::min(step, nb_all - b0);
+                size_t gi = run_first;
+                while (gi < groups.size() && groups[gi].blocks + nb > cap_blocks) ++gi;
+                if (gi == groups.size()) groups.push_back(Grp{{}, 0, 0});
+                groups[gi].pieces.push_back(Piece{p, b0, nb});
+                groups[gi].blocks += nb;
+                gp.cut = gp.cut || nb < nb_all;
+            }
         }
         for (size_t gi = run_first; gi < groups.size(); ++gi)
             groups[gi].cost = ((int64_t)prefix_lens[lead] + 64) * groups[gi].blocks;
@@ -334,17 +343,21 @@ GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32
     gp.blk_cu.push_back(0);
     gp.sub_cu.push_back(0);
     for (const Grp& gr : groups) {
-        gp.p0.push_back(gr.seqs[0]);
-        gp.shared = gp.shared || gr.seqs.size() > 1;
+        gp.p0.push_back(gr.pieces[0].seq);
         gp.max_blocks = std::max(gp.max_blocks, gr.blocks);
-        for (int32_t p : gr.seqs) {
-            for (int b = 0; b < blocks_of(p); ++b) {
-                gp.blk_seq.push_back(p);
+        for (size_t pi = 0; pi < gr.pieces.size(); ++pi) {
+            const Piece& pc = gr.pieces[pi];
+            for (int b = pc.b0; b < pc.b0 + pc.nb; ++b) {
+                gp.blk_seq.push_back(pc.seq);
                 gp.blk_row0.push_back(b * 32);
             }
-            for (int32_t k0 = 0; k0 < new_lens[p]; k0 += 32) {
-                gp.sub_page.push_back((int32_t)(new_page[p] + k0 / kPageTokens));
-                gp.sub_seq.push_back(p);
+            bool listed = false;                             // the sequence's own keys once per group
+            for (size_t pj = 0; pj < pi; ++pj) listed = listed || gr.pieces[pj].seq == pc.seq;
+            if (listed) continue;
+            gp.shared = gp.shared || pi > 0;
+            for (int32_t k0 = 0; k0 < new_lens[pc.seq]; k0 += 32) {
+                gp.sub_page.push_back((int32_t)(new_page[pc.seq] + k0 / kPageTokens));
+                gp.sub_seq.push_back(pc.seq);
                 gp.sub_key0.push_back(k0);
             }
         }

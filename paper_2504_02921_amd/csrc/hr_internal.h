@@ -124,15 +124,19 @@ struct GroupPlan {
     int32_t n_groups = 0, max_blocks = 0;
     bool shared = false;                     // some group holds more than one sequence
     bool uneven = false;                     // the groups differ in work: the heaviest-first order is worth having
+    bool cut = false;                        // some sequence's blocks are spread over several groups
     size_t ints() const {
         return p0.size() + blk_cu.size() + sub_cu.size() + 2 * blk_seq.size() + 3 * sub_page.size();
     }
 };
-// g: query heads per kv head; cap_blocks: most blocks a group may hold (a sequence with more is a group of its own).
+// g: query heads per kv head; cap_blocks: most blocks a group may hold.  A sequence with more blocks is a group of its
+// own, or, with cut_long (calls of at most kGroupCutMaxSeqs sequences, where work items are scarce), is cut into several
+// groups that each stream the document and the sequence's own keys for their share of its rows.
 // Groups come in order of decreasing work (document keys x blocks), so that a round-robin walk starts the long ones
 // first.
+constexpr int64_t kGroupCutMaxSeqs = 256;
 GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* page_table,
-                          int64_t pt_stride, int g, int cap_blocks);
+                          int64_t pt_stride, int g, int cap_blocks, bool cut_long = false);
 size_t group_plan_ints_bound(int64_t n_seq, int64_t T, int g);
 // Writes the plan at dst (>= plan.ints() entries) in the order p0, blk_cu, sub_cu, blk_seq, blk_row0, sub_page, sub_seq,
 // sub_key0.

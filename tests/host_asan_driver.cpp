@@ -103,6 +103,30 @@ int main() {
         hr::GroupPlan up = hr::make_group_plan(3, ud.data(), uq.data(), upt.data(), 1, g, cap);
         CHECK(!up.shared && up.n_groups == 3 && up.max_blocks == 1);
         CHECK(!up.uneven && gp.uneven);
+        // scarce work items: sequences are cut into pieces of at most 4 blocks; every (sequence, block) exactly once, and
+        // every group lists the own keys of each of its sequences exactly once
+        hr::GroupPlan cp4 = hr::make_group_plan(n, gd.data(), gq.data(), gpt.data(), stride, g, 4, true);
+        CHECK(cp4.cut && cp4.max_blocks <= 4 && cp4.ints() <= hr::group_plan_ints_bound(n, Tq, g));
+        std::vector<std::vector<char>> seen(n);
+        for (int64_t p = 0; p < n; ++p) seen[p].assign((gq[p] * g + 31) / 32, 0);
+        for (int gi = 0; gi < cp4.n_groups; ++gi) {
+            std::vector<int> subs_in_group(n, 0), blocks_in_group(n, 0);
+            for (int b = cp4.blk_cu[gi]; b < cp4.blk_cu[gi + 1]; ++b) {
+                const int32_t p = cp4.blk_seq[b];
+                CHECK(cp4.blk_row0[b] % 32 == 0 && cp4.blk_row0[b] / 32 < (int)seen[p].size() && !seen[p][cp4.blk_row0[b] / 32]);
+                seen[p][cp4.blk_row0[b] / 32] = 1;
+                CHECK(gd[p] == gd[cp4.p0[gi]]);
+                ++blocks_in_group[p];
+            }
+            for (int sidx = cp4.sub_cu[gi]; sidx < cp4.sub_cu[gi + 1]; ++sidx) {
+                const int32_t p = cp4.sub_seq[sidx];
+                CHECK(cp4.sub_key0[sidx] == 32 * subs_in_group[p] && cp4.sub_page[sidx] == new_page[p] + 2 * subs_in_group[p]);
+                ++subs_in_group[p];
+            }
+            for (int64_t p = 0; p < n; ++p) CHECK(subs_in_group[p] == (blocks_in_group[p] ? (gq[p] + 31) / 32 : 0));
+        }
+        for (int64_t p = 0; p < n; ++p)
+            for (char c : seen[p]) CHECK(c == 1);
         std::vector<int32_t> rd = {16, 48, 32};                   // nothing shared, lengths differ: heaviest first
         hr::GroupPlan rp = hr::make_group_plan(3, rd.data(), uq.data(), upt.data(), 1, g, cap);
         CHECK(!rp.shared && rp.uneven && rp.p0[0] == 1 && rp.p0[1] == 2 && rp.p0[2] == 0);

@@ -304,13 +304,16 @@ def test_shortened_last_layer_is_bit_identical(d, n_q, n_kv, kv, monkeypatch):
     np.testing.assert_array_equal(scores[0], scores[1])
 
 
-@pytest.mark.parametrize("d,n_q,n_kv,kv,qlen", [(64, 14, 2, "bf16", (1, 40)), (64, 4, 2, "bf16", (30, 64)), (128, 8, 2, "fp8", (1, 40))])
-def test_pairs_sharing_a_document_are_batched_bit_identically(d, n_q, n_kv, kv, qlen, monkeypatch):
+@pytest.mark.parametrize("d,n_q,n_kv,kv,qlen,n_queries", [(64, 14, 2, "bf16", (1, 40), 12), (64, 14, 2, "bf16", (1, 40), 30),
+                                                          (64, 4, 2, "bf16", (30, 64), 12), (128, 8, 2, "fp8", (1, 40), 12),
+                                                          (128, 8, 2, "fp8", (1, 40), 30)])
+def test_pairs_sharing_a_document_are_batched_bit_identically(d, n_q, n_kv, kv, qlen, n_queries, monkeypatch):
     """Pairs whose candidates are the same pool document share one pass over its pages.  Few documents and many
-    queries make groups of several pairs (and groups that fill up and spill into a second one); the scores must match
-    the oracle and be bit for bit those of the run with the batching switched off."""
+    queries make groups of several pairs (and groups that fill up and spill into a second one); with 12 queries work
+    items are scarce and a pair's row blocks are also spread over several work items, with 30 they are not.  The scores
+    must match the oracle and be bit for bit those of the run with the batching switched off."""
     model = small_model(dtype="bf16", n_layers=3, hidden=256, n_q=n_q, n_kv=n_kv, d=d, ffn=320, vocab=500)
-    cfg = wlmod.WorkloadCfg("shared_docs", model, 12, 5, (5, 200), qlen, kv, pool_docs=7, zipf_a=1.1, seed=31)
+    cfg = wlmod.WorkloadCfg("shared_docs", model, n_queries, 5, (5, 200), qlen, kv, pool_docs=7, zipf_a=1.1, seed=31)
     w = wlmod.SeededWeights(model, seed=32, std=0.05, gain_jitter=0.1)
     wl = wlmod.make_workload(cfg, spare_pages=3)
     assert len(set(int(x) for x in wl.pair_doc)) < wl.n_pairs // 3
