@@ -17,6 +17,10 @@
  *     workspaces and outputs are all caller-owned.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls that take a stream enqueue work and return without waiting.
+ *   - A model handle carries per-call host state (a pinned staging buffer, an event, a second stream): calls on
+ *     one handle must not overlap in host time; different handles, and pools, are independent.  The library
+ *     allocates no device memory, but it owns that small pinned host buffer and, once a scoring call has been
+ *     cut in two halves, one stream and three events per model handle (released by hr_model_destroy).
  *   - Every call returns HR_OK (0) or a negative hr_status.  On error nothing
  *     is enqueued and no library state changes.  Nothing throws or aborts.
  *   - All matrices are row-major [out][in]; activations use the model dtype
