@@ -15,6 +15,7 @@ Besides the headline pairs/s the line carries
   roofline_attention  the KV-streaming attention kernel against HBM peak
   cpu_baseline        the CPU oracle timed on a bounded sample of the same pairs
   no_reuse            the same GPU running the full [doc ; query] prefill on a few pairs
+  doc_prefill         stage one on the device: documents prefilled into pool pages (ingest rate)
   host_tier           the same batch when every document's pages first come from pinned host memory
                       (bus-inclusive rate, page-in overlapped with scoring; never `value`)
 """
@@ -50,6 +51,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-reuse-pairs", type=int, default=256, help="pairs for the no-reuse reference (0 = skip)")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events during the timed steps")
+    ap.add_argument("--prefill-docs", type=int, default=128, help="documents for the document-prefill (ingest) leg (0 = skip)")
     ap.add_argument("--host-tier-batches", type=int, default=6,
                     help="batches of the paged leg: every batch's documents come from pinned host memory (0 = skip)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -238,6 +240,32 @@ def main():
         except hb.HrError as e:
             no_reuse = {"value": None, "note": str(e)}
 
+    # ---- stage one on the device: documents prefilled straight into pool pages (ingest rate) ---------
+    doc_prefill = None
+    if args.prefill_docs > 0:
+        nd = min(args.prefill_docs, wl.n_docs)
+        toks = [wl.doc_tokens(d) for d in range(nd)]
+        pages = [wl.pool_doc_pages[d] for d in range(nd)]
+        n_tok = int(sum(len(t) for t in toks))
+        try:
+            pool_p = hb.KVPool(m.n_layers, m.n_kv_heads, m.head_dim, wl.num_pages, cfg.kv_dtype, dev)
+            best = None
+            for _ in range(2):
+                torch.cuda.synchronize()
+                tt = time.perf_counter()
+                model.doc_prefill(pool_p, toks, pages)
+                torch.cuda.synchronize()
+                el = time.perf_counter() - tt
+                best = el if best is None else min(best, el)
+                pool_p.free(np.concatenate(pages))
+            doc_prefill = {"value": round(n_tok / best, 1), "unit": "document tokens/s", "docs": nd, "docs_per_s": round(nd / best, 1),
+                           "note": "hr_doc_prefill: random document tokens of the workload's lengths, K/V of every layer written to pool pages"
+                                   + (" (quantised to fp8 as stored)" if cfg.kv_dtype == "fp8" else "")}
+            pool_p.close()
+            del pool_p
+        except hb.HrError as e:
+            doc_prefill = {"value": None, "note": str(e)}
+
     # ---- host tier: every batch's document pages are paged in from pinned host memory ----------------
     # Two pools alternate: while one batch is scored from one of them, the next batch's pages arrive in the other on a
     # second stream.  The rate includes the bus (it is not `value`): with every document cold it is the bus that
@@ -365,7 +393,7 @@ def main():
                                        "survey steps before it" if not args.no_events else "none"),
                    "events_in_timed_region": "none"},
         "roofline": roofline, "roofline_attention": roof_attn, "gemm_overall": gemm_all, "one_stream": single,
-        "kernel_breakdown": breakdown, "cpu_baseline": cpu, "no_reuse": no_reuse, "host_tier": host_tier,
+        "kernel_breakdown": breakdown, "cpu_baseline": cpu, "no_reuse": no_reuse, "doc_prefill": doc_prefill, "host_tier": host_tier,
         "paper_context": "2-3x end-to-end service throughput from reranker KV reuse on 8x A100 (Table 1); not this metric",
     }
     print(json.dumps(line), flush=True)
