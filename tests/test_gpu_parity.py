@@ -370,6 +370,42 @@ def test_two_stream_halves_are_bit_identical_and_ordered_on_the_callers_stream()
         case.close()
 
 
+def test_split_and_unsplit_calls_back_to_back_on_changing_streams():
+    """Calls that are cut in two halves and calls that are not, enqueued back to back without host synchronisation,
+    on two different caller streams in turn: every result equals the one-stream result of the same call."""
+    import torch
+    model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=4, n_kv=2, d=64, ffn=320, vocab=500)
+    big = wlmod.WorkloadCfg("big", model, 32, 12, (5, 120), (24, 44), "bf16", pool_docs=40, zipf_a=0.8, seed=61)
+    w = wlmod.SeededWeights(model, seed=62, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(big, spare_pages=3)
+    assert wl.total_q_tokens >= 8192
+    small = wl.subset(np.arange(0, 40))
+    other = wl.subset(np.arange(48, wl.n_pairs))
+    assert small.total_q_tokens < 8192 <= other.total_q_tokens
+    case = H.Case(wl, w)
+    try:
+        case.fill_from_prefill()
+        calls = [wl, small, other, small, wl]
+        case.model.set_streams(1)
+        want = [case.gpu_scores(c) for c in calls]
+        case.model.set_streams(2)
+        # one workspace per call so that calls on different streams do not share scratch memory
+        s_a, s_b = torch.cuda.Stream(), torch.cuda.Stream()
+        outs = []
+        ws_keep = []
+        for i, c in enumerate(calls):
+            st = s_a if i % 2 == 0 else s_b
+            with torch.cuda.stream(st):
+                case.model._ws = None                          # force a fresh workspace for this call
+                outs.append(case.model.score(case.pool, c.page_table, c.doc_lens, c.query_tokens, c.query_lens))
+                ws_keep.append(case.model._ws)
+        torch.cuda.synchronize()
+        for got, ref in zip(outs, want):
+            np.testing.assert_array_equal(got.cpu().numpy().astype(np.float64), ref)
+    finally:
+        case.close()
+
+
 @pytest.mark.parametrize("kv", ["f32", "bf16", "fp8"])
 def test_host_tier_round_trip_keeps_pages_and_scores(kv):
     """Documents are evicted to pinned host memory as page records, their pages freed, and paged in again at other
