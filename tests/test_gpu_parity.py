@@ -548,3 +548,14 @@ def test_fp8_prefill_quantises_like_the_oracle(d, n_q, n_kv):
     H.assert_scores_close(case.gpu_scores(), case.oracle_scores(), H.TOL["bf16"], "fp8 prefill + scoring pass")
     pool16.close()
     case.close()
+
+
+def test_demo_walkthrough_runs_and_is_consistent():
+    """The package's end-to-end demo: prefill, score, top-k, no-reuse comparison, host-tier round trip."""
+    from paper_2504_02921_amd import demo
+    scores, best, gap, same = demo.main(verbose=False)
+    assert scores.shape == (18,) and best.shape == (3, 2) and np.all(np.isfinite(scores))
+    assert gap <= 2 * H.TOL["bf16"]          # both sides are the GPU's 16-bit passes: each within the bar of the exact value
+    assert same
+    for q in range(3):
+        assert best[q, 0] == int(np.argmax(scores[q * 6:(q + 1) * 6]))
