@@ -409,6 +409,34 @@ def test_fp8_pool_scores_close_to_unquantised_and_cached_path_consistent():
     np.testing.assert_array_equal(gk, ofp8.dequantize_doc_kv(kc, ks)[1])
 
 
+def test_kv4_known_values_and_properties():
+    """The 4-bit transfer format against hand-computed cases and the properties any symmetric 15-level quantiser with
+    scale amax / 7 must have: the extreme element is exact, errors are at most half a step, codes of a group hit +-7,
+    zero groups stay zero, ties go to the even code, and storing twice changes nothing more."""
+    from oracle import kv4
+    x = np.zeros((2, 64))
+    x[0, :8] = [7.0, -7.0, 3.5, 2.5, 0.5, -0.5, 1.0, 6.49]           # scale 1: ties 3.5 -> 4, 2.5 -> 2, +-0.5 -> 0
+    x[0, 32:36] = [0.875, 0.4375, -0.0625, 0.0]                       # scale 0.125 exactly: ties 3.5 -> 4, -0.5 -> 0
+    codes, scale = kv4.quantize(x)
+    assert codes.dtype == np.int8 and scale.dtype == np.float32 and scale.shape == (2, 2)
+    assert codes[0, :8].tolist() == [7, -7, 4, 2, 0, 0, 1, 6]
+    assert scale[0, 0] == np.float32(1.0) and scale[0, 1] == np.float32(0.125)
+    assert codes[0, 32:36].tolist() == [7, 4, 0, 0]
+    assert np.all(codes[1] == 0) and np.all(scale[1] == 1.0)
+    y = kv4.dequantize(codes, scale)
+    assert y[0, 0] == 7.0 and y[0, 3] == 2.0 and y[0, 32] == 0.875 and y[0, 33] == 0.5 and y[0, 34] == 0.0
+    rng = np.random.default_rng(0)
+    z = rng.standard_normal((3, 5, 2, 128)).astype(np.float16).astype(np.float64) * 3
+    c, sc = kv4.quantize(z)
+    g = z.reshape(3, 5, 2, 4, 32)
+    assert np.array_equal(np.abs(c).reshape(3, 5, 2, 4, 32).max(-1), np.full((3, 5, 2, 4), 7))
+    back = kv4.dequantize(c, sc).reshape(3, 5, 2, 4, 32)
+    step = sc.astype(np.float64)[..., None]
+    assert np.all(np.abs(back - g) <= step / 2 + np.abs(g) * 2.0 ** -10)     # half a step, plus the rounding to half
+    again = kv4.round_trip(back.reshape(z.shape))
+    assert np.abs(again - back.reshape(z.shape)).max() <= np.abs(back).max() * 2.0 ** -9   # a second pass is (nearly) idempotent
+
+
 def test_topk_order_ties_break_by_index():
     s = np.array([0.5, 2.0, 2.0, -1.0, 3.0, 3.0, 3.0, 0.0])
     order = orr.topk_order(s, 2, 4)
