@@ -182,6 +182,20 @@ int hr_kv_pages_out(const hr_pool* pool, int32_t n_pages, const int32_t* page_id
  * a second stream it overlaps with hr_rerank_score calls that read other pages of the same pool. */
 int hr_kv_pages_in(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, const void* src, void* stream);
 
+/* The same with 4-bit records (Section 4.1 names a 4-bit KV cache, KV4W16A16, and Appendix B expands quantised KV
+ * to 16 bits after it is loaded; the paper gives no format, this is the library's): the pool stays 16-bit, a page
+ * is quantised as it leaves and expanded as it arrives.  16-bit pools only (HR_ERR_UNSUPPORTED_SHAPE otherwise).
+ * Per token and per 32 consecutive channels of one (layer, kv head), separately for K and V: scale = amax / 7 in
+ * fp32 (1 if all zero), code = x / scale rounded to the nearest integer (ties to even) in [-7, 7]; a loaded page
+ * holds code * scale rounded to half.  Record of one page, for every (layer, kv head) in that order:
+ *   K codes [16 tokens][head_dim / 2] bytes (channel 2i in the low nibble, 2i + 1 in the high one, two's complement),
+ *   V codes likewise, K scales [16][head_dim / 32] fp32, V scales [16][head_dim / 32] fp32
+ * = 20 * head_dim bytes per (layer, kv head), 3.2 times smaller than the 16-bit record.  Arguments, memory kinds,
+ * page states and errors as for hr_kv_pages_out / hr_kv_pages_in. */
+size_t hr_kv_page_record4_bytes(const hr_pool* pool);
+int hr_kv_pages_out4(const hr_pool* pool, int32_t n_pages, const int32_t* page_ids, void* dst, void* stream);
+int hr_kv_pages_in4(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, const void* src, void* stream);
+
 /* ---- weights ---- */
 
 /* Bytes of device memory for the library's packed copy of the layer weights

@@ -56,7 +56,7 @@ class hr_weight_ptrs(C.Structure):
 EXPORTS = [
     "hr_status_str", "hr_last_error", "hr_kv_pool_bytes", "hr_kv_pool_create", "hr_kv_pool_destroy", "hr_kv_pool_free_pages",
     "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_read", "hr_doc_kv_free", "hr_kv_page_record_bytes", "hr_kv_pages_out",
-    "hr_kv_pages_in", "hr_weights_pack_bytes", "hr_weights_load",
+    "hr_kv_pages_in", "hr_kv_page_record4_bytes", "hr_kv_pages_out4", "hr_kv_pages_in4", "hr_weights_pack_bytes", "hr_weights_load",
     "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_set_streams", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
     "hr_rerank_topk", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
@@ -90,6 +90,9 @@ def _load() -> C.CDLL:
         "hr_kv_page_record_bytes": (C.c_size_t, [C.c_void_p]),
         "hr_kv_pages_out": (C.c_int, [C.c_void_p, C.c_int32, i32p, C.c_void_p, C.c_void_p]),
         "hr_kv_pages_in": (C.c_int, [C.c_void_p, C.c_int32, i32p, C.c_void_p, C.c_void_p]),
+        "hr_kv_page_record4_bytes": (C.c_size_t, [C.c_void_p]),
+        "hr_kv_pages_out4": (C.c_int, [C.c_void_p, C.c_int32, i32p, C.c_void_p, C.c_void_p]),
+        "hr_kv_pages_in4": (C.c_int, [C.c_void_p, C.c_int32, i32p, C.c_void_p, C.c_void_p]),
         "hr_weights_pack_bytes": (C.c_size_t, [C.POINTER(hr_model_cfg)]),
         "hr_weights_load": (C.c_int, [C.POINTER(hr_model_cfg), C.POINTER(hr_weight_ptrs), C.c_void_p, C.c_size_t,
                                       C.c_void_p, C.POINTER(C.c_void_p)]),
@@ -248,6 +251,23 @@ class KVPool:
     @property
     def page_record_bytes(self) -> int:
         return int(lib.hr_kv_page_record_bytes(self.handle))
+
+    @property
+    def page_record4_bytes(self) -> int:
+        return int(lib.hr_kv_page_record4_bytes(self.handle))
+
+    def pages_out4(self, page_ids, records, stream=None) -> None:
+        """4-bit records (16-bit pools): quantised as the pages leave."""
+        ids = _i32(page_ids)
+        assert records.numel() * records.element_size() >= len(ids) * self.page_record4_bytes
+        check(lib.hr_kv_pages_out4(self.handle, len(ids), _i32p(ids), C.c_void_p(records.data_ptr()), _stream_ptr(stream)),
+              "hr_kv_pages_out4")
+
+    def pages_in4(self, page_ids, records, stream=None) -> None:
+        ids = _i32(page_ids)
+        assert records.numel() * records.element_size() >= len(ids) * self.page_record4_bytes
+        check(lib.hr_kv_pages_in4(self.handle, len(ids), _i32p(ids), C.c_void_p(records.data_ptr()), _stream_ptr(stream)),
+              "hr_kv_pages_in4")
 
     def pages_out(self, page_ids, records, stream=None) -> None:
         """records: uint8 tensor of len(page_ids) * page_record_bytes, on the device or in pinned host memory."""

@@ -411,9 +411,11 @@ static char* device_view(const void* p) {
     return (char*)attr.devicePointer;
 }
 
-static int pages_move(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, const void* records, bool to_pool, void* stream) {
+static int pages_move(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, const void* records, bool to_pool, void* stream,
+                      bool four_bit = false) {
     int rc = hr::pool_check_pages(pool, n_pages, page_ids, !to_pool);
     if (rc != HR_OK) return rc;
+    if (four_bit && hr::page_record4_bytes(pool->lay) == 0) return HR_ERR_UNSUPPORTED_SHAPE;
     if (n_pages == 0) return HR_OK;
     if (!records || (uintptr_t)records % 16 != 0) return HR_ERR_INVALID_ARG;
     char* rec = device_view(records);
@@ -421,7 +423,8 @@ static int pages_move(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, c
         snprintf(g_last_error, sizeof(g_last_error), "page records must be device memory or host memory pinned by the HIP runtime");
         return HR_ERR_INVALID_ARG;
     }
-    hipError_t e = hr::launch_pages_move(pool->lay, pool->base, page_ids, n_pages, rec, to_pool, (hipStream_t)stream);
+    hipError_t e = four_bit ? hr::launch_pages_move4(pool->lay, pool->base, page_ids, n_pages, rec, to_pool, (hipStream_t)stream)
+                            : hr::launch_pages_move(pool->lay, pool->base, page_ids, n_pages, rec, to_pool, (hipStream_t)stream);
     if (e != hipSuccess) {
         note_hip_error(e, "page move kernel");
         return HR_ERR_DEVICE;
@@ -436,6 +439,14 @@ int hr_kv_pages_out(const hr_pool* pool, int32_t n_pages, const int32_t* page_id
 
 int hr_kv_pages_in(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, const void* src, void* stream) {
     return pages_move(pool, n_pages, page_ids, src, true, stream);
+}
+
+int hr_kv_pages_out4(const hr_pool* pool, int32_t n_pages, const int32_t* page_ids, void* dst, void* stream) {
+    return pages_move(const_cast<hr_pool*>(pool), n_pages, page_ids, dst, false, stream, true);
+}
+
+int hr_kv_pages_in4(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, const void* src, void* stream) {
+    return pages_move(pool, n_pages, page_ids, src, true, stream, true);
 }
 
 size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t total_q_tokens, int32_t pt_stride) {

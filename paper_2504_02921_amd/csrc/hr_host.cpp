@@ -122,6 +122,11 @@ int pool_check_read(const hr_pool* pool, int32_t doc_len, const int32_t* page_id
     return HR_OK;
 }
 
+size_t page_record4_bytes(const PoolLayout& lay) {
+    if (lay.kv_dtype != HR_BF16 || lay.d % 32 != 0) return 0;
+    return (size_t)lay.n_layers * lay.n_kv * 20 * lay.d;      // per (layer, kv head): 16 d bytes of codes + 4 d of scales
+}
+
 int pool_check_write(const hr_pool* pool, int32_t doc_len, const int32_t* page_ids) {
     if (!pool || !page_ids) return HR_ERR_INVALID_ARG;
     if (doc_len <= 0) return HR_ERR_LEN_RANGE;
@@ -403,6 +408,7 @@ const char* hr_status_str(int s) {
 }
 
 size_t hr_kv_page_record_bytes(const hr_pool* pool) { return pool ? hr::page_record_bytes(pool->lay) : 0; }
+size_t hr_kv_page_record4_bytes(const hr_pool* pool) { return pool ? hr::page_record4_bytes(pool->lay) : 0; }
 
 size_t hr_kv_pool_bytes(const hr_pool_cfg* cfg) {
     if (!hr::pool_cfg_valid(cfg)) return 0;

@@ -89,6 +89,7 @@ void pool_mark(hr_pool* pool, const int32_t* page_ids, int n, PageState st);
 // n pages by id: all in range, and all holding a document (want_used) or all distinct and not holding one
 int pool_check_pages(const hr_pool* pool, int64_t n, const int32_t* page_ids, bool want_used);
 size_t page_record_bytes(const PoolLayout& lay);
+size_t page_record4_bytes(const PoolLayout& lay);      // 4-bit records of a 16-bit pool; 0 for other pools
 int score_check_args(const hr_model_cfg& mc, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table,
                      int32_t pt_stride, const int32_t* doc_lens, const int32_t* query_tokens,
                      const int32_t* query_lens, int64_t max_keys, int64_t* total_q_out);

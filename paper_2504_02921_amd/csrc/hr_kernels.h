@@ -96,6 +96,9 @@ hipError_t launch_kv_gather(const PoolLayout& lay, const char* pool_base, const 
 // whole pages between the pool and page records ([layer][kv head][K | V], then the fp8 scales): to_pool picks the direction
 hipError_t launch_pages_move(const PoolLayout& lay, char* pool_base, const int32_t* page_ids_host, int64_t n_pages, char* records,
                              bool to_pool, hipStream_t st);
+// the same with 4-bit records (16-bit pools; quantised on the way out, expanded on the way in)
+hipError_t launch_pages_move4(const PoolLayout& lay, char* pool_base, const int32_t* page_ids_host, int64_t n_pages, char* records,
+                              bool to_pool, hipStream_t st);
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t st);
 // dst[i][:] = src[rows[i]][:] for n rows of `cols` floats (device arrays)
 hipError_t launch_gather_rows_f32(const float* src, const int32_t* rows, float* dst, int n, int cols, hipStream_t st);

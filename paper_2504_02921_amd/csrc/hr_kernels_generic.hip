@@ -668,6 +668,78 @@ hipError_t launch_pages_move(const PoolLayout& lay, char* pool_base, const int32
     return hipSuccess;
 }
 
+// ---- host tier, 4-bit records of a 16-bit pool.  One workgroup per (page, layer, kv head), one thread per group of 32
+// channels of one token of K or V: 2 * 16 * d / 32 = d threads.  Out: gather the group from the page (K: four 16-byte
+// chunks of the token's row, V: 32 keys-major elements), scale = amax / 7, codes by round-to-nearest-even of the exact
+// quotient.  In: codes * scale, rounded to half, back to the page positions.
+namespace {
+__device__ __forceinline__ size_t kv4_group_elem(bool is_v, int t, int c, int d) {
+    return is_v ? (size_t)kPageTokens * d + v_elem(t, c, d) : (size_t)k_elem(t, c, d, 2);
+}
+
+template <bool TO_POOL>
+__global__ void pages_move4_kernel(half_t* __restrict__ pool, PageIdChunk page_ids, char* __restrict__ records, size_t record_bytes,
+                                   int num_pages, int n_kv, int d) {
+    const int page = page_ids.ids[blockIdx.x];
+    const int layer = blockIdx.y / n_kv, h = blockIdx.y % n_kv;
+    const int gpt = d / 32;                                   // groups per token
+    const int tid = threadIdx.x;                              // 0 .. d - 1
+    const bool is_v = tid >= kPageTokens * gpt;
+    const int r = is_v ? tid - kPageTokens * gpt : tid;
+    const int t = r / gpt, gi = r - t * gpt;
+    half_t* pg = pool + (((size_t)layer * num_pages + page) * n_kv + h) * (2 * kPageTokens * d);
+    char* rec = records + (size_t)blockIdx.x * record_bytes + (size_t)blockIdx.y * (20 * d);
+    uint4* codes = (uint4*)(rec + (is_v ? kPageTokens * d / 2 : 0) + t * (d / 2) + gi * 16);
+    float* scale = (float*)(rec + kPageTokens * d) + (is_v ? kPageTokens * gpt : 0) + t * gpt + gi;
+    if constexpr (!TO_POOL) {
+        float x[32];
+        float amax = 0.f;
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            x[i] = (float)pg[kv4_group_elem(is_v, t, gi * 32 + i, d)];
+            amax = fmaxf(amax, fabsf(x[i]));
+        }
+        const float sc = amax > 0.f ? amax / 7.0f : 1.0f;
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            double q = rint((double)x[i] / (double)sc);       // the default rounding mode: ties to even
+            q = q < -7.0 ? -7.0 : (q > 7.0 ? 7.0 : q);
+            w[i >> 3] |= ((uint32_t)(int)q & 0xFu) << ((i & 7) * 4);
+        }
+        *codes = make_uint4(w[0], w[1], w[2], w[3]);
+        *scale = sc;
+    } else {
+        const uint4 cw = *codes;
+        const float sc = *scale;
+        const uint32_t w[4] = {cw.x, cw.y, cw.z, cw.w};
+#pragma unroll
+        for (int i = 0; i < 32; ++i) {
+            const int code = ((int)(w[i >> 3] << (28 - (i & 7) * 4))) >> 28;      // sign-extended nibble
+            pg[kv4_group_elem(is_v, t, gi * 32 + i, d)] = from_float<half_t>((float)code * sc);
+        }
+    }
+}
+}  // namespace
+
+hipError_t launch_pages_move4(const PoolLayout& lay, char* pool_base, const int32_t* page_ids_host, int64_t n_pages, char* records,
+                              bool to_pool, hipStream_t st) {
+    const size_t rec = page_record4_bytes(lay);
+    if (rec == 0) return hipErrorInvalidValue;
+    for (int64_t pg0 = 0; pg0 < n_pages; pg0 += 256) {
+        const int n = (int)(n_pages - pg0 < 256 ? n_pages - pg0 : 256);
+        PageIdChunk ids;
+        for (int i = 0; i < 256; ++i) ids.ids[i] = i < n ? page_ids_host[pg0 + i] : 0;
+        const dim3 grid((unsigned)n, (unsigned)(lay.n_layers * lay.n_kv));
+        char* r = records + (size_t)pg0 * rec;
+        if (to_pool) pages_move4_kernel<true><<<grid, lay.d, 0, st>>>((half_t*)pool_base, ids, r, rec, lay.num_pages, lay.n_kv, lay.d);
+        else pages_move4_kernel<false><<<grid, lay.d, 0, st>>>((half_t*)pool_base, ids, r, rec, lay.num_pages, lay.n_kv, lay.d);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 // ---- dst[i][:] = src[rows[i]][:]: the rows of the last query tokens, for the last layer's shortened tail
 namespace {
 __global__ void __launch_bounds__(256) gather_rows_f32_kernel(const float* __restrict__ src, const int32_t* __restrict__ rows,

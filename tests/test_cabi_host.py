@@ -161,7 +161,19 @@ def test_page_record_size_and_host_tier_validation():
     assert hb.lib.hr_kv_pages_in(h, 1, (C.c_int32 * 1)(3), None, None) == hb.HR_ERR_INVALID_ARG
     assert hb.lib.hr_kv_pages_in(h, 1, (C.c_int32 * 1)(3), C.c_void_p(FAKE_DEV + 4), None) == hb.HR_ERR_INVALID_ARG   # alignment
     assert hb.lib.hr_kv_pool_free_pages(h) == 8                               # nothing was marked by the refused calls
+    # 4-bit records exist for 16-bit pools only: 20 bytes per channel of every (layer, kv head)
+    assert hb.lib.hr_kv_page_record4_bytes(h) == 0 and hb.lib.hr_kv_page_record4_bytes(None) == 0
+    assert move(hb.lib.hr_kv_pages_in4, [3]) == hb.HR_ERR_UNSUPPORTED_SHAPE   # this one is an fp32 pool
     hb.lib.hr_kv_pool_destroy(h)
+    cfg16, h16 = make_pool(num_pages=8, kv="bf16", layers=3, n_kv=2, d=128)
+    assert hb.lib.hr_kv_page_record4_bytes(h16) == 3 * 2 * 20 * 128
+    assert hb.lib.hr_kv_page_record_bytes(h16) == 3 * 2 * 2 * 16 * 128 * 2
+    for fn in (hb.lib.hr_kv_pages_out4, hb.lib.hr_kv_pages_in4):
+        assert move(fn, [0, 8], pool=h16) == hb.HR_ERR_PAGE_RANGE
+        assert move(fn, [], pool=h16) == hb.HR_OK
+    assert move(hb.lib.hr_kv_pages_out4, [0], pool=h16) == hb.HR_ERR_TABLE_SHORT
+    assert move(hb.lib.hr_kv_pages_in4, [1, 1], pool=h16) == hb.HR_ERR_PAGE_DUP
+    hb.lib.hr_kv_pool_destroy(h16)
 
 
 def test_weights_pack_bytes_and_model_cfg_validation():

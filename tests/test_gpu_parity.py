@@ -550,6 +550,89 @@ def test_fp8_prefill_quantises_like_the_oracle(d, n_q, n_kv):
     case.close()
 
 
+@pytest.mark.parametrize("d,n_q,n_kv", [(64, 4, 2), (128, 4, 1)])
+def test_four_bit_host_tier_matches_the_oracle_quantiser(d, n_q, n_kv):
+    """Documents leave a 16-bit pool as 4-bit records and come back at other pages.  The records' codes and scales, and
+    the halves the pool holds afterwards, must be bit for bit the oracle quantiser's applied to the halves that left; the
+    scores from the reloaded pages must match the oracle run on that dequantised KV.  An fp8 pool is refused."""
+    import torch
+    from oracle import kv4
+    from paper_2504_02921_amd import binding as hb
+    model = small_model(dtype="bf16", n_layers=2, hidden=128, n_q=n_q, n_kv=n_kv, d=d, ffn=192, vocab=300)
+    cfg = wlmod.WorkloadCfg("kv4_tier", model, 3, 4, (5, 90), (2, 20), "bf16", pool_docs=6, zipf_a=0.5, seed=71)
+    w = wlmod.SeededWeights(model, seed=72, std=0.05)
+    wl = wlmod.make_workload(cfg, spare_pages=40)
+    case = H.Case(wl, w)
+    try:
+        case.fill_from_prefill()
+        pool = case.pool
+        docs = sorted(set(int(x) for x in wl.pair_doc))
+        old_pages = np.concatenate([wl.pool_doc_pages[x] for x in docs]).astype(np.int32)
+        kv_before = {x: pool.read(int(wl.pool_doc_lens[x]), wl.pool_doc_pages[x]) for x in docs}
+        torch.cuda.synchronize()
+        rec = pool.page_record4_bytes
+        assert rec == model.n_layers * n_kv * 20 * d and rec * 16 == pool.page_record_bytes * 5
+        host = torch.zeros(len(old_pages) * rec, dtype=torch.uint8, pin_memory=True)
+        pool.pages_out4(old_pages, host)
+        torch.cuda.synchronize()
+        # the records against the oracle: K codes | V codes | K scales | V scales per (layer, kv head)
+        raw = host.numpy().reshape(len(old_pages), model.n_layers, n_kv, 20 * d)
+        pos = 0
+        for x in docs:
+            D = int(wl.pool_doc_lens[x])
+            k, v = (t.cpu().numpy().astype(np.float64) for t in kv_before[x])       # halves [L][D][n_kv][d]
+            for name, val, code_off, scale_off in (("K", k, 0, 16 * d), ("V", v, 8 * d, 16 * d + 16 * (d // 32) * 4)):
+                want_c, want_s = kv4.quantize(val)
+                n_pg = (D + 15) // 16
+                r = raw[pos:pos + n_pg]                                            # [pages][L][n_kv][bytes]
+                cb = r[..., code_off:code_off + 8 * d].reshape(n_pg, model.n_layers, n_kv, 16, d // 2)
+                lo = (cb & 0xF).astype(np.int8)
+                hi = (cb >> 4).astype(np.int8)
+                nib = np.stack([lo, hi], axis=-1).reshape(n_pg, model.n_layers, n_kv, 16, d)
+                nib = np.where(nib > 7, nib - 16, nib)
+                got_c = nib.transpose(1, 0, 3, 2, 4).reshape(model.n_layers, n_pg * 16, n_kv, d)[:, :D]
+                sb = np.ascontiguousarray(r[..., scale_off:scale_off + 16 * (d // 32) * 4]).view(np.float32)
+                got_s = sb.reshape(n_pg, model.n_layers, n_kv, 16, d // 32).transpose(1, 0, 3, 2, 4).reshape(model.n_layers, n_pg * 16, n_kv, d // 32)[:, :D]
+                assert np.array_equal(got_c, want_c), f"{name} codes of document {x}"
+                assert np.array_equal(got_s, want_s), f"{name} scales of document {x}"
+            pos += (D + 15) // 16
+        # reload at other pages; the pool holds the oracle's dequantised halves
+        pool.free(old_pages)
+        rng = np.random.default_rng(9)
+        used_elsewhere = set(int(p) for x in range(wl.n_docs) if x not in docs for p in wl.pool_doc_pages[x])
+        candidates = np.array([p for p in range(wl.num_pages) if p not in used_elsewhere], np.int32)
+        new_pages = rng.permutation(candidates)[:len(old_pages)].astype(np.int32)
+        pool.pages_in4(new_pages, host)
+        remap = {int(o): int(n) for o, n in zip(old_pages, new_pages)}
+        oracle_pool = orr.PagedKV(model.n_layers, n_kv, d, 16, "bf16")
+        for x in docs:
+            D = int(wl.pool_doc_lens[x])
+            pages = np.array([remap[int(p)] for p in wl.pool_doc_pages[x]], np.int32)
+            gk, gv = pool.read(D, pages)
+            torch.cuda.synchronize()
+            k, v = (t.cpu().numpy().astype(np.float64) for t in kv_before[x])
+            wk, wv = kv4.round_trip(k), kv4.round_trip(v)
+            assert np.array_equal(gk.cpu().numpy().astype(np.float64), wk) and np.array_equal(gv.cpu().numpy().astype(np.float64), wv)
+            oracle_pool.write(pages, wk, wv)
+        pt = wl.page_table.copy()
+        for i in range(pt.shape[0]):
+            for j in range(pt.shape[1]):
+                if pt[i, j] >= 0:
+                    pt[i, j] = remap[int(pt[i, j])]
+        moved = dataclasses.replace(wl, page_table=pt)
+        got = case.gpu_scores(moved)
+        want = orr.score_cached(w, model, oracle_pool, moved.page_table, moved.doc_lens, moved.query_tokens, moved.query_lens)
+        H.assert_scores_close(got, want, H.TOL["bf16"], "scores from 4-bit records")
+        pool8 = hb.KVPool(model.n_layers, n_kv, d, 4, "fp8", "cuda:0")
+        assert pool8.page_record4_bytes == 0
+        with pytest.raises(hb.HrError) as ei:
+            pool8.pages_out4(np.array([0], np.int32), host)
+        assert ei.value.status in (-7, -10)          # nothing written there / not a 16-bit pool, whichever is checked first
+        pool8.close()
+    finally:
+        case.close()
+
+
 def test_demo_walkthrough_runs_and_is_consistent():
     """The package's end-to-end demo: prefill, score, top-k, no-reuse comparison, host-tier round trip."""
     from paper_2504_02921_amd import demo
