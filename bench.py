@@ -18,6 +18,7 @@ Besides the headline pairs/s the line carries
   doc_prefill         stage one on the device: documents prefilled into pool pages (ingest rate)
   host_tier           the same batch when every document's pages first come from pinned host memory
                       (bus-inclusive rate, page-in overlapped with scoring; never `value`)
+  host_tier_4bit      the same with 4-bit records in the tier (16-bit pools)
 """
 
 import argparse
