@@ -680,6 +680,9 @@ __device__ __forceinline__ size_t kv4_group_elem(bool is_v, int t, int c, int d)
 template <bool TO_POOL>
 __global__ void pages_move4_kernel(half_t* __restrict__ pool, PageIdChunk page_ids, char* __restrict__ records, size_t record_bytes,
                                    int num_pages, int n_kv, int d) {
+    // The page (4 or 8 KiB) passes through LDS so that the pool side is read and written in whole 16-byte words; the
+    // groups' element order (strided in the V block) is an LDS access pattern only.
+    __shared__ __attribute__((aligned(16))) half_t page_lds[2 * kPageTokens * 128];
     const int page = page_ids.ids[blockIdx.x];
     const int layer = blockIdx.y / n_kv, h = blockIdx.y % n_kv;
     const int gpt = d / 32;                                   // groups per token
@@ -687,16 +690,21 @@ __global__ void pages_move4_kernel(half_t* __restrict__ pool, PageIdChunk page_i
     const bool is_v = tid >= kPageTokens * gpt;
     const int r = is_v ? tid - kPageTokens * gpt : tid;
     const int t = r / gpt, gi = r - t * gpt;
-    half_t* pg = pool + (((size_t)layer * num_pages + page) * n_kv + h) * (2 * kPageTokens * d);
+    uint4* pg = (uint4*)(pool + (((size_t)layer * num_pages + page) * n_kv + h) * (2 * kPageTokens * d));
+    uint4* lds16 = (uint4*)page_lds;
+    constexpr int WPT = 2 * kPageTokens * 2 / 16;             // 16-byte words of the page per thread: 4 (page = 64 d bytes)
     char* rec = records + (size_t)blockIdx.x * record_bytes + (size_t)blockIdx.y * (20 * d);
     uint4* codes = (uint4*)(rec + (is_v ? kPageTokens * d / 2 : 0) + t * (d / 2) + gi * 16);
     float* scale = (float*)(rec + kPageTokens * d) + (is_v ? kPageTokens * gpt : 0) + t * gpt + gi;
     if constexpr (!TO_POOL) {
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) lds16[i * d + tid] = pg[i * d + tid];
+        __syncthreads();
         float x[32];
         float amax = 0.f;
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
-            x[i] = (float)pg[kv4_group_elem(is_v, t, gi * 32 + i, d)];
+            x[i] = (float)page_lds[kv4_group_elem(is_v, t, gi * 32 + i, d)];
             amax = fmaxf(amax, fabsf(x[i]));
         }
         const float sc = amax > 0.f ? amax / 7.0f : 1.0f;
@@ -716,8 +724,11 @@ __global__ void pages_move4_kernel(half_t* __restrict__ pool, PageIdChunk page_i
 #pragma unroll
         for (int i = 0; i < 32; ++i) {
             const int code = ((int)(w[i >> 3] << (28 - (i & 7) * 4))) >> 28;      // sign-extended nibble
-            pg[kv4_group_elem(is_v, t, gi * 32 + i, d)] = from_float<half_t>((float)code * sc);
+            page_lds[kv4_group_elem(is_v, t, gi * 32 + i, d)] = from_float<half_t>((float)code * sc);
         }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < WPT; ++i) pg[i * d + tid] = lds16[i * d + tid];
     }
 }
 }  // namespace
