@@ -46,6 +46,8 @@ using namespace hr;
 constexpr int64_t kGenericMaxKeys = 15000;     // scores of one row live in LDS in the generic attention
 constexpr int64_t kMfmaMaxKeys = 1 << 20;
 constexpr int64_t kSplitMinTokens = 8192;      // query tokens from which a scoring call is cut in two halves
+constexpr size_t kSplitSlackBytes = (size_t)1 << 20;   // what two carvings of a workspace may need beyond one (alignment gaps,
+                                                       // the larger group-plan room of calls with few pairs)
 
 thread_local char g_last_error[256] = "";
 
@@ -454,7 +456,7 @@ size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t tot
     // + room for the per-part alignment when the call runs as two halves (each with its own carving)
     return hr::make_workspace(m->cfg, n_pairs, total_q_tokens, pt_stride, !m->mfma_gemm, -1, 0,
                               (int64_t)hr::group_plan_ints_bound(n_pairs, total_q_tokens, m->cfg.n_q_heads / m->cfg.n_kv_heads))
-               .total + (m->mfma_gemm ? (size_t)256 * 1024 : 0);
+               .total + (m->mfma_gemm ? kSplitSlackBytes : 0);
 }
 
 // One contiguous part of a scoring call.  prepare: its metadata (already validated) is built at `stage` and its upload to the

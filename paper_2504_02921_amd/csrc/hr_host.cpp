@@ -279,8 +279,8 @@ ChunkPlan make_chunk_plan(int64_t n_seq, const int32_t* lens, int chunk) {
 
 size_t group_plan_ints_bound(int64_t n_seq, int64_t T, int g) {
     // every sequence adds at most one partial block and one partial sub-tile; a call of few sequences may cut each of
-    // them into up to 16 groups (one per block), each of which lists the sequence's sub-tiles
-    const size_t cut = n_seq <= kGroupCutMaxSeqs ? 16 : 1;
+    // them into up to 4 groups (16 blocks at most, 4 per group), each of which lists the sequence's sub-tiles
+    const size_t cut = n_seq <= kGroupCutMaxSeqs ? 4 : 1;
     const size_t nb = (size_t)(T * g / 32 + n_seq), ns = (size_t)(T / 32 + n_seq) * cut, ng = (size_t)n_seq * cut;
     return ng + 2 * (ng + 1) + 2 * nb + 3 * ns;
 }

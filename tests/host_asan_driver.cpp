@@ -131,6 +131,24 @@ int main() {
         hr::GroupPlan rp = hr::make_group_plan(3, rd.data(), uq.data(), upt.data(), 1, g, cap);
         CHECK(!rp.shared && rp.uneven && rp.p0[0] == 1 && rp.p0[1] == 2 && rp.p0[2] == 0);
     }
+    // a call cut in two halves: the two carvings fit the whole call's workspace plus the 1 MB the size query adds
+    {
+        hr_model_cfg mcs[2] = {{24, 896, 14, 2, 64, 4864, 1000, 1, 2, HR_BF16, 1e6f, 1e-6f}, {32, 4096, 32, 8, 128, 14336, 1000, 1, 2, HR_BF16, 5e5f, 1e-5f}};
+        unsigned rs = 12345u;
+        auto rnd = [&](unsigned n) { rs = rs * 1664525u + 1013904223u; return (rs >> 8) % n; };
+        for (int it = 0; it < 400; ++it) {
+            const hr_model_cfg& mc2 = mcs[it & 1];
+            const int g2 = mc2.n_q_heads / mc2.n_kv_heads;
+            const int64_t n = 2 + rnd(3000), T = n + rnd(40000), stride = 1 + rnd(130);
+            const int64_t na = 1 + rnd((unsigned)(n - 1)), Ta = na + rnd((unsigned)(T - n + 1));       // Ta >= na, Tb >= nb
+            const int64_t nb = n - na, Tb = T - Ta;
+            if (Tb < nb) continue;
+            const size_t whole = hr::make_workspace(mc2, n, T, stride, false, -1, 0, (int64_t)hr::group_plan_ints_bound(n, T, g2)).total;
+            const size_t a_part = hr::make_workspace(mc2, na, Ta, stride, false, -1, 0, (int64_t)hr::group_plan_ints_bound(na, Ta, g2)).total;
+            const size_t b_part = hr::make_workspace(mc2, nb, Tb, stride, false, -1, 0, (int64_t)hr::group_plan_ints_bound(nb, Tb, g2)).total;
+            CHECK(a_part + b_part <= whole + (1 << 20));
+        }
+    }
     // pool bookkeeping and validation paths
     hr_pool_cfg pc{2, 2, 64, 16, 8, HR_BF16};
     hr_pool* pool = nullptr;
