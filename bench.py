@@ -110,6 +110,8 @@ def main():
     # microseconds of stream time per launch, ~6 % of a step when all ~170 launches are bracketed) and give the
     # rooflines.  The timed region itself records no events (on two streams they cost more than they tell).
     streams = 1 if os.environ.get("HR_STREAMS", "") == "1" else 2
+    model.set_streams(streams)
+    parts = model.parts(wl.total_q_tokens) if model.attention_path(pool) == "mfma" else 1     # what the library does at this size
     survey = {}
     if not args.no_events:
         model.set_streams(1)
@@ -409,7 +411,7 @@ def main():
                    "doc_len": cfg.doc_len, "query_len": cfg.query_len, "kv_dtype": cfg.kv_dtype,
                    "gemm_path": model.gemm_path(), "attention_path": model.attention_path(pool),
                    "last_layer": "last token of each pair only" if shortened else "all tokens",
-                   "streams": streams,
+                   "streams": parts,
                    "roofline_region": (f"{args.steps} one-stream steps right after the timed region (kernel alone on the chip); breakdown from 2 one-stream "
                                        "survey steps before it" if not args.no_events else "none"),
                    "events_in_timed_region": "none"},

@@ -246,6 +246,10 @@ int hr_rerank_score(hr_model* model, const hr_pool* pool, int32_t n_pairs,
  * HR_ERR_INVALID_ARG for other values. */
 int hr_rerank_set_streams(hr_model* model, int n_streams);
 
+/* In how many parts (1 or 2) a scoring call with this many query tokens runs on the current device, given at least two
+ * pairs and a model / pool combination on the MFMA kernels; a negative status on invalid arguments.  For reporting. */
+int hr_rerank_parts(const hr_model* model, int64_t total_q_tokens);
+
 /* The host-side checks hr_rerank_score performs before it enqueues anything, on their own: no
  * device work, no model handle needed.  Returns HR_OK or the status hr_rerank_score would return
  * for these arguments (lengths, page-table rows, page states, token ids, pool/model agreement). */

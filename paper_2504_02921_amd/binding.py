@@ -57,7 +57,7 @@ EXPORTS = [
     "hr_status_str", "hr_last_error", "hr_kv_pool_bytes", "hr_kv_pool_create", "hr_kv_pool_destroy", "hr_kv_pool_free_pages",
     "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_read", "hr_doc_kv_free", "hr_kv_page_record_bytes", "hr_kv_pages_out",
     "hr_kv_pages_in", "hr_kv_page_record4_bytes", "hr_kv_pages_out4", "hr_kv_pages_in4", "hr_weights_pack_bytes", "hr_weights_load",
-    "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_set_streams", "hr_rerank_validate",
+    "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_set_streams", "hr_rerank_parts", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
     "hr_rerank_topk", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
 ]
@@ -101,6 +101,7 @@ def _load() -> C.CDLL:
         "hr_rerank_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, i32p, C.c_int32, i32p, i32p, i32p,
                                       C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
         "hr_rerank_set_streams": (C.c_int, [C.c_void_p, C.c_int]),
+        "hr_rerank_parts": (C.c_int, [C.c_void_p, C.c_int64]),
         "hr_rerank_validate": (C.c_int, [C.POINTER(hr_model_cfg), C.c_void_p, C.c_int32, i32p, C.c_int32, i32p, i32p, i32p]),
         "hr_rerank_full_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int64]),
         "hr_rerank_score_full": (C.c_int, [C.c_void_p, C.c_int32, i32p, i32p, i32p, i32p, C.c_void_p, C.c_size_t,
@@ -388,6 +389,9 @@ class Model:
                                  C.c_void_p(ws.data_ptr()), ws.numel(), C.c_void_p(scores.data_ptr()), _stream_ptr(stream))
         check(st, "hr_rerank_score")
         return scores[:P]
+
+    def parts(self, total_q_tokens: int) -> int:
+        return int(lib.hr_rerank_parts(self.handle, int(total_q_tokens)))
 
     def set_streams(self, n: int) -> None:
         check(lib.hr_rerank_set_streams(self.handle, int(n)), "hr_rerank_set_streams")

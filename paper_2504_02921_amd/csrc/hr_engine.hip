@@ -459,6 +459,12 @@ size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t tot
                .total + (m->mfma_gemm ? kSplitSlackBytes : 0);
 }
 
+// Whether a scoring call of T query tokens is cut in two halves (given the MFMA attention and at least two pairs).
+static bool split_wanted(const hr_model* m, int64_t T) {
+    const int64_t tiles_h = ((T + 255) / 256) * ((m->cfg.hidden + 255) / 256);
+    return m->n_streams >= 2 && m->mfma_gemm && T >= kSplitMinTokens && 2 * tiles_h <= 7 * (int64_t)hr::device_cu_count();
+}
+
 // One contiguous part of a scoring call.  prepare: its metadata (already validated) is built at `stage` and its upload to the
 // head of `wsb` is enqueued on `st`; run: the layers are enqueued (on any stream ordered behind the upload).  ws / ml are
 // the part's own carving.
@@ -547,9 +553,7 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     // rounds of 256 x 256 tiles, where the partly filled last round is a large share (0.5B shape: -7.7 % at 1.25
     // rounds, -2.4 % at 2.5, +0.6 % at 5; 8B shape: -6.7 % at 3.1 rounds, +0.5 % at 4.0, +7 % at 4.75 and 6.25: there two
     // kernels that share the chip cost each other more than the rounds they fill).
-    const int64_t tiles_h = ((T + 255) / 256) * ((m->cfg.hidden + 255) / 256);
-    if (m->n_streams >= 2 && m->mfma_gemm && mfma_attn && n_pairs >= 2 && T >= kSplitMinTokens &&
-        2 * tiles_h <= 7 * (int64_t)hr::device_cu_count()) {
+    if (mfma_attn && n_pairs >= 2 && split_wanted(m, T)) {
         int64_t t = 0;
         int32_t p = 0;
         while (p < n_pairs - 1 && t < T / 2) t += query_lens[p++];
@@ -608,6 +612,11 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     m->stage_pending = true;
     if (rc != HR_OK) return rc;
     return run_score_part(m, pool, part, ws, wsb, max_q, scores_dev, st);
+}
+
+int hr_rerank_parts(const hr_model* m, int64_t total_q_tokens) {
+    if (!m || total_q_tokens < 0) return HR_ERR_INVALID_ARG;
+    return split_wanted(m, total_q_tokens) ? 2 : 1;
 }
 
 int hr_rerank_set_streams(hr_model* m, int n_streams) {

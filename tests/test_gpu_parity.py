@@ -351,7 +351,9 @@ def test_two_stream_halves_are_bit_identical_and_ordered_on_the_callers_stream()
             s2 = case.model.score(case.pool, wl.page_table, wl.doc_lens, wl.query_tokens, wl.query_lens)
             top2 = hb.rerank_topk(s2, seg, 3)
         side.synchronize()
+        assert case.model.parts(wl.total_q_tokens) == 2 and case.model.parts(100) == 1 and case.model.parts(10 ** 8) == 1
         case.model.set_streams(1)
+        assert case.model.parts(wl.total_q_tokens) == 1
         s1 = case.gpu_scores()
         np.testing.assert_array_equal(s2.cpu().numpy().astype(np.float64), s1)
         np.testing.assert_array_equal(top2.cpu().numpy(), orr.topk(s1, seg, 3))
