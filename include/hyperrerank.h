@@ -21,6 +21,8 @@
  *     one handle must not overlap in host time; different handles, and pools, are independent.  The library
  *     allocates no device memory, but it owns that small pinned host buffer and, once a scoring call has been
  *     cut in two halves, one stream and three events per model handle (released by hr_model_destroy).
+ *   - Calls that upload per-call metadata (scoring, prefill) wait on the host for the previous upload of the same
+ *     handle and copy from its staging buffer: they are not meant to be recorded into a HIP graph.
  *   - Every call returns HR_OK (0) or a negative hr_status.  On error nothing
  *     is enqueued and no library state changes.  Nothing throws or aborts.
  *   - All matrices are row-major [out][in]; activations use the model dtype
