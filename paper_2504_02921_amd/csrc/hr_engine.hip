@@ -1,5 +1,6 @@
-// Device-facing entry points of libhyperrerank: weight packing, pool writes and the layer loop of
-// the scoring pass (query suffix over cached document KV) and of the no-reuse reference pass.
+// Device-facing entry points of libhyperrerank: weight packing, pool writes and reads, the host tier's page moves, and
+// the layer loop shared by the scoring pass (query suffix over cached document KV; large calls as two halves on two
+// streams), the no-reuse reference pass and the document prefill.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>

@@ -1,15 +1,16 @@
 // 16-bit MFMA GEMM family for the projections of the scoring pass (gfx950).  Operands are half
 // (the caller's bf16 weights are converted once when they are packed; activations are produced as half):
 //   C[M][N] = A[M][K] * W[N][K]^T with fp32 accumulation and a fused epilogue
-//     EPI_QKV_ROPE  : split into q / k / v, rotate-half RoPE on q and k, store bf16
+//     EPI_QKV_ROPE  : split into q / k / v, rotate-half RoPE on q and k, store half (K and V as pool-format pages)
 //     EPI_RESID_ADD : x[M][N] += C   (fp32 residual stream)
-//     EPI_SWIGLU    : gate/up rows interleaved in blocks of 32 -> m = silu(g) * u, store bf16
+//     EPI_SWIGLU    : gate/up rows interleaved in blocks of 32 -> m = silu(g) * u, store half
 // Both operands are K-contiguous, which is exactly the MFMA operand order (a lane holds 8
 // consecutive k of one row / column), so tiles go global -> LDS -> registers without transposes.
 //
-// Tiling: 256 x BN x 64 macro tile per 256-thread workgroup (4 wavefronts as 2 x 2, each wave
-// 128 x BN/2 = 4 x (BN/64) blocks of v_mfma_f32_32x32x16_f16), LDS double-buffered, rows of 64
-// k (128 B) with the 16-byte chunk index XOR-swizzled by the row pair ((row >> 1) & 7): LDS serves
+// Tiling: BM x BN x 64 macro tiles of 32 x 32 blocks of v_mfma_f32_32x32x16_f16: 256 x 256 with 8 wavefronts
+// (one workgroup per CU), 128 x 128 with 4 (two per CU), wider-than-tall shapes for 128-wide heads, and ring
+// variants with 3-5 LDS stages for launches of few rows; the launcher picks per call.  LDS rows are 64 k
+// (128 B) with the 16-byte chunk index XOR-swizzled by the row pair ((row >> 1) & 7): LDS serves
 // 256 bytes per cycle to 16 lanes of a ds_read_b128, i.e. two 128-byte rows side by side, so 16
 // consecutive rows must use 8 different chunk positions per row parity (measured: 217 B/clk/CU with
 // this pattern against 119 with a (row & 7) swizzle and 32 unswizzled).
