@@ -613,21 +613,25 @@ hipError_t launch_pack_rows(int dtype, const void* src, void* dst, int rows, int
 }
 
 
-// ---- host tier: whole pages between the pool and page records.  One workgroup per (page, layer) moves the layer's
-// n_kv * (K block + V block) bytes, contiguous on both sides, as 16-byte words, four loads in flight per thread (the
-// record side may be pinned host memory behind the bus: many small workgroups keep enough reads outstanding); the first
-// 2 * n_kv threads also move the layer's fp8 scales.
+// ---- host tier: whole pages between the pool and page records; a (page, layer) unit is n_kv * (K block + V block)
+// bytes, contiguous on both sides, moved as 16-byte words.
+// Out of the pool: one workgroup per unit; the first 2 * n_kv threads also move the layer's fp8 scales.
+// Into the pool: a fixed, small number of workgroups walk the chunk's records word by word in record order, eight
+// 16-byte loads in flight per thread.  The records may be pinned host memory behind the bus, and a page-in usually runs
+// next to a scoring call that fills the compute units: a few long-lived workgroups hold on to the slots they have won
+// and keep ~1 MB of reads outstanding, where thousands of short ones wait for a slot each (measured at the 0.5B shape
+// next to scoring: 53 against 44 GB/s sustained over a batch; alone both reach the bus rate).
 namespace {
-template <bool TO_POOL>
-__global__ void __launch_bounds__(256) pages_move_kernel(char* __restrict__ pool, float* __restrict__ scales, PageIdChunk page_ids,
-                                                         char* __restrict__ records, size_t record_bytes, int layer_bytes, int n_layers,
-                                                         int num_pages, int n_kv) {
+constexpr int kPageInWalkers = 64;    // measured: 16 too few (40 GB/s), 32..64 the bus rate, 96 and more lose again
+constexpr int kPageIn4Walkers = 128;  // 4-bit records (one unit in flight ahead per workgroup): 32 too few, 96..128 best
+
+__global__ void __launch_bounds__(256) pages_out_kernel(const char* __restrict__ pool, const float* __restrict__ scales,
+                                                        PageIdChunk page_ids, char* __restrict__ records, size_t record_bytes,
+                                                        int layer_bytes, int n_layers, int num_pages, int n_kv) {
     const int page = page_ids.ids[blockIdx.x], layer = blockIdx.y;
     char* rec = records + (size_t)blockIdx.x * record_bytes;
-    uint4* pw = (uint4*)(pool + ((size_t)layer * num_pages + page) * layer_bytes);
-    uint4* rw = (uint4*)(rec + (size_t)layer * layer_bytes);
-    const uint4* src = TO_POOL ? rw : pw;
-    uint4* dst = TO_POOL ? pw : rw;
+    const uint4* src = (const uint4*)(pool + ((size_t)layer * num_pages + page) * layer_bytes);
+    uint4* dst = (uint4*)(rec + (size_t)layer * layer_bytes);
     const int n = layer_bytes / 16;
     for (int i0 = threadIdx.x; i0 < n; i0 += 4 * 256) {
         uint4 v[4];
@@ -638,11 +642,41 @@ __global__ void __launch_bounds__(256) pages_move_kernel(char* __restrict__ pool
         for (int u = 0; u < 4; ++u)
             if (i0 + u * 256 < n) dst[i0 + u * 256] = v[u];
     }
-    if (scales && (int)threadIdx.x < 2 * n_kv) {
-        float* ps = scales + ((size_t)layer * num_pages + page) * n_kv * 2 + threadIdx.x;
-        float* rs = (float*)(rec + (size_t)n_layers * layer_bytes) + (size_t)layer * n_kv * 2 + threadIdx.x;
-        if (TO_POOL) *ps = *rs;
-        else *rs = *ps;
+    if (scales && (int)threadIdx.x < 2 * n_kv)
+        ((float*)(rec + (size_t)n_layers * layer_bytes))[(size_t)layer * n_kv * 2 + threadIdx.x] =
+            scales[((size_t)layer * num_pages + page) * n_kv * 2 + threadIdx.x];
+}
+
+__global__ void __launch_bounds__(256) pages_in_kernel(char* __restrict__ pool, float* __restrict__ scales, PageIdChunk page_ids,
+                                                       const char* __restrict__ records, size_t record_bytes, int layer_bytes,
+                                                       int n_layers, int num_pages, int n_kv, int n_chunk_pages) {
+    const int n = layer_bytes / 16;                            // words of one unit
+    const long long words = (long long)n_chunk_pages * n_layers * n;
+    for (long long w0 = (long long)blockIdx.x * 2048 + threadIdx.x; w0 < words; w0 += (long long)gridDim.x * 2048) {
+        uint4 v[8];
+        uint4* dst[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const long long w = w0 + u * 256;
+            dst[u] = nullptr;
+            if (w < words) {
+                const int unit = (int)(w / n), off = (int)(w - (long long)unit * n);
+                const int pi = unit / n_layers, layer = unit - pi * n_layers;
+                v[u] = ((const uint4*)(records + (size_t)pi * record_bytes + (size_t)layer * layer_bytes))[off];
+                dst[u] = (uint4*)(pool + ((size_t)layer * num_pages + page_ids.ids[pi]) * layer_bytes) + off;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (dst[u]) *dst[u] = v[u];
+    }
+    if (scales) {
+        const int per_page = n_layers * n_kv * 2;
+        for (int s = blockIdx.x * 256 + threadIdx.x; s < n_chunk_pages * per_page; s += gridDim.x * 256) {
+            const int pi = s / per_page, r = s - pi * per_page, layer = r / (n_kv * 2), j = r - layer * (n_kv * 2);
+            scales[((size_t)layer * num_pages + page_ids.ids[pi]) * n_kv * 2 + j] =
+                ((const float*)(records + (size_t)pi * record_bytes + (size_t)n_layers * layer_bytes))[r];
+        }
     }
 }
 }  // namespace
@@ -656,20 +690,24 @@ hipError_t launch_pages_move(const PoolLayout& lay, char* pool_base, const int32
         const int n = (int)(n_pages - pg0 < 256 ? n_pages - pg0 : 256);
         PageIdChunk ids;
         for (int i = 0; i < 256; ++i) ids.ids[i] = i < n ? page_ids_host[pg0 + i] : 0;
-        const dim3 grid((unsigned)n, (unsigned)lay.n_layers);
         char* r = records + (size_t)pg0 * rec;
-        if (to_pool)
-            pages_move_kernel<true><<<grid, 256, 0, st>>>(pool_base, scales, ids, r, rec, layer_bytes, lay.n_layers, lay.num_pages, lay.n_kv);
-        else
-            pages_move_kernel<false><<<grid, 256, 0, st>>>(pool_base, scales, ids, r, rec, layer_bytes, lay.n_layers, lay.num_pages, lay.n_kv);
+        if (to_pool) {
+            const long long passes = ((long long)n * lay.n_layers * (layer_bytes / 16) + 2047) / 2048;
+            const unsigned grid = (unsigned)(passes < kPageInWalkers ? passes : kPageInWalkers);
+            pages_in_kernel<<<grid, 256, 0, st>>>(pool_base, scales, ids, r, rec, layer_bytes, lay.n_layers, lay.num_pages, lay.n_kv, n);
+        } else {
+            pages_out_kernel<<<dim3((unsigned)n, (unsigned)lay.n_layers), 256, 0, st>>>(pool_base, scales, ids, r, rec, layer_bytes,
+                                                                                        lay.n_layers, lay.num_pages, lay.n_kv);
+        }
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-// ---- host tier, 4-bit records of a 16-bit pool.  One workgroup per (page, layer, kv head), one thread per group of 32
-// channels of one token of K or V: 2 * 16 * d / 32 = d threads.  Out: gather the group from the page (K: four 16-byte
+// ---- host tier, 4-bit records of a 16-bit pool.  A unit is a (page, layer, kv head); one thread per group of 32
+// channels of one token of K or V: 2 * 16 * d / 32 = d threads.  Out of the pool one workgroup per unit, into the pool
+// kPageIn4Walkers workgroups that walk the units (see above).  Out: gather the group from the page (K: four 16-byte
 // chunks of the token's row, V: 32 keys-major elements), scale = amax / 7, codes by round-to-nearest-even of the exact
 // quotient.  In: codes * scale, rounded to half, back to the page positions.
 namespace {
@@ -679,56 +717,78 @@ __device__ __forceinline__ size_t kv4_group_elem(bool is_v, int t, int c, int d)
 
 template <bool TO_POOL>
 __global__ void pages_move4_kernel(half_t* __restrict__ pool, PageIdChunk page_ids, char* __restrict__ records, size_t record_bytes,
-                                   int num_pages, int n_kv, int d) {
+                                   int num_pages, int n_kv, int d, int units_per_page, int n_units) {
     // The page (4 or 8 KiB) passes through LDS so that the pool side is read and written in whole 16-byte words; the
-    // groups' element order (strided in the V block) is an LDS access pattern only.
+    // groups' element order (strided in the V block) is an LDS access pattern only.  A workgroup walks the units
+    // (page, layer, kv head) in record order with the grid's stride; on the way in, the next unit's codes and scale are
+    // requested before the current one is expanded, so that every workgroup keeps a read on the bus.
     __shared__ __attribute__((aligned(16))) half_t page_lds[2 * kPageTokens * 128];
-    const int page = page_ids.ids[blockIdx.x];
-    const int layer = blockIdx.y / n_kv, h = blockIdx.y % n_kv;
     const int gpt = d / 32;                                   // groups per token
     const int tid = threadIdx.x;                              // 0 .. d - 1
     const bool is_v = tid >= kPageTokens * gpt;
     const int r = is_v ? tid - kPageTokens * gpt : tid;
     const int t = r / gpt, gi = r - t * gpt;
-    uint4* pg = (uint4*)(pool + (((size_t)layer * num_pages + page) * n_kv + h) * (2 * kPageTokens * d));
     uint4* lds16 = (uint4*)page_lds;
     constexpr int WPT = 2 * kPageTokens * 2 / 16;             // 16-byte words of the page per thread: 4 (page = 64 d bytes)
-    char* rec = records + (size_t)blockIdx.x * record_bytes + (size_t)blockIdx.y * (20 * d);
-    uint4* codes = (uint4*)(rec + (is_v ? kPageTokens * d / 2 : 0) + t * (d / 2) + gi * 16);
-    float* scale = (float*)(rec + kPageTokens * d) + (is_v ? kPageTokens * gpt : 0) + t * gpt + gi;
-    if constexpr (!TO_POOL) {
+    const size_t code_off = (size_t)(is_v ? kPageTokens * d / 2 : 0) + t * (d / 2) + gi * 16;
+    const size_t scale_off = (size_t)kPageTokens * d + 4 * ((is_v ? kPageTokens * gpt : 0) + t * gpt + gi);
+    auto unit_rec = [&](int u) { return records + (size_t)(u / units_per_page) * record_bytes + (size_t)(u % units_per_page) * (20 * d); };
+    auto unit_page = [&](int u) {
+        const int y = u % units_per_page, layer = y / n_kv, h = y - layer * n_kv;
+        return (uint4*)(pool + (((size_t)layer * num_pages + page_ids.ids[u / units_per_page]) * n_kv + h) * (2 * kPageTokens * d));
+    };
+    int u = blockIdx.x;
+    if (u >= n_units) return;
+    uint4 cw = make_uint4(0u, 0u, 0u, 0u);
+    float sc = 0.f;
+    if constexpr (TO_POOL) {
+        cw = *(const uint4*)(unit_rec(u) + code_off);
+        sc = *(const float*)(unit_rec(u) + scale_off);
+    }
+    for (; u < n_units; u += gridDim.x) {
+        uint4* pg = unit_page(u);
+        if constexpr (!TO_POOL) {
+            char* rec = unit_rec(u);
 #pragma unroll
-        for (int i = 0; i < WPT; ++i) lds16[i * d + tid] = pg[i * d + tid];
-        __syncthreads();
-        float x[32];
-        float amax = 0.f;
+            for (int i = 0; i < WPT; ++i) lds16[i * d + tid] = pg[i * d + tid];
+            __syncthreads();
+            float x[32];
+            float amax = 0.f;
 #pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            x[i] = (float)page_lds[kv4_group_elem(is_v, t, gi * 32 + i, d)];
-            amax = fmaxf(amax, fabsf(x[i]));
+            for (int i = 0; i < 32; ++i) {
+                x[i] = (float)page_lds[kv4_group_elem(is_v, t, gi * 32 + i, d)];
+                amax = fmaxf(amax, fabsf(x[i]));
+            }
+            const float s1 = amax > 0.f ? amax / 7.0f : 1.0f;
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                double q = rint((double)x[i] / (double)s1);   // the default rounding mode: ties to even
+                q = q < -7.0 ? -7.0 : (q > 7.0 ? 7.0 : q);
+                w[i >> 3] |= ((uint32_t)(int)q & 0xFu) << ((i & 7) * 4);
+            }
+            *(uint4*)(rec + code_off) = make_uint4(w[0], w[1], w[2], w[3]);
+            *(float*)(rec + scale_off) = s1;
+            __syncthreads();                                  // the page in LDS is read out before the next one lands
+        } else {
+            const uint4 cur = cw;
+            const float cur_sc = sc;
+            const int un = u + (int)gridDim.x;
+            if (un < n_units) {
+                cw = *(const uint4*)(unit_rec(un) + code_off);
+                sc = *(const float*)(unit_rec(un) + scale_off);
+            }
+            const uint32_t w[4] = {cur.x, cur.y, cur.z, cur.w};
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                const int code = ((int)(w[i >> 3] << (28 - (i & 7) * 4))) >> 28;      // sign-extended nibble
+                page_lds[kv4_group_elem(is_v, t, gi * 32 + i, d)] = from_float<half_t>((float)code * cur_sc);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < WPT; ++i) pg[i * d + tid] = lds16[i * d + tid];
+            __syncthreads();
         }
-        const float sc = amax > 0.f ? amax / 7.0f : 1.0f;
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            double q = rint((double)x[i] / (double)sc);       // the default rounding mode: ties to even
-            q = q < -7.0 ? -7.0 : (q > 7.0 ? 7.0 : q);
-            w[i >> 3] |= ((uint32_t)(int)q & 0xFu) << ((i & 7) * 4);
-        }
-        *codes = make_uint4(w[0], w[1], w[2], w[3]);
-        *scale = sc;
-    } else {
-        const uint4 cw = *codes;
-        const float sc = *scale;
-        const uint32_t w[4] = {cw.x, cw.y, cw.z, cw.w};
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-            const int code = ((int)(w[i >> 3] << (28 - (i & 7) * 4))) >> 28;      // sign-extended nibble
-            page_lds[kv4_group_elem(is_v, t, gi * 32 + i, d)] = from_float<half_t>((float)code * sc);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < WPT; ++i) pg[i * d + tid] = lds16[i * d + tid];
     }
 }
 }  // namespace
@@ -741,10 +801,11 @@ hipError_t launch_pages_move4(const PoolLayout& lay, char* pool_base, const int3
         const int n = (int)(n_pages - pg0 < 256 ? n_pages - pg0 : 256);
         PageIdChunk ids;
         for (int i = 0; i < 256; ++i) ids.ids[i] = i < n ? page_ids_host[pg0 + i] : 0;
-        const dim3 grid((unsigned)n, (unsigned)(lay.n_layers * lay.n_kv));
+        const int upp = lay.n_layers * lay.n_kv, units = n * upp;
+        const unsigned grid = (unsigned)(to_pool && kPageIn4Walkers < units ? kPageIn4Walkers : units);
         char* r = records + (size_t)pg0 * rec;
-        if (to_pool) pages_move4_kernel<true><<<grid, lay.d, 0, st>>>((half_t*)pool_base, ids, r, rec, lay.num_pages, lay.n_kv, lay.d);
-        else pages_move4_kernel<false><<<grid, lay.d, 0, st>>>((half_t*)pool_base, ids, r, rec, lay.num_pages, lay.n_kv, lay.d);
+        if (to_pool) pages_move4_kernel<true><<<grid, lay.d, 0, st>>>((half_t*)pool_base, ids, r, rec, lay.num_pages, lay.n_kv, lay.d, upp, units);
+        else pages_move4_kernel<false><<<grid, lay.d, 0, st>>>((half_t*)pool_base, ids, r, rec, lay.num_pages, lay.n_kv, lay.d, upp, units);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

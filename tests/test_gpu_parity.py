@@ -635,6 +635,35 @@ def test_four_bit_host_tier_matches_the_oracle_quantiser(d, n_q, n_kv):
         case.close()
 
 
+@pytest.mark.parametrize("d,n_q,n_kv,kv", [(64, 14, 2, "bf16"), (128, 8, 8, "fp8")])
+def test_prefixes_of_a_batch_score_the_same_bits_across_scheduling_thresholds(d, n_q, n_kv, kv):
+    """The library picks tile shapes, ring or two-stage GEMMs, attention work-item plans and one or two streams from the
+    size of the call.  Scoring the first n pairs of a batch for n on both sides of those thresholds must give the bits
+    those pairs have inside the whole batch."""
+    hidden = 256 if d == 64 else 512
+    model = small_model(dtype="bf16", n_layers=2, hidden=hidden, n_q=n_q, n_kv=n_kv, d=d, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("thresholds", model, 40, 8, (5, 100), (20, 40), kv, pool_docs=30, zipf_a=0.9, seed=81)
+    w = wlmod.SeededWeights(model, seed=82, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(cfg, spare_pages=3)
+    assert wl.total_q_tokens >= 8192              # the whole batch runs as two halves
+    case = H.Case(wl, w)
+    try:
+        case.fill_synthetic(oracle_doc_ids=[], all_docs=True)
+        whole = case.gpu_scores()
+        assert np.all(np.isfinite(whole))
+        cus = 256
+        first_split = int(np.searchsorted(np.cumsum(wl.query_lens), 8192)) + 1    # fewest pairs with >= 8192 tokens
+        marks = {1, 2, 3, cus // (2 * n_kv), cus // (2 * n_kv) + 1, 128, 129, first_split - 1, first_split,
+                 wl.n_pairs - 1}
+        assert case.model.parts(int(wl.query_lens[:first_split - 1].sum())) == 1
+        assert case.model.parts(int(wl.query_lens[:first_split].sum())) == 2
+        for n in sorted(x for x in marks if 1 <= x < wl.n_pairs):
+            part = case.gpu_scores(wl.subset(np.arange(n)))
+            np.testing.assert_array_equal(part, whole[:n], err_msg=f"first {n} pairs")
+    finally:
+        case.close()
+
+
 def test_demo_walkthrough_runs_and_is_consistent():
     """The package's end-to-end demo: prefill, score, top-k, no-reuse comparison, host-tier round trip."""
     from paper_2504_02921_amd import demo
