@@ -47,6 +47,7 @@ using namespace hr;
 constexpr int64_t kGenericMaxKeys = 15000;     // scores of one row live in LDS in the generic attention
 constexpr int64_t kMfmaMaxKeys = 1 << 20;
 constexpr int64_t kSplitMinTokens = 8192;      // query tokens from which a scoring call is cut in two halves
+constexpr double kSplitMaxFill = 0.85;         // ... when the N = hidden GEMMs' tiles fill less than this share of their rounds
 constexpr size_t kSplitSlackBytes = (size_t)1 << 20;   // what two carvings of a workspace may need beyond one (alignment gaps,
                                                        // the larger group-plan room of calls with few pairs)
 
@@ -460,10 +461,10 @@ size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t tot
                .total + (m->mfma_gemm ? kSplitSlackBytes : 0);
 }
 
-// Whether a scoring call of T query tokens is cut in two halves (given the MFMA attention and at least two pairs).
+// Whether a scoring call of T query tokens is cut in two halves (given the MFMA attention and at least two pairs): when
+// the tiles of the N = hidden GEMMs would leave more than 15 % of the workgroup slots of their rounds empty.
 static bool split_wanted(const hr_model* m, int64_t T) {
-    const int64_t tiles_h = ((T + 255) / 256) * ((m->cfg.hidden + 255) / 256);
-    return m->n_streams >= 2 && m->mfma_gemm && T >= kSplitMinTokens && 2 * tiles_h <= 7 * (int64_t)hr::device_cu_count();
+    return m->n_streams >= 2 && m->mfma_gemm && T >= kSplitMinTokens && hr::gemm_resid_fill(T, m->cfg.hidden) < kSplitMaxFill;
 }
 
 // One contiguous part of a scoring call.  prepare: its metadata (already validated) is built at `stage` and its upload to the
@@ -542,18 +543,18 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     hipStream_t st = (hipStream_t)stream;
     char* wsb = (char*)workspace_dev;
 
-    // Two halves on two streams.  Every GEMM of a call ends with a round of tiles that fills only part of the chip (e.g.
-    // 1120 tiles on 512 resident workgroups), and the next kernel of the same stream cannot start before it is over; with
-    // the pairs cut in two halves that run on two streams, one half's kernels start on the CUs the other half's last
-    // round leaves idle.  A pair's arithmetic does not depend on the batch around it, so the scores are bit for bit the
-    // same.  Only when both halves still fill the chip on their own, only on the MFMA path, and only for calls small
-    // enough for the last rounds to matter.
+    // Two halves on two streams.  A GEMM whose tiles do not divide into full rounds of the chip ends with a round that
+    // fills only part of it, and the next kernel of the same stream cannot start before it is over; with the pairs cut in
+    // two halves that run on two streams, one half's kernels start on the CUs the other half's last round leaves idle.
+    // A pair's arithmetic does not depend on the batch around it, so the scores are bit for bit the same.  Only on the
+    // MFMA path, and only when the narrowest GEMMs of a layer (O and down projection, N = hidden) leave a sizeable
+    // share of their rounds empty: two kernels that share the chip cost each other a few percent, which the halves
+    // must first win back.
     int32_t n_a = n_pairs;
     int64_t T_a = T;
-    // Measured: the halves gain while the narrowest GEMMs of a layer (O and down projection, N = hidden) have few
-    // rounds of 256 x 256 tiles, where the partly filled last round is a large share (0.5B shape: -7.7 % at 1.25
-    // rounds, -2.4 % at 2.5, +0.6 % at 5; 8B shape: -6.7 % at 3.1 rounds, +0.5 % at 4.0, +7 % at 4.75 and 6.25: there two
-    // kernels that share the chip cost each other more than the rounds they fill).
+    // Measured, two streams against one, by the fill of those rounds: 0.5B shape 62 % -> -11 %, 78 % -> -5 %, 94 % ->
+    // +9 % and -3 %, 100 % -> -0.7 %, -2 %, +2 %; 8B shape 83 % -> -1.5 %, 87 % -> 0, 92 % -> +5.4 %, 94 % -> -1.2 %,
+    // +3.8 %, +1 %, 98 % -> +3 %, 100 % -> 0, +3.5 %.
     if (mfma_attn && n_pairs >= 2 && split_wanted(m, T)) {
         int64_t t = 0;
         int32_t p = 0;

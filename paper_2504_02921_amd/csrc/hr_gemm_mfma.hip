@@ -82,19 +82,21 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BM / WM / 32][BN /
         // bank conflicts of the column-wise writes) the update reads and writes whole 512-byte row segments.  The
         // stages hold BM x CW floats, so the tile goes in PASSES column slabs; each wave tile lies in one slab.
         constexpr int LDS_BYTES = 2 * (BM + BN) * BK * (int)sizeof(half_t);
-        constexpr int PASSES = (BM * BN * 4 + LDS_BYTES - 1) / LDS_BYTES;
+        constexpr int PASSES_MIN = (BM * BN * 4 + LDS_BYTES - 1) / LDS_BYTES;
+        constexpr int PASSES = PASSES_MIN <= 2 ? PASSES_MIN : (PASSES_MIN <= 4 ? 4 : 8);     // a divisor of BN
         constexpr int CW = BN / PASSES;                 // slab width in columns
         constexpr int CPRW = CW / 4;                    // 16-byte chunks per slab row
         constexpr int ITER = BM * CPRW / NT;
-        static_assert(EPI != EPI_RESID_ADD || (CW % TN == 0 && CPRW % 16 == 0 && (BM * CPRW) % (4 * NT) == 0 && BM * CW * 4 <= LDS_BYTES),
+        constexpr int NG = ITER % 4 == 0 ? 4 : 5;       // register groups of the x update (320-row tiles: 10 = 5 x 2)
+        static_assert(EPI != EPI_RESID_ADD || (CW % TN == 0 && CPRW % 16 == 0 && (BM * CPRW) % (NG * NT) == 0 && BM * CW * 4 <= LDS_BYTES),
                       "slab shape");
         float* stage = (float*)smem;
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
-            // x in four groups of G chunks per lane (registers): the first is requested before the stage is written, so
+            // x in NG groups of G chunks per lane (registers): the first is requested before the stage is written, so
             // its latency hides behind the write and the barrier.  Every address is clamped into the matrix, only
             // valid chunks are written back.
-            constexpr int G = ITER / 4;
+            constexpr int G = ITER / NG;
             float4 xv[G];
             auto load_x = [&](int first) {
 #pragma unroll
@@ -149,7 +151,7 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BM / WM / 32][BN /
             __syncthreads();
             update_x(0);
 #pragma unroll
-            for (int g = 1; g < 4; ++g) {
+            for (int g = 1; g < NG; ++g) {
                 load_x(g * G);
                 update_x(g * G);
             }
@@ -657,23 +659,41 @@ int cu_count() {
     return n;
 }
 
-// Tile shape choice.  Two shapes are kept: "big" = 256 x 256 with 8 waves (one workgroup per CU, the
-// highest rate per output) and "small" = 128 x 128 with 4 waves (two workgroups per CU, ~14 % more
-// time per output but four times finer tiles).  With T x N outputs spread over 256 CUs the last round
-// of tiles is what decides (e.g. N = 896: 3.5 big column tiles), so the cost of a shape is modelled as
-// rounds x resident workgroups x tile area x relative cost per output, from measured rates.
-bool prefer_big(int64_t M, int N, int small_bn) {
+// Tile shape choice.  "big" = 256 x 256 with 8 waves (one workgroup per CU, the highest rate per output), "tall" =
+// 320 x 256 with 8 waves (residual epilogue only: 12.5 % more operand bytes per k-tile for 25 % more rows, and 20 % fewer
+// tiles) and "small" = 128 x 128 with 4 waves (two workgroups per CU, ~14 % more time per output but four times finer
+// tiles).  With T x N outputs spread over 256 CUs the last round of tiles is what decides (e.g. T = 20480, N = 896:
+// 320 big tiles are two rounds, 256 tall tiles one), so the cost of a shape is modelled as rounds x resident
+// workgroups x tile area x relative cost per output, from measured rates.
+enum TileChoice { TILE_SMALL, TILE_BIG, TILE_TALL };
+
+TileChoice choose_tile(int64_t M, int N, int small_bn, bool tall_ok) {
     const int64_t cus = cu_count();
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    const int64_t tall_tiles = ((M + 319) / 320) * ((N + 255) / 256);
     const int64_t small_tiles = ((M + 127) / 128) * ((N + small_bn - 1) / small_bn);
     const double big = (double)((big_tiles + cus - 1) / cus) * 256.0 * 256.0 * 1.0;
+    const double tall = (double)((tall_tiles + cus - 1) / cus) * 320.0 * 256.0 * 0.9;
     const double small = (double)((small_tiles + 2 * cus - 1) / (2 * cus)) * 2.0 * 128.0 * small_bn * 1.14;
-    return big <= small;
+    if (tall_ok && tall < big && tall <= small) return TILE_TALL;
+    return big <= small ? TILE_BIG : TILE_SMALL;
 }
 
 }  // namespace
 
 int device_cu_count() { return cu_count(); }
+
+double gemm_resid_fill(int64_t M, int N) {
+    const int64_t cus = cu_count();
+    int64_t tiles = 0, slots = cus;
+    switch (choose_tile(M, N, 128, true)) {
+        case TILE_TALL: tiles = ((M + 319) / 320) * ((N + 255) / 256); break;
+        case TILE_BIG: tiles = ((M + 255) / 256) * ((N + 255) / 256); break;
+        case TILE_SMALL: tiles = ((M + 127) / 128) * ((N + 127) / 128); slots = 2 * cus; break;
+    }
+    if (tiles <= 0) return 1.0;
+    return (double)tiles / (double)(((tiles + slots - 1) / slots) * slots);
+}
 
 bool gemm_mfma_supported(const hr_model_cfg& c) {
     if (c.dtype != HR_BF16) return false;
@@ -708,9 +728,11 @@ hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st)
                 return r64 ? launch_ring<EPI_SWIGLU, 64, 128, 2, 2, 1, 5>(a, st) : launch_ring<EPI_SWIGLU, 128, 128, 2, 2, 1, 4>(a, st);
         }
     }
-    bool big = prefer_big(a.M, a.N, wide_head ? 256 : 128);
-    if (var == 0) big = true;
-    if (var == 2) big = false;
+    TileChoice tile = choose_tile(a.M, a.N, wide_head ? 256 : 128, epi == EPI_RESID_ADD);
+    if (var == 0) tile = TILE_BIG;
+    if (var == 2) tile = TILE_SMALL;
+    if (tile == TILE_TALL) return launch_tile<EPI_RESID_ADD, 320, 256, 2, 4, 1>(a, st);
+    const bool big = tile == TILE_BIG;
     switch (epi) {
         case EPI_QKV_ROPE:
             if (!wide_head) {

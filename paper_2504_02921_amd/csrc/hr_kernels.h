@@ -56,6 +56,9 @@ hipError_t launch_pack_rows(int dtype, const void* src, void* dst, int rows, int
 // ---- MFMA paths (bf16) ----
 bool gemm_mfma_supported(const hr_model_cfg& c);
 int device_cu_count();      // compute units of the current device (256 if it cannot be asked)
+// Share of the workgroup slots that the tiles of an M x N residual GEMM fill in the rounds they take (tile shape as the
+// launcher would choose it): 1.0 = every round full.
+double gemm_resid_fill(int64_t M, int N);
 enum GemmEpilogue { EPI_QKV_ROPE = 0, EPI_RESID_ADD = 1, EPI_SWIGLU = 2 };
 struct GemmArgs {
     const void* A;      // [M][K] bf16
