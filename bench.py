@@ -6,7 +6,8 @@ One "step" = one hr_rerank_score call over the whole workload (all pairs, all la
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2_qwen0p5b]
 
-The timed steps run the way the library runs them: a large call as two halves on two streams.
+The timed steps run the way the library runs them: in one piece, or (where the library chooses so for
+the size of the call) as two halves on two streams; config.streams says which.
 Besides the headline pairs/s the line carries
   roofline            the kernel class with the largest share of the step (per-kernel HIP events,
                       recorded by the library on the stream it launches on), measured in K more steps
@@ -101,8 +102,8 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # The library runs a large call as two halves on two streams (one half's kernels fill the CUs that the other half's
-    # last round of GEMM tiles leaves idle).  That is what the timed region measures.  A kernel's own duration is then
+    # The library may run a large call as two halves on two streams (one half's kernels fill the CUs that the other half's
+    # last round of GEMM tiles leaves idle).  The timed region measures what it chooses for this size.  A kernel's own duration is then
     # no longer a statement about the kernel: it includes waiting for CUs the other half's kernel holds.  So the
     # per-kernel figures come from steps with the second stream switched off, where every kernel has the chip to itself:
     # two survey steps before the timed region time every kernel class (the breakdown, and which class is dominant);

@@ -232,8 +232,8 @@ size_t hr_rerank_workspace_bytes(const hr_model* model, int32_t n_pairs, int64_t
  * Pairs of one call whose doc_lens and page-table rows are identical (the same cached document: Section 3.3,
  * pairwise independence makes a document's KV reusable for every query) share one pass over its pages in the
  * attention kernels; the scores are bit for bit those of the pairs scored alone.
- * A call with at least 8192 query tokens on the MFMA path, up to the size where the O / down projection takes 3.5
- * rounds of 256 x 256 tiles on the device, runs as two halves of the pairs, the first on `stream`,
+ * A call with at least 8192 query tokens on the MFMA path whose O / down projection tiles would leave more than 15 % of
+ * the device's workgroup slots empty in the rounds they take runs as two halves of the pairs, the first on `stream`,
  * the second on a stream of the library's own that starts behind the work already enqueued on `stream` and that
  * `stream` waits for before anything enqueued after the call (see hr_rerank_set_streams); to the caller the call
  * is ordered on `stream` as if it were one piece of work. */
