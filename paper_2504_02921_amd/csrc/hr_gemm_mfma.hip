@@ -8,14 +8,16 @@
 // consecutive k of one row / column), so tiles go global -> LDS -> registers without transposes.
 //
 // Tiling: BM x BN x 64 macro tiles of 32 x 32 blocks of v_mfma_f32_32x32x16_f16: 256 x 256 with 8 wavefronts
-// (one workgroup per CU), 128 x 128 with 4 (two per CU), wider-than-tall shapes for 128-wide heads, and ring
-// variants with 3-5 LDS stages for launches of few rows; the launcher picks per call.  LDS rows are 64 k
+// (one workgroup per CU), 320 x 256 with 8 for residual-add launches where the taller tile saves a round of the chip,
+// 128 x 128 with 4 (two per CU), wider-than-tall shapes for 128-wide heads, and ring variants with 3-5 LDS stages for
+// launches of few rows; the launcher picks per call.  LDS rows are 64 k
 // (128 B) with the 16-byte chunk index XOR-swizzled by the row pair ((row >> 1) & 7): LDS serves
 // 256 bytes per cycle to 16 lanes of a ds_read_b128, i.e. two 128-byte rows side by side, so 16
 // consecutive rows must use 8 different chunk positions per row parity (measured: 217 B/clk/CU with
 // this pattern against 119 with a (row & 7) swizzle and 32 unswizzled).
 // Workgroup ids are remapped so that each XCD (ids are dealt round-robin over 8 XCDs) works on a
-// contiguous run of tiles, grouped 8 tiles tall, keeping its private L2 on few A/W panels.
+// contiguous run of tiles, grouped 8 tiles tall, keeping its private L2 on few A/W panels (groups 4 or 16 tall
+// measured the same).
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
