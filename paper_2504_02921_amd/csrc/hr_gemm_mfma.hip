@@ -8,7 +8,7 @@
 // consecutive k of one row / column), so tiles go global -> LDS -> registers without transposes.
 //
 // Tiling: BM x BN x 64 macro tiles of 32 x 32 blocks of v_mfma_f32_32x32x16_f16: 256 x 256 with 8 wavefronts
-// (one workgroup per CU), 320 x 256 with 8 for residual-add launches where the taller tile saves a round of the chip,
+// (one workgroup per CU), 320 x 256 with 8 for residual-add and long-K gate/up launches where it saves rounds of the chip,
 // 128 x 128 with 4 (two per CU), wider-than-tall shapes for 128-wide heads, and ring variants with 3-5 LDS stages for
 // launches of few rows; the launcher picks per call.  LDS rows are 64 k
 // (128 B) with the 16-byte chunk index XOR-swizzled by the row pair ((row >> 1) & 7): LDS serves
@@ -167,10 +167,16 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BM / WM / 32][BN /
         constexpr int ITER = BM * CPRO / NT;
         static_assert(EPI != EPI_SWIGLU || ((CPRO == 16 || CPRO == 8) && (BM * CPRO) % NT == 0), "output tile shape");
         auto swz = [](int r) { return CPRO == 16 ? (r & 15) : ((r >> 1) & 7); };
-        // staged in the second stages of A and W: the first ones may already be receiving the next tile
+        // staged in the second stages of A and W: the first ones may already be receiving the next tile.  The tall tile's
+        // output does not fit there; its launch is not persistent and stages from the start of the LDS.
+        constexpr bool WHOLE = BM > 256;
         constexpr int R1 = BM * BK / OW;                 // tile rows that fit the A stage
-        static_assert(EPI != EPI_SWIGLU || (R1 <= BM && (BM - R1) * OW <= BN * BK), "staging fits the second stages");
-        auto stage_row = [&](int r) { return r < R1 ? sA + BM * BK + r * OW : sB + BN * BK + (r - R1) * OW; };
+        static_assert(EPI != EPI_SWIGLU || (WHOLE ? BM * OW <= 2 * (BM + BN) * BK : (R1 <= BM && (BM - R1) * OW <= BN * BK)),
+                      "staging fits the stages");
+        auto stage_row = [&](int r) {
+            if constexpr (WHOLE) return (half_t*)smem + r * OW;
+            else return r < R1 ? sA + BM * BK + r * OW : sB + BN * BK + (r - R1) * OW;
+        };
         half_t* out = (half_t*)a.out0;
         const int F = a.N / 2;
 #pragma unroll
@@ -353,7 +359,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
     // XCD-chunked order) and requests the first k-tile of its next tile before it starts the epilogue of the current
     // one, so only a workgroup's first tile pays the start-up round trip (3.4k of a 50k-cycle tile at K = 896).  Its
     // epilogue has no loads that would queue behind that request.  The other launches run one tile per workgroup.
-    constexpr bool PERSIST = EPI == EPI_SWIGLU;
+    constexpr bool PERSIST = EPI == EPI_SWIGLU && BM <= 256;
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (a.N + BN - 1) / BN;
     int vpid = blockIdx.x;
     TileCoord tc = map_tile(vpid, tiles_m, tiles_n);
@@ -607,7 +613,7 @@ hipError_t launch_tile(const GemmArgs& a, hipStream_t st) {
     const int n_tiles = tiles_m * tiles_n;
     const int per_xcd = (n_tiles + kXcds - 1) / kXcds;
     int grid = per_xcd * kXcds;
-    if (EPI == EPI_SWIGLU && tuning_variant() != 5) {
+    if (EPI == EPI_SWIGLU && BM <= 256 && tuning_variant() != 5) {
         // persistent launch: as many workgroups as are resident at once (one big or two small tiles per CU), a multiple
         // of the XCD count so that the walk blockIdx.x + k * gridDim.x stays on its XCD
         const int resident = cu_count() * (BM >= 256 ? 1 : 2) / kXcds * kXcds;
@@ -662,8 +668,8 @@ int cu_count() {
 }
 
 // Tile shape choice.  "big" = 256 x 256 with 8 waves (one workgroup per CU, the highest rate per output), "tall" =
-// 320 x 256 with 8 waves (residual epilogue only: 12.5 % more operand bytes per k-tile for 25 % more rows, and 20 % fewer
-// tiles) and "small" = 128 x 128 with 4 waves (two workgroups per CU, ~14 % more time per output but four times finer
+// 320 x 256 with 8 waves (where the caller allows it: 12.5 % more operand bytes per k-tile for 25 % more rows, and 20 %
+// fewer tiles) and "small" = 128 x 128 with 4 waves (two workgroups per CU, ~14 % more time per output but four times finer
 // tiles).  With T x N outputs spread over 256 CUs the last round of tiles is what decides (e.g. T = 20480, N = 896:
 // 320 big tiles are two rounds, 256 tall tiles one), so the cost of a shape is modelled as rounds x resident
 // workgroups x tile area x relative cost per output, from measured rates.
@@ -730,10 +736,14 @@ hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st)
                 return r64 ? launch_ring<EPI_SWIGLU, 64, 128, 2, 2, 1, 5>(a, st) : launch_ring<EPI_SWIGLU, 128, 128, 2, 2, 1, 4>(a, st);
         }
     }
-    TileChoice tile = choose_tile(a.M, a.N, wide_head ? 256 : 128, epi == EPI_RESID_ADD);
+    // the tall tile: residual-add launches, and gate/up launches with a long k loop (not persistent: at K = 896 the
+    // start-up round trip per tile costs more than the shape saves)
+    const bool tall_ok = epi == EPI_RESID_ADD || (epi == EPI_SWIGLU && a.K >= 2048 && var != 8);
+    TileChoice tile = choose_tile(a.M, a.N, wide_head ? 256 : 128, tall_ok);
     if (var == 0) tile = TILE_BIG;
     if (var == 2) tile = TILE_SMALL;
-    if (tile == TILE_TALL) return launch_tile<EPI_RESID_ADD, 320, 256, 2, 4, 1>(a, st);
+    if (tile == TILE_TALL)
+        return epi == EPI_RESID_ADD ? launch_tile<EPI_RESID_ADD, 320, 256, 2, 4, 1>(a, st) : launch_tile<EPI_SWIGLU, 320, 256, 2, 4, 1>(a, st);
     const bool big = tile == TILE_BIG;
     switch (epi) {
         case EPI_QKV_ROPE:
