@@ -737,7 +737,7 @@ hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st)
         }
     }
     // the tall tile: residual-add launches, and gate/up launches with a long k loop (not persistent: at K = 896 the
-    // start-up round trip per tile costs more than the shape saves)
+    // start-up round trip per tile costs more than the shape saves: 8.8 against 8.0 ms per step at the 0.5B shape)
     const bool tall_ok = epi == EPI_RESID_ADD || (epi == EPI_SWIGLU && a.K >= 2048 && var != 8);
     TileChoice tile = choose_tile(a.M, a.N, wide_head ? 256 : 128, tall_ok);
     if (var == 0) tile = TILE_BIG;
