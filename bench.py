@@ -14,6 +14,8 @@ Besides the headline pairs/s the line carries
                       with the second stream switched off, where the kernel has the chip to itself
   one_stream          the rate of those steps
   roofline_attention  the KV-streaming attention kernel against HBM peak
+  ceilings            yardsticks on the same device from plain library calls (a copy-like kernel, the
+                      vendor GEMM on a large square and on this workload's projection shapes)
   cpu_baseline        the CPU oracle timed on a bounded sample of the same pairs
   no_reuse            the same GPU running the full [doc ; query] prefill on a few pairs
   doc_prefill         stage one on the device: documents prefilled into pool pages (ingest rate)
@@ -56,6 +58,7 @@ def main():
     ap.add_argument("--prefill-docs", type=int, default=128, help="documents for the document-prefill (ingest) leg (0 = skip)")
     ap.add_argument("--host-tier-batches", type=int, default=6,
                     help="batches of the paged leg: every batch's documents come from pinned host memory (0 = skip)")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the vendor-library yardsticks (copy kernel, library GEMM)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -225,6 +228,44 @@ def main():
                     "note": "all four projections, from the survey steps"}
     else:
         gemm_all = None
+
+    # ---- what this device gives to plain library calls (yardsticks, not part of the scoring path): a 1 GiB copy-like
+    # kernel for the memory side, the vendor GEMM on a large square and on the dominant projection's own shape
+    ceilings = None
+    if not args.no_ceilings and model.gemm_path() == "mfma":
+        def timed(fn, n):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(n):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n * 1e-3
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        t_copy = timed(lambda: torch.bitwise_not(src, out=dst), 10)
+        del src, dst
+        ceilings = {"hbm_copy_GBps": round(2 * (1 << 30) / t_copy / 1e9, 1),
+                    "note": "torch.bitwise_not over 1 GiB (read + write); torch.matmul in half precision (the vendor library), without the "
+                            "fused epilogues of this path"}
+        shapes = {"square_8192": (8192, 8192, 8192)}
+        if T >= 1024:
+            shapes["gate_up_shape"] = (T, 2 * m.ffn, m.hidden)
+            shapes["down_shape"] = (T, m.hidden, m.ffn)
+        for key, (mm, nn, kk) in shapes.items():
+            a_ = torch.randn(mm, kk, device=dev, dtype=torch.float16) * 0.1
+            b_ = torch.randn(nn, kk, device=dev, dtype=torch.float16) * 0.1
+            c_ = torch.empty(mm, nn, device=dev, dtype=torch.float16)
+            t_mm = timed(lambda: torch.matmul(a_, b_.t(), out=c_), 10)
+            ceilings["matmul_" + key] = {"M": mm, "N": nn, "K": kk, "ms": round(t_mm * 1e3, 4), "TFLOPs": round(2.0 * mm * nn * kk / t_mm / 1e12, 1)}
+            del a_, b_, c_
+        if roofline and roofline.get("bound") == "mfma":
+            roofline["frac_of_library_square_gemm"] = round(roofline["achieved"] / ceilings["matmul_square_8192"]["TFLOPs"], 4)
+        if roof_attn:
+            roof_attn["frac_of_copy_kernel"] = round(roof_attn["achieved"] / ceilings["hbm_copy_GBps"], 4)
 
     # ---- same-GPU no-reuse reference on a few pairs ------------------------------------------
     no_reuse = None
@@ -417,7 +458,7 @@ def main():
                                        "survey steps before it" if not args.no_events else "none"),
                    "events_in_timed_region": "none"},
         "roofline": roofline, "roofline_attention": roof_attn, "gemm_overall": gemm_all, "one_stream": single,
-        "kernel_breakdown": breakdown, "cpu_baseline": cpu, "no_reuse": no_reuse, "doc_prefill": doc_prefill, "host_tier": host_tier, "host_tier_4bit": host_tier4,
+        "kernel_breakdown": breakdown, "ceilings": ceilings, "cpu_baseline": cpu, "no_reuse": no_reuse, "doc_prefill": doc_prefill, "host_tier": host_tier, "host_tier_4bit": host_tier4,
         "paper_context": "2-3x end-to-end service throughput from reranker KV reuse on 8x A100 (Table 1); not this metric",
     }
     print(json.dumps(line), flush=True)
