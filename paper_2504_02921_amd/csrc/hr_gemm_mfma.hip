@@ -24,6 +24,7 @@
 #include <type_traits>
 
 #include "hr_device_types.h"
+#include "hr_internal.h"
 #include "hr_kernels.h"
 #include "hr_layout.h"
 
@@ -667,41 +668,11 @@ int cu_count() {
     return n;
 }
 
-// Tile shape choice.  "big" = 256 x 256 with 8 waves (one workgroup per CU, the highest rate per output), "tall" =
-// 320 x 256 with 8 waves (where the caller allows it: 12.5 % more operand bytes per k-tile for 25 % more rows, and 20 %
-// fewer tiles) and "small" = 128 x 128 with 4 waves (two workgroups per CU, ~14 % more time per output but four times finer
-// tiles).  With T x N outputs spread over 256 CUs the last round of tiles is what decides (e.g. T = 20480, N = 896:
-// 320 big tiles are two rounds, 256 tall tiles one), so the cost of a shape is modelled as rounds x resident
-// workgroups x tile area x relative cost per output, from measured rates.
-enum TileChoice { TILE_SMALL, TILE_BIG, TILE_TALL };
-
-TileChoice choose_tile(int64_t M, int N, int small_bn, bool tall_ok) {
-    const int64_t cus = cu_count();
-    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-    const int64_t tall_tiles = ((M + 319) / 320) * ((N + 255) / 256);
-    const int64_t small_tiles = ((M + 127) / 128) * ((N + small_bn - 1) / small_bn);
-    const double big = (double)((big_tiles + cus - 1) / cus) * 256.0 * 256.0 * 1.0;
-    const double tall = (double)((tall_tiles + cus - 1) / cus) * 320.0 * 256.0 * 0.9;
-    const double small = (double)((small_tiles + 2 * cus - 1) / (2 * cus)) * 2.0 * 128.0 * small_bn * 1.14;
-    if (tall_ok && tall < big && tall <= small) return TILE_TALL;
-    return big <= small ? TILE_BIG : TILE_SMALL;
-}
-
 }  // namespace
 
 int device_cu_count() { return cu_count(); }
 
-double gemm_resid_fill(int64_t M, int N) {
-    const int64_t cus = cu_count();
-    int64_t tiles = 0, slots = cus;
-    switch (choose_tile(M, N, 128, true)) {
-        case TILE_TALL: tiles = ((M + 319) / 320) * ((N + 255) / 256); break;
-        case TILE_BIG: tiles = ((M + 255) / 256) * ((N + 255) / 256); break;
-        case TILE_SMALL: tiles = ((M + 127) / 128) * ((N + 127) / 128); slots = 2 * cus; break;
-    }
-    if (tiles <= 0) return 1.0;
-    return (double)tiles / (double)(((tiles + slots - 1) / slots) * slots);
-}
+double gemm_resid_fill(int64_t M, int N) { return gemm_tile_fill(M, N, cu_count()); }
 
 bool gemm_mfma_supported(const hr_model_cfg& c) {
     if (c.dtype != HR_BF16) return false;
@@ -739,7 +710,7 @@ hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st)
     // the tall tile: residual-add launches, and gate/up launches with a long k loop (not persistent: at K = 896 the
     // start-up round trip per tile costs more than the shape saves: 8.8 against 8.0 ms per step at the 0.5B shape)
     const bool tall_ok = epi == EPI_RESID_ADD || (epi == EPI_SWIGLU && a.K >= 2048 && var != 8);
-    TileChoice tile = choose_tile(a.M, a.N, wide_head ? 256 : 128, tall_ok);
+    TileChoice tile = choose_gemm_tile(a.M, a.N, wide_head ? 256 : 128, tall_ok, cu_count());
     if (var == 0) tile = TILE_BIG;
     if (var == 2) tile = TILE_SMALL;
     if (tile == TILE_TALL)

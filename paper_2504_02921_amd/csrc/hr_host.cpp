@@ -380,6 +380,30 @@ void store_group_plan(const GroupPlan& gp, int32_t* dst) {
     }
 }
 
+TileChoice choose_gemm_tile(int64_t M, int N, int small_bn, bool tall_ok, int cus_) {
+    const int64_t cus = cus_ > 0 ? cus_ : 1;
+    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+    const int64_t tall_tiles = ((M + 319) / 320) * ((N + 255) / 256);
+    const int64_t small_tiles = ((M + 127) / 128) * ((N + small_bn - 1) / small_bn);
+    const double big = (double)((big_tiles + cus - 1) / cus) * 256.0 * 256.0 * 1.0;
+    const double tall = (double)((tall_tiles + cus - 1) / cus) * 320.0 * 256.0 * 0.9;
+    const double small = (double)((small_tiles + 2 * cus - 1) / (2 * cus)) * 2.0 * 128.0 * small_bn * 1.14;
+    if (tall_ok && tall < big && tall <= small) return TILE_TALL;
+    return big <= small ? TILE_BIG : TILE_SMALL;
+}
+
+double gemm_tile_fill(int64_t M, int N, int cus_) {
+    const int64_t cus = cus_ > 0 ? cus_ : 1;
+    int64_t tiles = 0, slots = cus;
+    switch (choose_gemm_tile(M, N, 128, true, (int)cus)) {
+        case TILE_TALL: tiles = ((M + 319) / 320) * ((N + 255) / 256); break;
+        case TILE_BIG: tiles = ((M + 255) / 256) * ((N + 255) / 256); break;
+        case TILE_SMALL: tiles = ((M + 127) / 128) * ((N + 127) / 128); slots = 2 * cus; break;
+    }
+    if (tiles <= 0) return 1.0;
+    return (double)tiles / (double)(((tiles + slots - 1) / slots) * slots);
+}
+
 }  // namespace hr
 
 // ------------------------------------------------------------------------------------------------

@@ -139,6 +139,19 @@ constexpr int64_t kGroupCutMaxSeqs = 128;      // more sequences than this alway
 GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* page_table,
                           int64_t pt_stride, int g, int cap_blocks, bool cut_long = false);
 size_t group_plan_ints_bound(int64_t n_seq, int64_t T, int g);
+
+// ---- tile shape of an M x N MFMA GEMM launch on a device of `cus` compute units.  "big" = 256 x 256 with 8 waves (one
+// workgroup per CU, the highest rate per output), "tall" = 320 x 256 with 8 waves (where the caller allows it: 12.5 % more
+// operand bytes per k-tile for 25 % more rows, and 20 % fewer tiles) and "small" = 128 x small_bn with 4 waves (two
+// workgroups per CU, ~14 % more time per output but four times finer tiles).  With M x N outputs spread over the CUs the
+// last round of tiles is what decides (e.g. M = 20480, N = 896 on 256 CUs: 320 big tiles are two rounds, 256 tall tiles
+// one), so the cost of a shape is modelled as rounds x resident workgroups x tile area x relative cost per output,
+// from measured rates.
+enum TileChoice { TILE_SMALL, TILE_BIG, TILE_TALL };
+TileChoice choose_gemm_tile(int64_t M, int N, int small_bn, bool tall_ok, int cus);
+// Share of the workgroup slots that the tiles of an M x N residual GEMM fill in the rounds they take, in the shape
+// choose_gemm_tile picks for it (tall allowed): 1.0 = every round full.
+double gemm_tile_fill(int64_t M, int N, int cus);
 // Writes the plan at dst (>= plan.ints() entries) in the order p0, blk_cu, sub_cu, blk_seq, blk_row0, sub_page, sub_seq,
 // sub_key0.
 void store_group_plan(const GroupPlan& plan, int32_t* dst);

@@ -172,6 +172,37 @@ int main() {
     dls[1] = 48;
     CHECK(hr::score_check_args(mc, pool, 2, table, 3, dls, qt, qls, 1 << 20, &T) == HR_ERR_TABLE_SHORT);
     hr_kv_pool_destroy(pool);
+
+    // tile shape choice: the chosen shape is the cheapest of the model, the tall tile only where allowed and only where it
+    // saves rounds, the fill of the rounds lies in (0, 1]; the cases the design names come out as stated
+    {
+        auto rounds = [](int64_t tiles, int64_t slots) { return (tiles + slots - 1) / slots; };
+        std::srand(7);
+        for (int it = 0; it < 2000; ++it) {
+            const int64_t M = 1 + std::rand() % 120000;
+            const int N = 64 * (1 + std::rand() % 480);
+            const int cus = 8 * (1 + std::rand() % 40);
+            const hr::TileChoice no_tall = hr::choose_gemm_tile(M, N, 128, false, cus);
+            const hr::TileChoice any = hr::choose_gemm_tile(M, N, 128, true, cus);
+            CHECK(no_tall != hr::TILE_TALL);
+            if (any == hr::TILE_TALL) {
+                const int64_t big = ((M + 255) / 256) * ((N + 255) / 256), tall = ((M + 319) / 320) * ((N + 255) / 256);
+                CHECK(rounds(tall, cus) < rounds(big, cus));
+            } else {
+                CHECK(any == no_tall);
+            }
+            const double fill = hr::gemm_tile_fill(M, N, cus);
+            CHECK(fill > 0.0 && fill <= 1.0);
+        }
+        CHECK(hr::choose_gemm_tile(20480, 896, 128, true, 256) == hr::TILE_TALL);      // 320 big tiles = 2 rounds, 256 tall = 1
+        CHECK(hr::choose_gemm_tile(20480, 896, 128, false, 256) == hr::TILE_SMALL);     // 1120 small tiles in 3 rounds beat 2 big rounds
+        CHECK(hr::gemm_tile_fill(20480, 896, 256) == 1.0);
+        CHECK(hr::choose_gemm_tile(10240, 896, 128, true, 256) == hr::TILE_BIG);       // one round either way: the cheaper tile
+        CHECK(hr::choose_gemm_tile(12800, 4096, 128, true, 256) == hr::TILE_TALL);     // 800 -> 640 tiles, 4 -> 3 rounds
+        const double f8b = hr::gemm_tile_fill(12800, 4096, 256);
+        CHECK(f8b > 0.83 && f8b < 0.84);                                               // 640 of 768 slots
+        CHECK(hr::gemm_tile_fill(25600, 4096, 256) == 1.0);                            // 1280 tall tiles = 5 full rounds
+    }
     std::printf("host logic clean under sanitizers\n");
     return 0;
 }
