@@ -66,6 +66,12 @@ void note_hip_error(hipError_t e, const char* what) {
         }                                              \
     } while (0)
 
+// The MFMA attention reads the new tokens' K/V as pool-format pages, which only the MFMA QKV projection's epilogue
+// writes: the two kernel families are chosen together.
+bool use_mfma_attn(const hr_model* m, int kv_dtype, int max_new_len) {
+    return !m->force_generic && m->mfma_gemm && attn_mfma_supported(m->cfg, kv_dtype, max_new_len);
+}
+
 const void* layer_w(const hr_model* m, int l, size_t off) {
     size_t esz = dtype_size(m->cfg.dtype);
     return m->pack_base + ((size_t)l * m->pack.layer_elems + off) * esz;
@@ -171,7 +177,7 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
         pv.num_pages = 1;
         if (self_prefix) pv.data = (const char*)k;     // layer index 0 of a one-layer "pool" = the new-KV page buffer
     }
-    const bool mfma_attn = !m->force_generic && attn_mfma_supported(c, pv.kv_dtype, max_new_len);
+    const bool mfma_attn = use_mfma_attn(m, pv.kv_dtype, max_new_len);
     if (self_prefix && !mfma_attn) return HR_ERR_UNSUPPORTED_SHAPE;
     // the shortened last layer needs one output row per sequence, the MFMA kernels, something to save (T > P), and
     // room for P fp32 rows in the q buffer
@@ -528,7 +534,7 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     int max_q = 0;
     if (n_pairs > 0 && query_lens)
         for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
-    const bool mfma_attn = !m->force_generic && hr::attn_mfma_supported(m->cfg, pool->cfg.kv_dtype, max_q);
+    const bool mfma_attn = use_mfma_attn(m, pool->cfg.kv_dtype, max_q);
     int64_t T = 0;
     int rc = hr::score_check_args(m->cfg, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens,
                                   mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys, &T);
@@ -633,7 +639,7 @@ int hr_rerank_validate(const hr_model_cfg* cfg, const hr_pool* pool, int32_t n_p
     int max_q = 0;
     if (n_pairs > 0 && query_lens)
         for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
-    const bool mfma_attn = hr::attn_mfma_supported(*cfg, pool->cfg.kv_dtype, max_q);
+    const bool mfma_attn = hr::gemm_mfma_supported(*cfg) && hr::attn_mfma_supported(*cfg, pool->cfg.kv_dtype, max_q);
     return hr::score_check_args(*cfg, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens,
                                 mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys, nullptr);
 }
@@ -840,7 +846,7 @@ const char* hr_last_error(void) { return g_last_error; }
 
 const char* hr_attention_path(const hr_model* m, const hr_pool* pool) {
     if (!m || !pool) return "none";
-    return !m->force_generic && hr::attn_mfma_supported(m->cfg, pool->cfg.kv_dtype, 1) ? "mfma" : "generic";
+    return use_mfma_attn(m, pool->cfg.kv_dtype, 1) ? "mfma" : "generic";
 }
 
 const char* hr_gemm_path(const hr_model* m) {

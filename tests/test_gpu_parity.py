@@ -112,6 +112,19 @@ def test_mfma_attention_shapes_and_edges(d, n_q, n_kv, kv, doc_len, q_len):
     case.close()
 
 
+@pytest.mark.parametrize("hidden,ffn", [(256, 688), (200, 320)])
+def test_bf16_wide_heads_with_projection_shapes_outside_the_mfma_family(hidden, ffn):
+    """head_dim 64 suits the MFMA attention, but hidden / ffn are not multiples of 64, so the projections run on the
+    generic kernels, which leave the new tokens' K/V row-major and not as pages: attention must follow them."""
+    model = small_model(dtype="bf16", n_layers=2, hidden=hidden, n_q=4, n_kv=2, d=64, ffn=ffn, vocab=500)
+    cfg = wlmod.WorkloadCfg("bf16_mixed", model, 3, 4, (20, 100), (3, 33), "bf16", seed=hidden)
+    w = wlmod.SeededWeights(model, seed=16, std=0.05, gain_jitter=0.1)
+    case, got, want = run_case(cfg, w, H.TOL["bf16"])
+    assert case.model.gemm_path() == "generic" and case.model.attention_path(case.pool) == "generic"
+    assert np.abs(want).max() > 1e-2
+    case.close()
+
+
 def test_fp8_pool_small_model():
     model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=8, n_kv=2, d=32, ffn=352)
     cfg = wlmod.WorkloadCfg("fp8_small", model, 2, 4, (20, 90), (3, 12), "fp8", seed=5)
