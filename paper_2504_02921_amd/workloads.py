@@ -334,39 +334,82 @@ def synthetic_kv_sigma(model: ModelCfg) -> float:
     return 0.02 * math.sqrt(model.hidden)
 
 
+_M31 = (1 << 31) - 1
+
+
+def _hash31(x):
+    """Integer mixer on int64 tensors whose values lie in [0, 2^31): multiply / xor-shift rounds kept below 2^31,
+    with multipliers below 2^32, so that no product reaches 2^63 (no reliance on wrap-around).  Pure integer
+    arithmetic: the same bits on every device."""
+    x = (x * 0x9E3779B1) & _M31
+    x = ((x ^ (x >> 15)) * 0x45D9F3B) & _M31
+    x = ((x ^ (x >> 13)) * 0x2C1B3C6D) & _M31
+    x = ((x ^ (x >> 16)) * 0x297A2D39) & _M31
+    return x ^ (x >> 15)
+
+
+def _stream_key(seed: int, doc_id: int, which: int) -> int:
+    return int(np.random.SeedSequence([seed, 9001, int(doc_id), which]).generate_state(1)[0]) & _M31
+
+
+_IH_MEAN = 6 * 1023 / 2.0                                  # six uniform 10-bit fields
+_IH_STD = math.sqrt(6 * (1024.0 ** 2 - 1.0) / 12.0)
+
+
+def _bell_int(n: int, key_a: int, key_b: int, device):
+    """n seeded bell-shaped integers (sum of six uniform 10-bit fields of two counter hashes), as an int64 tensor:
+    mean _IH_MEAN, std _IH_STD, support within 4.24 std of the mean."""
+    import torch
+    idx = torch.arange(n, dtype=torch.int64, device=device)
+    h1 = _hash31(idx ^ key_a)
+    h2 = _hash31((idx + 0x3C6EF35) & _M31 ^ key_b)
+    s = (h1 & 1023) + ((h1 >> 10) & 1023) + ((h1 >> 20) & 1023)
+    s += (h2 & 1023) + ((h2 >> 10) & 1023) + ((h2 >> 20) & 1023)
+    return s
+
+
 def synthetic_doc_kv(wl: Workload, doc_id: int, device: str = "cpu"):
     """Seeded stand-in for one document's cached KV, logical layout [L][D][n_kv][d].
 
     Returns a dict of torch tensors on `device`:
-      f32 / bf16 pools: {"k", "v"} in that dtype.
+      f32 / bf16 pools: {"k", "v"} in that dtype, bell-shaped with std synthetic_kv_sigma.
       fp8 pools: {"k", "v"} as uint8 E4M3 codes, {"k_scale", "v_scale"} fp32
-      [L][n_pages][n_kv]; codes are drawn as N(0, 96^2) cast to fp8 and the
-      scales are drawn directly (log-uniform around sigma/96), so no quantiser
-      is involved: the scoring pass treats document KV as an opaque input.
-    The values depend on the device kind of the torch generator; callers that
-    feed both the oracle and the GPU pool copy the *same* tensor to both.
+      [L][n_pages][n_kv]; the coded values are bell-shaped with std 96 and the
+      scales are drawn directly (log-uniform within a factor sqrt(2) of sigma/96),
+      so no quantiser is involved: the scoring pass treats document KV as an opaque input.
+    Counter-based: every element is an integer hash of (seed, document, tensor, element index) turned into a value
+    by exact float operations (integer -> fp32, one multiplication, one library cast), so the bytes do not depend
+    on the device that draws them: the CPU oracle's inputs can be produced without a GPU and the GPU pool filled
+    on the device.
     """
     import torch
 
     m = wl.cfg.model
     D = int(wl.pool_doc_lens[doc_id])
-    g = torch.Generator(device=device)
-    g.manual_seed(int(np.random.SeedSequence([wl.cfg.seed, 9001, int(doc_id)]).generate_state(1)[0]))
     shape = (m.n_layers, D, m.n_kv_heads, m.head_dim)
+    n = m.n_layers * D * m.n_kv_heads * m.head_dim
+    assert n < (1 << 31)
     sigma = synthetic_kv_sigma(m)
+    seed = wl.cfg.seed
     out = {}
     if wl.cfg.kv_dtype in ("f32", "bf16"):
         dt = torch.float32 if wl.cfg.kv_dtype == "f32" else torch.bfloat16
-        for name in ("k", "v"):
-            out[name] = (torch.randn(shape, generator=g, device=device, dtype=torch.float32) * sigma).to(dt)
+        unit = float(np.float32(sigma / _IH_STD))
+        for w, name in enumerate(("k", "v")):
+            s = _bell_int(n, _stream_key(seed, doc_id, 2 * w), _stream_key(seed, doc_id, 2 * w + 1), device)
+            x = (s * 2 - int(2 * _IH_MEAN)).to(torch.float32) * (0.5 * unit)
+            out[name] = x.to(dt).reshape(shape)
         return out
     if wl.cfg.kv_dtype == "fp8":
         n_pages = (D + PAGE_TOKENS - 1) // PAGE_TOKENS
-        for name in ("k", "v"):
-            x = torch.randn(shape, generator=g, device=device, dtype=torch.float32) * 96.0
-            x = x.clamp_(-448.0, 448.0)
-            out[name] = x.to(torch.float8_e4m3fn).view(torch.uint8)
-            u = torch.rand((m.n_layers, n_pages, m.n_kv_heads), generator=g, device=device, dtype=torch.float32)
-            out[name + "_scale"] = (sigma / 96.0) * torch.exp2(u - 0.5)
+        unit = float(np.float32(96.0 / _IH_STD))
+        table = torch.from_numpy(((sigma / 96.0) * np.exp2(np.arange(256, dtype=np.float64) / 256.0 - 0.5)).astype(np.float32)).to(device)
+        ns = m.n_layers * n_pages * m.n_kv_heads
+        for w, name in enumerate(("k", "v")):
+            s = _bell_int(n, _stream_key(seed, doc_id, 2 * w), _stream_key(seed, doc_id, 2 * w + 1), device)
+            x = (s * 2 - int(2 * _IH_MEAN)).to(torch.float32) * (0.5 * unit)
+            out[name] = x.clamp_(-448.0, 448.0).to(torch.float8_e4m3fn).view(torch.uint8).reshape(shape)
+            pick = _hash31(torch.arange(ns, dtype=torch.int64, device=device) ^ _stream_key(seed, doc_id, 4 + w)) & 255
+            out[name + "_scale"] = table[pick].reshape(m.n_layers, n_pages, m.n_kv_heads)
         return out
     raise ValueError(wl.cfg.kv_dtype)

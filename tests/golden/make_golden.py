@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Writes the stored oracle scores the GPU parity tests compare against at the full sizes of the workload
+configurations:  tests/golden/<config>_scores.json.
+
+Only `oracle/` (the float64 CPU definition of the scoring pass) and the seeded input generators in
+`paper_2504_02921_amd/workloads.py` (which hold none of the method's arithmetic) are used: no value in these
+files comes from the HIP library.  The document KV of these shapes is the seeded opaque stand-in
+(`synthetic_doc_kv`: a CPU prefill of 0.5B / 8B-shaped documents would take hours), drawn here on the CPU; the
+GPU tests draw the same bytes on the device and check a sample of them against a CPU draw.
+
+Which pairs (the coverage rule: the full pair set where the host finishes in reasonable time, else a stratified
+subset that holds the extreme lengths and whole queries for the ranking check):
+  c2_qwen0p5b   all 640 pairs
+  c3_llama8b    all 400 pairs
+  c4_ragged     4 pairs of every one of the 256 queries (every query length), two whole queries, and the pairs
+                with the shortest / longest document and query: >= 1024 pairs
+  c5_long_fp8   the first query's 100 candidates and 2 candidates of each other query
+
+    python tests/golden/make_golden.py c3_llama8b [--store-gb 12]
+
+Run time on 8 cores: c2 ~5 min, c4 ~10 min, c5 ~40 min, c3 ~60 min.
+"""
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from oracle import reranker as orr                      # noqa: E402
+from paper_2504_02921_amd import workloads as wlmod     # noqa: E402
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def golden_pairs(wl) -> np.ndarray:
+    cfg = wl.cfg
+    n_c = cfg.n_cands
+    if cfg.name in ("c2_qwen0p5b", "c3_llama8b"):
+        return np.arange(wl.n_pairs, dtype=np.int64)
+    rng = np.random.default_rng(np.random.SeedSequence([cfg.seed, 5150]))
+    idx = {int(np.argmin(wl.doc_lens)), int(np.argmax(wl.doc_lens)), int(np.argmin(wl.query_lens)), int(np.argmax(wl.query_lens))}
+    if cfg.name == "c4_ragged":
+        for q in range(cfg.n_queries):
+            idx |= set((q * n_c + rng.choice(n_c, size=4, replace=False)).tolist())
+        for q in (0, cfg.n_queries - 1):
+            idx |= set(range(q * n_c, (q + 1) * n_c))
+    elif cfg.name == "c5_long_fp8":
+        idx |= set(range(n_c))
+        for q in range(1, cfg.n_queries):
+            idx |= set((q * n_c + rng.choice(n_c, size=2, replace=False)).tolist())
+    else:
+        raise ValueError(cfg.name)
+    return np.array(sorted(idx), dtype=np.int64)
+
+
+def whole_queries(cfg, pairs: np.ndarray):
+    have = set(pairs.tolist())
+    return [q for q in range(cfg.n_queries) if all(q * cfg.n_cands + c in have for c in range(cfg.n_cands))]
+
+
+def inputs_digest(wl, pairs: np.ndarray) -> str:
+    """Fingerprint of what the stored scores were computed from: the selected pairs' integer inputs and the bytes of
+    the first selected document's synthetic KV."""
+    import torch
+    h = hashlib.sha256()
+    sub = wl.subset(pairs)
+    for a in (pairs, sub.page_table, sub.doc_lens, sub.query_lens, sub.query_tokens):
+        h.update(np.ascontiguousarray(a).tobytes())
+    kv = wlmod.synthetic_doc_kv(wl, int(sub.pair_doc[0]), "cpu")
+    for name in sorted(kv):
+        t = kv[name]
+        if t.dtype == torch.bfloat16:
+            t = t.view(torch.int16)
+        h.update(t.contiguous().numpy().tobytes())
+    return h.hexdigest()
+
+
+def doc_store_bytes(wl, d: int) -> int:
+    m = wl.cfg.model
+    per = 1 if wl.cfg.kv_dtype == "fp8" else 8
+    pages = (int(wl.pool_doc_lens[d]) + 15) // 16
+    return m.n_layers * pages * 16 * m.n_kv_heads * m.head_dim * 2 * per
+
+
+def write_doc(opool, wl, d: int):
+    import torch
+    kv = wlmod.synthetic_doc_kv(wl, d, "cpu")
+    pages = wl.pool_doc_pages[d]
+    if wl.cfg.kv_dtype == "fp8":
+        opool.write(pages, kv["k"].numpy(), kv["v"].numpy(), kv["k_scale"].numpy(), kv["v_scale"].numpy())
+    else:
+        opool.write(pages, kv["k"].to(torch.float64).numpy(), kv["v"].to(torch.float64).numpy())
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("config")
+    ap.add_argument("--store-gb", type=float, default=12.0, help="most document KV held by the oracle's store at a time")
+    args = ap.parse_args()
+    cfg = wlmod.CONFIGS[args.config]
+    m = cfg.model
+    wl = wlmod.make_workload(cfg)
+    w = wlmod.SeededWeights(m, seed=cfg.seed)
+    pairs = golden_pairs(wl)
+    print(f"{cfg.name}: {len(pairs)} of {wl.n_pairs} pairs", flush=True)
+
+    # chunks of consecutive selected pairs whose distinct documents fit the store budget
+    budget = args.store_gb * 1e9
+    chunks, cur, cur_docs, cur_bytes = [], [], set(), 0
+    for p in pairs:
+        d = int(wl.pair_doc[p])
+        add = 0 if d in cur_docs else doc_store_bytes(wl, d)
+        if cur and cur_bytes + add > budget:
+            chunks.append(cur)
+            cur, cur_docs, cur_bytes, add = [], set(), 0, doc_store_bytes(wl, d)
+        cur.append(int(p))
+        cur_docs.add(d)
+        cur_bytes += add
+    if cur:
+        chunks.append(cur)
+
+    scores = np.empty(len(pairs), dtype=np.float64)
+    t0 = time.time()
+    done = 0
+    for ci, chunk in enumerate(chunks):
+        opool = orr.PagedKV(m.n_layers, m.n_kv_heads, m.head_dim, 16, cfg.kv_dtype)
+        for d in sorted(set(int(wl.pair_doc[p]) for p in chunk)):
+            write_doc(opool, wl, d)
+        print(f"  chunk {ci + 1}/{len(chunks)}: {len(chunk)} pairs, store filled at {time.time() - t0:.0f} s", flush=True)
+        sub = wl.subset(np.array(chunk))
+        s = orr.score_cached(w, m, opool, sub.page_table, sub.doc_lens, sub.query_tokens, sub.query_lens)
+        scores[done:done + len(chunk)] = s
+        done += len(chunk)
+        del opool
+        print(f"  chunk {ci + 1}/{len(chunks)} scored at {time.time() - t0:.0f} s", flush=True)
+
+    out = {
+        "config": cfg.name,
+        "what": "oracle.reranker.score_cached (float64) on the seeded workload; document KV = workloads.synthetic_doc_kv",
+        "written_by": "tests/golden/make_golden.py",
+        "seed": cfg.seed,
+        "n_pairs_total": wl.n_pairs,
+        "whole_queries": whole_queries(cfg, pairs),
+        "inputs_sha256": inputs_digest(wl, pairs),
+        "oracle_seconds": round(time.time() - t0, 1),
+        "host_threads": len(os.sched_getaffinity(0)),
+        "pairs": pairs.tolist(),
+        "scores": [repr(float(x)) for x in scores],
+    }
+    path = os.path.join(HERE, f"{cfg.name}_scores.json")
+    with open(path, "w") as f:
+        json.dump(out, f, indent=0)
+        f.write("\n")
+    print(f"wrote {path}: {len(pairs)} scores, mean |s| {np.abs(scores).mean():.3f}, {time.time() - t0:.0f} s", flush=True)
+
+
+if __name__ == "__main__":
+    main()
