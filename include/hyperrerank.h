@@ -264,7 +264,8 @@ int hr_rerank_validate(const hr_model_cfg* cfg, const hr_pool* pool, int32_t n_p
 size_t hr_rerank_full_workspace_bytes(const hr_model* model, int32_t n_pairs, int64_t total_tokens);
 
 /* scores[p] from one causal pass over the concatenation of doc_tokens and query_tokens of pair p;
- * no pool is involved.  doc_tokens / query_tokens are flat host int32 arrays, pair after pair. */
+ * no pool is involved.  doc_tokens / query_tokens are flat host int32 arrays, pair after pair.
+ * A sequence may hold up to 32768 tokens on the MFMA kernels (15000 on the generic ones): HR_ERR_LEN_RANGE beyond. */
 int hr_rerank_score_full(hr_model* model, int32_t n_pairs,
                          const int32_t* doc_tokens, const int32_t* doc_lens,
                          const int32_t* query_tokens, const int32_t* query_lens,
@@ -279,7 +280,7 @@ size_t hr_doc_prefill_workspace_bytes(const hr_model* model, int32_t n_docs, int
  * K and V in the pool pages the caller names, ready for hr_rerank_score.  Same kernels as the scoring pass: a
  * document is processed as chunks of 64 tokens whose prefix is the document's own earlier pages.
  *   doc_tokens  host int32, the documents' token ids back to back
- *   doc_lens    host int32 [n_docs], each >= 1
+ *   doc_lens    host int32 [n_docs], each 1 .. 32768
  *   page_table  host int32 [n_docs][pt_stride]; row d names ceil(doc_lens[d]/16) distinct free (or reserved) pages
  * 16-bit and fp8 pools, MFMA-covered models only (HR_ERR_UNSUPPORTED_SHAPE otherwise).  For an fp8 pool every page
  * is quantised as it is stored: per (layer, page, kv head) and separately for K and V, scale = amax / 448 over the page
@@ -308,7 +309,6 @@ int hr_rerank_topk(const float* scores_dev, const int32_t* seg_dev, int32_t n_qu
 
 /* ---- introspection for benchmarks ---- */
 
-/* Name of the kernel family a model/pool combination runs ("generic", "mfma"); never NULL. */
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch of a scoring call is
  * bracketed by two HIP events on the call's stream, tagged with a kernel class (hr_profile_name:
  * "gemm_gate_up", "attention", ...; hr_profile_count classes).  hr_profile_read waits for the
@@ -323,8 +323,17 @@ int hr_profile_count(void);
 const char* hr_profile_name(int idx);
 int hr_profile_read(hr_model* model, double* ms_out, int64_t* launches_out);
 
+/* Name of the kernel family a model / pool combination runs: "mfma" or "generic" ("none" for a null handle); never
+ * NULL.  The MFMA attention is only chosen together with the MFMA projections. */
 const char* hr_attention_path(const hr_model* model, const hr_pool* pool);
 const char* hr_gemm_path(const hr_model* model);
+
+/* Environment switches, read once per model handle at hr_weights_load.  They exist for A/B runs of the tests and
+ * benchmarks (each pair of settings must give the same score bits) and change no result:
+ *   HR_FORCE_GENERIC=1      every step on the generic fp32-arithmetic kernels
+ *   HR_NO_LAST_SHORTCUT=1   the last layer runs on every token instead of each pair's last one
+ *   HR_NO_DOC_GROUPS=1      pairs that share a document are not batched into one attention work item
+ *   HR_STREAMS=1            the initial value of hr_rerank_set_streams is 1 */
 
 #ifdef __cplusplus
 }

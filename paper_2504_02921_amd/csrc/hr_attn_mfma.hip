@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 
@@ -575,40 +576,32 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     flush_out();
 }
 
-int attn_wgs_override() {
-    static int v = -1;
-    if (v < 0) {
-        const char* e = getenv("HR_ATTN_WGS");      // tuning runs only
-        v = e ? atoi(e) : 0;
-    }
-    return v;
-}
-
 template <int HD, int NW, int R, bool FP8>
 hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const MetaView& mv, const PoolView& pv, int layer, int n_q,
                       int last_only, const GroupView& gv, hipStream_t st) {
     constexpr int SB = stage_bytes(FP8);
     const size_t lds = 2 * SB + 2 * Geo<HD, FP8, SB>::PPS * 2 * sizeof(float) + (FP8 ? 2 * SB : 0);
-    static bool attr_set = false;
-    if (!attr_set) {
+    // once per kernel instantiation and device (a host thread may drive any device): the LDS attribute, and the size of
+    // the persistent grid = as many workgroups as can be resident (LDS: two per CU), each looping over work items
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> max_wgs_dev[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return hipErrorUnknown;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    int max_wgs = max_wgs_dev[dev].load(std::memory_order_acquire);
+    if (max_wgs == 0) {
         hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<HD, NW, R, FP8>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    // persistent grid: as many workgroups as can be resident (LDS: two per CU), each loops over work items
-    static int max_wgs = 0;
-    if (max_wgs == 0) {
-        int dev = 0, per_cu = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return hipErrorUnknown;
+        int per_cu = 0, cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return hipErrorUnknown;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<HD, NW, R, FP8>, NW * 64, lds) != hipSuccess || per_cu < 1)
             per_cu = 1;
-        max_wgs = prop.multiProcessorCount * per_cu;
+        max_wgs = cus * per_cu;
+        max_wgs_dev[dev].store(max_wgs, std::memory_order_release);
     }
     const int n_items = (gv.n_groups > 0 ? gv.n_groups : mv.n_seq) * pv.n_kv;
-    const int env_wgs = attn_wgs_override();
-    const int grid = std::min(n_items, env_wgs > 0 ? env_wgs : max_wgs);
+    const int grid = std::min(n_items, max_wgs);
     attn_mfma_kernel<HD, NW, R, FP8><<<dim3((unsigned)grid), NW * 64, lds, st>>>(q, kv_new, o, mv, pv, layer, n_q, mv.cu, mv.prefix_len, mv.page_table,
                                                                              mv.new_cu, pv.scales, last_only, gv.n_groups, gv.p0,
                                                                              gv.blk_cu, gv.sub_cu, gv.blk_seq, gv.blk_row0, gv.sub_page,
@@ -644,25 +637,15 @@ hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, co
 #define HR_ATTN_CASE(HD, NW, R)                                                                       \
     return fp8 ? launch_one<HD, NW, R, true>(qh, kvn, oh, mv, pv, layer, n_q, last_only ? 1 : 0, gv, st)   \
                : launch_one<HD, NW, R, false>(qh, kvn, oh, mv, pv, layer, n_q, last_only ? 1 : 0, gv, st)
-    static int var = -1;
-    if (var < 0) {
-        const char* e = getenv("HR_ATTN_VARIANT");
-        var = e ? atoi(e) : 0;
-    }
-    const bool wide = var == 1;
     if (pv.d == 64) {
         if (rows <= 128) { HR_ATTN_CASE(64, 4, 1); }
-        if (rows <= 256) {
-            if (wide) { HR_ATTN_CASE(64, 8, 1); }
-            HR_ATTN_CASE(64, 4, 2);
-        }
+        if (rows <= 256) { HR_ATTN_CASE(64, 4, 2); }
         HR_ATTN_CASE(64, 8, 2);
     } else {
         if (rows <= 128) { HR_ATTN_CASE(128, 4, 1); }
         if (rows <= 256) {
             // two row blocks per wave at d = 128 need more registers than two waves per SIMD leave (measured at 256 rows,
             // fp8 pool: 2.1 ms with 4 waves x 2 blocks, 1.3 ms with 8 waves x 1 block)
-            if (var == 2) { HR_ATTN_CASE(128, 4, 2); }
             HR_ATTN_CASE(128, 8, 1);
         }
         HR_ATTN_CASE(128, 8, 2);

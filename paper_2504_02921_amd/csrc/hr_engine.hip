@@ -46,6 +46,8 @@ using namespace hr;
 
 constexpr int64_t kGenericMaxKeys = 15000;     // scores of one row live in LDS in the generic attention
 constexpr int64_t kMfmaMaxKeys = 1 << 20;
+constexpr int64_t kChunkedMaxKeys = 1 << 15;   // longest sequence of the chunked passes (no-reuse pass, document prefill): bounds
+                                               // the self page table, which has one row per 32- or 64-token chunk
 constexpr int64_t kSplitMinTokens = 8192;      // query tokens from which a scoring call is cut in two halves
 constexpr double kSplitMaxFill = 0.85;         // ... when the N = hidden GEMMs' tiles fill less than this share of their rounds
 constexpr size_t kSplitSlackBytes = (size_t)1 << 20;   // what two carvings of a workspace may need beyond one (alignment gaps,
@@ -651,7 +653,7 @@ size_t hr_rerank_full_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_
         // is at most as long as the longest sequence, itself at most total_tokens
         const int ch = full_chunk(m);
         const int64_t n_chunks = total_tokens / ch + n_pairs;
-        const int64_t stride = std::max<int64_t>(1, std::min<int64_t>(total_tokens, kGenericMaxKeys) / hr::kPageTokens);
+        const int64_t stride = std::max<int64_t>(1, std::min<int64_t>(total_tokens, kChunkedMaxKeys) / hr::kPageTokens);
         return hr::make_workspace(m->cfg, n_chunks, total_tokens, stride, false, n_pairs, 0).total;
     }
     return hr::make_workspace(m->cfg, n_pairs, total_tokens, 0, !m->mfma_gemm).total;
@@ -669,7 +671,7 @@ int hr_rerank_score_full(hr_model* m, int32_t n_pairs, const int32_t* doc_tokens
     for (int32_t p = 0; p < n_pairs; ++p) {
         if (doc_lens[p] < 0 || query_lens[p] <= 0) return HR_ERR_LEN_RANGE;
         int64_t n = (int64_t)doc_lens[p] + query_lens[p];
-        if (n > kGenericMaxKeys) return HR_ERR_LEN_RANGE;
+        if (n > (chunked_ok(m) ? kChunkedMaxKeys : kGenericMaxKeys)) return HR_ERR_LEN_RANGE;
         max_len = std::max(max_len, (int)n);
         T += n;
         Td += doc_lens[p];
@@ -725,7 +727,7 @@ size_t hr_doc_prefill_workspace_bytes(const hr_model* m, int32_t n_docs, int64_t
     if (!m || n_docs < 0 || total_tokens < 0 || !chunked_ok(m)) return 0;
     const int ch = full_chunk(m);
     const int64_t n_chunks = total_tokens / ch + n_docs;
-    const int64_t stride = std::max<int64_t>(1, std::min<int64_t>(total_tokens, kGenericMaxKeys) / hr::kPageTokens);
+    const int64_t stride = std::max<int64_t>(1, std::min<int64_t>(total_tokens, kChunkedMaxKeys) / hr::kPageTokens);
     const int64_t pages = total_tokens / hr::kPageTokens + n_docs;
     return hr::make_workspace(m->cfg, n_chunks, total_tokens, stride, false, n_docs, 2 * pages).total;
 }
@@ -744,7 +746,7 @@ int hr_doc_prefill(hr_model* m, hr_pool* pool, int32_t n_docs, const int32_t* do
     int max_len = 0;
     std::vector<int32_t> dst;          // flat list of target pages, document after document
     for (int32_t d = 0; d < n_docs; ++d) {
-        if (doc_lens[d] <= 0 || doc_lens[d] > kGenericMaxKeys) return HR_ERR_LEN_RANGE;
+        if (doc_lens[d] <= 0 || doc_lens[d] > kChunkedMaxKeys) return HR_ERR_LEN_RANGE;
         const int64_t np = ((int64_t)doc_lens[d] + hr::kPageTokens - 1) / hr::kPageTokens;
         if (np > pt_stride) return HR_ERR_TABLE_SHORT;
         int rc = hr::pool_check_write(pool, doc_lens[d], page_table + (size_t)d * pt_stride);

@@ -20,6 +20,7 @@
 // measured the same).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdlib>
 #include <type_traits>
 
@@ -606,7 +607,24 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_ring_kernel(GemmArgs a) {
 }
 
 int cu_count();
-int tuning_variant();
+
+// Per-device "done once" flags and cached values: a host thread may drive any device, and different model handles may
+// be used from different threads.
+constexpr int kMaxDevices = 64;
+inline int current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    return dev;
+}
+// hipFuncSetAttribute(max dynamic LDS) once per kernel instantiation and device
+template <typename K>
+hipError_t allow_dynamic_lds(K kernel, size_t lds, std::atomic<uint64_t>& done) {
+    const uint64_t bit = (uint64_t)1 << current_device();
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
 
 template <int EPI, int BM, int BN, int WM, int WN, int HB>
 hipError_t launch_tile(const GemmArgs& a, hipStream_t st) {
@@ -614,20 +632,15 @@ hipError_t launch_tile(const GemmArgs& a, hipStream_t st) {
     const int n_tiles = tiles_m * tiles_n;
     const int per_xcd = (n_tiles + kXcds - 1) / kXcds;
     int grid = per_xcd * kXcds;
-    if (EPI == EPI_SWIGLU && BM <= 256 && tuning_variant() != 5) {
+    if (EPI == EPI_SWIGLU && BM <= 256) {
         // persistent launch: as many workgroups as are resident at once (one big or two small tiles per CU), a multiple
         // of the XCD count so that the walk blockIdx.x + k * gridDim.x stays on its XCD
         const int resident = cu_count() * (BM >= 256 ? 1 : 2) / kXcds * kXcds;
         if (resident >= kXcds && grid > resident) grid = resident;
     }
     const size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(half_t);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, BM, BN, WM, WN, HB>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> attr_done{0};
+    if (hipError_t e = allow_dynamic_lds(gemm_mfma_kernel<EPI, BM, BN, WM, WN, HB>, lds, attr_done); e != hipSuccess) return e;
     gemm_mfma_kernel<EPI, BM, BN, WM, WN, HB><<<dim3((unsigned)grid), WM * WN * 64, lds, st>>>(a);
     return hipGetLastError();
 }
@@ -637,33 +650,19 @@ hipError_t launch_ring(const GemmArgs& a, hipStream_t st) {
     const int tiles_m = (int)((a.M + BM - 1) / BM), tiles_n = (a.N + BN - 1) / BN;
     const int grid = (tiles_m * tiles_n + kXcds - 1) / kXcds * kXcds;
     const size_t lds = (size_t)NS * (BM + BN) * BK * sizeof(half_t);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_ring_kernel<EPI, BM, BN, WM, WN, HB, NS>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static std::atomic<uint64_t> attr_done{0};
+    if (hipError_t e = allow_dynamic_lds(gemm_ring_kernel<EPI, BM, BN, WM, WN, HB, NS>, lds, attr_done); e != hipSuccess) return e;
     gemm_ring_kernel<EPI, BM, BN, WM, WN, HB, NS><<<dim3((unsigned)grid), WM * WN * 64, lds, st>>>(a);
     return hipGetLastError();
 }
 
-int tuning_variant() {
-    static int v = -2;
-    if (v == -2) {
-        const char* e = getenv("HR_GEMM_VARIANT");     // tuning runs only: force one tile shape
-        v = e ? atoi(e) : -1;
-    }
-    return v;
-}
-
 int cu_count() {
-    static int n = 0;
+    static std::atomic<int> cache[kMaxDevices];
+    const int dev = current_device();
+    int n = cache[dev].load(std::memory_order_relaxed);
     if (n == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
-        if (n <= 0) n = 256;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cache[dev].store(n, std::memory_order_relaxed);
     }
     return n;
 }
@@ -686,13 +685,12 @@ bool gemm_mfma_supported(const hr_model_cfg& c) {
 hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st) {
     if (a.M == 0) return hipSuccess;
     if (a.K % BK != 0) return hipErrorInvalidValue;
-    const int var = tuning_variant();
     const bool wide_head = epi == EPI_QKV_ROPE && a.d == 128;       // a wave must span a whole 128-wide head
     // Few rows: when even 128 x 128 tiles do not give every CU one, the ring variants take over.  64-row tiles double
     // the tile count; they pay when that still fits one round of the chip (a ring workgroup has its CU to itself),
     // otherwise 128-row tiles with fewer, larger k-steps do (modelled as rounds x bytes per k-tile).
     const int64_t tiles128 = ((a.M + 127) / 128) * ((a.N + (wide_head ? 255 : 127)) / (wide_head ? 256 : 128));
-    if (var < 0 && tiles128 < cu_count()) {
+    if (tiles128 < cu_count()) {
         const int64_t cus = cu_count();
         const int64_t t64 = ((a.M + 63) / 64) * ((a.N + (wide_head ? 255 : 127)) / (wide_head ? 256 : 128));
         if (wide_head) return launch_ring<EPI_QKV_ROPE, 64, 256, 2, 2, 2, 3>(a, st);
@@ -709,10 +707,8 @@ hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st)
     }
     // the tall tile: residual-add launches, and gate/up launches with a long k loop (not persistent: at K = 896 the
     // start-up round trip per tile costs more than the shape saves: 8.8 against 8.0 ms per step at the 0.5B shape)
-    const bool tall_ok = epi == EPI_RESID_ADD || (epi == EPI_SWIGLU && a.K >= 2048 && var != 8);
-    TileChoice tile = choose_gemm_tile(a.M, a.N, wide_head ? 256 : 128, tall_ok, cu_count());
-    if (var == 0) tile = TILE_BIG;
-    if (var == 2) tile = TILE_SMALL;
+    const bool tall_ok = epi == EPI_RESID_ADD || (epi == EPI_SWIGLU && a.K >= 2048);
+    const TileChoice tile = choose_gemm_tile(a.M, a.N, wide_head ? 256 : 128, tall_ok, cu_count());
     if (tile == TILE_TALL)
         return epi == EPI_RESID_ADD ? launch_tile<EPI_RESID_ADD, 320, 256, 2, 4, 1>(a, st) : launch_tile<EPI_SWIGLU, 320, 256, 2, 4, 1>(a, st);
     const bool big = tile == TILE_BIG;
