@@ -19,12 +19,14 @@
  *     Calls that take a stream enqueue work and return without waiting.
  *   - A model handle carries per-call host state (a pinned staging buffer, an event, a second stream): calls on
  *     one handle must not overlap in host time; different handles, and pools, are independent.  The library
- *     allocates no device memory, but it owns that small pinned host buffer and, once a scoring call has been
- *     cut in two halves, one stream and three events per model handle (released by hr_model_destroy).
+ *     allocates no device memory, but it owns that small pinned host buffer (1 MiB from hr_weights_load on, grown
+ *     when a call's metadata needs more) and, once a scoring call has been cut in two halves, one stream and three
+ *     events per model handle (released by hr_model_destroy).
  *   - Calls that upload per-call metadata (scoring, prefill) wait on the host for the previous upload of the same
  *     handle and copy from its staging buffer: they are not meant to be recorded into a HIP graph.
- *   - Every call returns HR_OK (0) or a negative hr_status.  On error nothing
- *     is enqueued and no library state changes.  Nothing throws or aborts.
+ *   - Every call returns HR_OK (0) or a negative hr_status.  Every argument check happens before anything is enqueued
+ *     or any library state changes; only HR_ERR_DEVICE (a HIP call failed mid-way) can leave part of a call's work on the
+ *     stream, and the outputs of that call are then undefined.  Nothing throws or aborts.
  *   - All matrices are row-major [out][in]; activations use the model dtype
  *     (HR_F32 or HR_BF16); norm gains and scores are fp32.
  *   - A page holds 16 consecutive tokens of one document for one (layer,
@@ -241,6 +243,25 @@ int hr_rerank_score(hr_model* model, const hr_pool* pool, int32_t n_pairs,
                     const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
                     const int32_t* query_tokens, const int32_t* query_lens,
                     void* workspace_dev, size_t workspace_bytes, float* scores_dev, void* stream);
+
+/* hr_rerank_score for callers that cannot allocate or hand over a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, validation, kernels and scores (bit for bit) as
+ * hr_rerank_score, except that the workspace is a file-scope device array inside the library
+ * (hr_rerank_static_scratch_bytes() = 64 MiB; every GPU the library runs on holds its own copy until the process ends)
+ * and the per-call metadata goes through the pinned staging buffer the model handle got at hr_weights_load (1 MiB).
+ * The call allocates nothing: no device or pinned memory, no streams, no events; it always runs in one piece on `stream`,
+ * and per-kernel timing (hr_profile_enable) is off for its duration.
+ *   HR_ERR_WORKSPACE_SMALL  the call would need more scratch than the array holds, or more metadata than the staging
+ *                           buffer holds (hr_last_error says which and how much); nothing is enqueued.  One query with
+ *                           20 candidates of 32 query tokens needs 15 MiB at the 0.5B shape and 46 MiB at the 8B shape.
+ * The array is shared by every static call on that GPU, whatever the model handle, and keeps the last call's contents
+ * (what must start at zero is cleared by the call itself): static calls that overlap in time on one GPU race with each
+ * other, also when issued on different streams.  Order them on one stream or with events. */
+size_t hr_rerank_static_scratch_bytes(void);
+int hr_rerank_score_static(hr_model* model, const hr_pool* pool, int32_t n_pairs,
+                           const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
+                           const int32_t* query_tokens, const int32_t* query_lens,
+                           float* scores_dev, void* stream);
 
 /* 1: scoring calls use the caller's stream only; 2 (the default): large calls are cut in two halves that run on
  * two streams, so that one half's kernels fill the compute units that the last, partly filled round of the other

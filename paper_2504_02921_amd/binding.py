@@ -57,7 +57,8 @@ EXPORTS = [
     "hr_status_str", "hr_last_error", "hr_kv_pool_bytes", "hr_kv_pool_create", "hr_kv_pool_destroy", "hr_kv_pool_free_pages",
     "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_read", "hr_doc_kv_free", "hr_kv_page_record_bytes", "hr_kv_pages_out",
     "hr_kv_pages_in", "hr_kv_page_record4_bytes", "hr_kv_pages_out4", "hr_kv_pages_in4", "hr_weights_pack_bytes", "hr_weights_load",
-    "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_set_streams", "hr_rerank_parts", "hr_rerank_validate",
+    "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_static_scratch_bytes",
+    "hr_rerank_score_static", "hr_rerank_set_streams", "hr_rerank_parts", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
     "hr_rerank_topk", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
 ]
@@ -100,6 +101,9 @@ def _load() -> C.CDLL:
         "hr_rerank_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int32, C.c_int64, C.c_int32]),
         "hr_rerank_score": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, i32p, C.c_int32, i32p, i32p, i32p,
                                       C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+        "hr_rerank_static_scratch_bytes": (C.c_size_t, []),
+        "hr_rerank_score_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, i32p, C.c_int32, i32p, i32p, i32p,
+                                             C.c_void_p, C.c_void_p]),
         "hr_rerank_set_streams": (C.c_int, [C.c_void_p, C.c_int]),
         "hr_rerank_parts": (C.c_int, [C.c_void_p, C.c_int64]),
         "hr_rerank_validate": (C.c_int, [C.POINTER(hr_model_cfg), C.c_void_p, C.c_int32, i32p, C.c_int32, i32p, i32p, i32p]),
@@ -389,6 +393,20 @@ class Model:
                                  C.c_void_p(ws.data_ptr()), ws.numel(), C.c_void_p(scores.data_ptr()), _stream_ptr(stream))
         check(st, "hr_rerank_score")
         return scores[:P]
+
+    def score_static(self, pool: KVPool, page_table, doc_lens, query_tokens, query_lens, out, stream=None):
+        """hr_rerank_score_static: the workspace is the library's own static device array; `out` is the caller's
+        fp32 device tensor of at least len(doc_lens) scores (nothing is allocated here either)."""
+        pt = _i32(page_table)
+        if pt.ndim == 1:
+            pt = pt.reshape(len(doc_lens), -1)
+        dl, qt, ql = _i32(doc_lens), _i32(query_tokens), _i32(query_lens)
+        P = len(dl)
+        stride = pt.shape[1] if pt.ndim == 2 else 0
+        st = lib.hr_rerank_score_static(self.handle, pool.handle, P, _i32p(pt), stride, _i32p(dl), _i32p(qt), _i32p(ql),
+                                        C.c_void_p(out.data_ptr()), _stream_ptr(stream))
+        check(st, "hr_rerank_score_static")
+        return out[:P]
 
     def parts(self, total_q_tokens: int) -> int:
         return int(lib.hr_rerank_parts(self.handle, int(total_q_tokens)))

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -38,7 +39,15 @@ struct hr_model {
     size_t stage_ints = 0;
     hipEvent_t stage_ev = nullptr;
     bool stage_pending = false;
+    int device = -1;                      // the HIP device that was current when the weights were loaded
 };
+
+// Scratch of hr_rerank_score_static: the workspace of a scoring call as a file-scope device array, for callers that
+// cannot hand over (or allocate) a workspace.  Every GPU the library runs on holds its own copy until the process ends.
+// In host code the array's name is only a stand-in for the symbol: the device address comes from hipGetSymbolAddress,
+// once per device, and that pointer is what kernels, copies and fills get.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -74,21 +83,49 @@ bool use_mfma_attn(const hr_model* m, int kv_dtype, int max_new_len) {
     return !m->force_generic && m->mfma_gemm && attn_mfma_supported(m->cfg, kv_dtype, max_new_len);
 }
 
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+char* g_scratch_ptr[kMaxDevices] = {};      // device address of g_static_scratch, per HIP device
+
+// Address of the static scratch on the current device (looked up on first use per device, with that device current).
+int static_scratch_ptr(char** out, int* dev_out = nullptr) {
+    int dev = -1;
+    HR_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return HR_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HR_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch)));
+        if (!p || (uintptr_t)p % kAlign != 0) return HR_ERR_DEVICE;
+        g_scratch_ptr[dev] = (char*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    if (dev_out) *dev_out = dev;
+    return HR_OK;
+}
+
 const void* layer_w(const hr_model* m, int l, size_t off) {
     size_t esz = dtype_size(m->cfg.dtype);
     return m->pack_base + ((size_t)l * m->pack.layer_elems + off) * esz;
 }
 
-int stage_reserve(hr_model* m, size_t ints) {
+constexpr size_t kStageMinInts = (size_t)1 << 18;      // staging a model handle starts with (1 MiB of pinned host memory)
+
+int stage_reserve(hr_model* m, size_t ints, bool may_grow = true) {
     if (m->stage_pending) {
         HR_HIP(hipEventSynchronize(m->stage_ev));
         m->stage_pending = false;
     }
     if (ints > m->stage_ints) {
+        if (!may_grow) {
+            snprintf(g_last_error, sizeof(g_last_error), "metadata of this call (%zu bytes) exceeds the handle's staging buffer (%zu bytes)",
+                     ints * sizeof(int32_t), m->stage_ints * sizeof(int32_t));
+            return HR_ERR_WORKSPACE_SMALL;
+        }
         if (m->stage) (void)hipHostFree(m->stage);
         m->stage = nullptr;
         m->stage_ints = 0;
-        size_t want = std::max(ints, (size_t)1 << 16);
+        size_t want = std::max(ints, kStageMinInts);
         HR_HIP(hipHostMalloc((void**)&m->stage, want * sizeof(int32_t), hipHostMallocDefault));
         m->stage_ints = want;
     }
@@ -341,6 +378,18 @@ int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* w, void* pack
     const char* ns = getenv("HR_STREAMS");               // "1": scoring calls stay on the caller's stream (profiling runs)
     if (ns && ns[0] == '1') m->n_streams = 1;
 
+    // set-up that later calls must not have to do: the address of the static scratch on this device, the pinned
+    // staging buffer for per-call metadata and its event
+    {
+        char* scratch = nullptr;
+        int rc = static_scratch_ptr(&scratch, &m->device);
+        if (rc == HR_OK) rc = stage_reserve(m, kStageMinInts);
+        if (rc != HR_OK) {
+            hr_model_destroy(m);
+            return rc;
+        }
+    }
+
     hipStream_t st = (hipStream_t)stream;
     const int dt = cfg->dtype;
     const size_t esz = hr::dtype_size(dt);
@@ -358,7 +407,7 @@ int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* w, void* pack
         if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wd[l], slab + pl.wd * esz, H, F, H, 1, 0, st);
         if (e != hipSuccess) {
             note_hip_error(e, "weight packing kernels");
-            delete m;
+            hr_model_destroy(m);
             return HR_ERR_DEVICE;
         }
     }
@@ -529,6 +578,23 @@ static int run_score_part(hr_model* m, const hr_pool* pool, const ScorePart& par
                       part.gv.n_groups > 0 ? &part.gv : nullptr, after_qkv0);
 }
 
+// A scoring call (already validated) in one piece on `st`, with the workspace at `wsb`.
+static int score_one_piece(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride,
+                           const int32_t* doc_lens, const int32_t* query_tokens, const int32_t* query_lens, int64_t T, bool mfma_attn,
+                           int max_q, const hr::Workspace& ws, int64_t grp_ints, char* wsb, float* scores_dev, hipStream_t st,
+                           bool staging_may_grow) {
+    const hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, pt_stride, -1, 0, grp_ints);
+    int rc = stage_reserve(m, ml.total, staging_may_grow);
+    if (rc != HR_OK) return rc;
+    ScorePart part;
+    rc = prepare_score_part(m, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens, T, mfma_attn, ws, ml, grp_ints,
+                            m->stage, wsb, st, &part);
+    HR_HIP(hipEventRecord(m->stage_ev, st));
+    m->stage_pending = true;
+    if (rc != HR_OK) return rc;
+    return run_score_part(m, pool, part, ws, wsb, max_q, scores_dev, st);
+}
+
 int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride,
                     const int32_t* doc_lens, const int32_t* query_tokens, const int32_t* query_lens, void* workspace_dev,
                     size_t workspace_bytes, float* scores_dev, void* stream) {
@@ -612,16 +678,44 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
             return rc_a != HR_OK ? rc_a : rc_b;
         }
     }
-    const hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, pt_stride, -1, 0, grp_ints);
-    rc = stage_reserve(m, ml.total);
+    return score_one_piece(m, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens, T, mfma_attn, max_q, ws, grp_ints,
+                           wsb, scores_dev, st, true);
+}
+
+size_t hr_rerank_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int hr_rerank_score_static(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride,
+                           const int32_t* doc_lens, const int32_t* query_tokens, const int32_t* query_lens, float* scores_dev,
+                           void* stream) {
+    if (!m || !pool) return HR_ERR_INVALID_ARG;
+    int max_q = 0;
+    if (n_pairs > 0 && query_lens)
+        for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
+    const bool mfma_attn = use_mfma_attn(m, pool->cfg.kv_dtype, max_q);
+    int64_t T = 0;
+    int rc = hr::score_check_args(m->cfg, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens,
+                                  mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys, &T);
     if (rc != HR_OK) return rc;
-    ScorePart part;
-    rc = prepare_score_part(m, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens, T, mfma_attn, ws, ml, grp_ints,
-                            m->stage, wsb, st, &part);
-    HR_HIP(hipEventRecord(m->stage_ev, st));
-    m->stage_pending = true;
+    if (n_pairs == 0) return HR_OK;
+    if (!scores_dev) return HR_ERR_INVALID_ARG;
+    const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
+    const int64_t grp_ints = (int64_t)hr::group_plan_ints_bound(n_pairs, T, g);
+    const hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints);
+    if (ws.total > kStaticScratchBytes) {
+        snprintf(g_last_error, sizeof(g_last_error), "hr_rerank_score_static: this call needs %zu bytes of scratch, the static array holds %zu",
+                 ws.total, kStaticScratchBytes);
+        return HR_ERR_WORKSPACE_SMALL;
+    }
+    char* scratch = nullptr;                    // this device's copy of the array (a table lookup after the first call)
+    rc = static_scratch_ptr(&scratch);
     if (rc != HR_OK) return rc;
-    return run_score_part(m, pool, part, ws, wsb, max_q, scores_dev, st);
+    // one piece on the caller's stream, no timing events (their pool grows on demand), staging as it was set up at load
+    const bool prof = m->prof_on;
+    m->prof_on = false;
+    rc = score_one_piece(m, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens, T, mfma_attn, max_q, ws, grp_ints,
+                         scratch, scores_dev, (hipStream_t)stream, false);
+    m->prof_on = prof;
+    return rc;
 }
 
 int hr_rerank_parts(const hr_model* m, int64_t total_q_tokens) {
