@@ -247,13 +247,13 @@ int hr_rerank_score(hr_model* model, const hr_pool* pool, int32_t n_pairs,
 /* hr_rerank_score for callers that cannot allocate or hand over a workspace: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, validation, kernels and scores (bit for bit) as
  * hr_rerank_score, except that the workspace is a file-scope device array inside the library
- * (hr_rerank_static_scratch_bytes() = 64 MiB; every GPU the library runs on holds its own copy until the process ends)
+ * (hr_rerank_static_scratch_bytes() = 128 MiB; every GPU the library runs on holds its own copy until the process ends)
  * and the per-call metadata goes through the pinned staging buffer the model handle got at hr_weights_load (1 MiB).
  * The call allocates nothing: no device or pinned memory, no streams, no events; it always runs in one piece on `stream`,
  * and per-kernel timing (hr_profile_enable) is off for its duration.
  *   HR_ERR_WORKSPACE_SMALL  the call would need more scratch than the array holds, or more metadata than the staging
  *                           buffer holds (hr_last_error says which and how much); nothing is enqueued.  One query with
- *                           20 candidates of 32 query tokens needs 15 MiB at the 0.5B shape and 46 MiB at the 8B shape.
+ *                           20 candidates of 32 query tokens needs about 13 MiB at the 0.5B shape and 85 MiB at the 8B shape.
  * The array is shared by every static call on that GPU, whatever the model handle, and keeps the last call's contents
  * (what must start at zero is cleared by the call itself): static calls that overlap in time on one GPU race with each
  * other, also when issued on different streams.  Order them on one stream or with events. */
@@ -262,6 +262,19 @@ int hr_rerank_score_static(hr_model* model, const hr_pool* pool, int32_t n_pairs
                            const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
                            const int32_t* query_tokens, const int32_t* query_lens,
                            float* scores_dev, void* stream);
+
+/* Precision of the scoring pass on the MFMA kernels (16-bit models).  Operands of the matrix instructions are IEEE halves
+ * (11 significant bits): weights and cached document K/V are exact as halves, but every activation that feeds an MFMA is
+ * rounded once per layer, and a deep, wide network amplifies the first layers' roundings most (Section 3.3 calls the
+ * cached pass lossless; the arithmetic's own rounding is what is left).  The first `n_layers` layers of hr_rerank_score
+ * therefore can run with split operands: each such activation is carried as a pair of halves hi + lo (22 bits) and every
+ * product with a lo term is one more MFMA chain into the same fp32 accumulator, about twice the work of those layers.
+ *   n_layers   0 .. model layers, or -1 for the default: 2 when layers x hidden >= 65536 (the 8B shape), else 0
+ * Changes hr_rerank_workspace_bytes (ask again after setting it).  hr_rerank_score_full and hr_doc_prefill always run
+ * with plain 16-bit operands.  HR_ERR_UNSUPPORTED_SHAPE if n_layers > 0 on a model that runs the generic kernels
+ * (those compute in fp32 throughout). */
+int hr_model_set_precise_layers(hr_model* model, int n_layers);
+int hr_model_precise_layers(const hr_model* model);
 
 /* 1: scoring calls use the caller's stream only; 2 (the default): large calls are cut in two halves that run on
  * two streams, so that one half's kernels fill the compute units that the last, partly filled round of the other
@@ -354,7 +367,9 @@ const char* hr_gemm_path(const hr_model* model);
  *   HR_FORCE_GENERIC=1      every step on the generic fp32-arithmetic kernels
  *   HR_NO_LAST_SHORTCUT=1   the last layer runs on every token instead of each pair's last one
  *   HR_NO_DOC_GROUPS=1      pairs that share a document are not batched into one attention work item
- *   HR_STREAMS=1            the initial value of hr_rerank_set_streams is 1 */
+ *   HR_STREAMS=1            the initial value of hr_rerank_set_streams is 1
+ * and one that does change results (within the tolerance): HR_PRECISE_LAYERS=n, the initial value of
+ * hr_model_set_precise_layers. */
 
 #ifdef __cplusplus
 }

@@ -58,7 +58,7 @@ EXPORTS = [
     "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_read", "hr_doc_kv_free", "hr_kv_page_record_bytes", "hr_kv_pages_out",
     "hr_kv_pages_in", "hr_kv_page_record4_bytes", "hr_kv_pages_out4", "hr_kv_pages_in4", "hr_weights_pack_bytes", "hr_weights_load",
     "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_static_scratch_bytes",
-    "hr_rerank_score_static", "hr_rerank_set_streams", "hr_rerank_parts", "hr_rerank_validate",
+    "hr_rerank_score_static", "hr_model_set_precise_layers", "hr_model_precise_layers", "hr_rerank_set_streams", "hr_rerank_parts", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
     "hr_rerank_topk", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
 ]
@@ -104,6 +104,8 @@ def _load() -> C.CDLL:
         "hr_rerank_static_scratch_bytes": (C.c_size_t, []),
         "hr_rerank_score_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, i32p, C.c_int32, i32p, i32p, i32p,
                                              C.c_void_p, C.c_void_p]),
+        "hr_model_set_precise_layers": (C.c_int, [C.c_void_p, C.c_int]),
+        "hr_model_precise_layers": (C.c_int, [C.c_void_p]),
         "hr_rerank_set_streams": (C.c_int, [C.c_void_p, C.c_int]),
         "hr_rerank_parts": (C.c_int, [C.c_void_p, C.c_int64]),
         "hr_rerank_validate": (C.c_int, [C.POINTER(hr_model_cfg), C.c_void_p, C.c_int32, i32p, C.c_int32, i32p, i32p, i32p]),
@@ -410,6 +412,12 @@ class Model:
 
     def parts(self, total_q_tokens: int) -> int:
         return int(lib.hr_rerank_parts(self.handle, int(total_q_tokens)))
+
+    def set_precise_layers(self, n: int) -> None:
+        check(lib.hr_model_set_precise_layers(self.handle, int(n)), "hr_model_set_precise_layers")
+
+    def precise_layers(self) -> int:
+        return int(lib.hr_model_precise_layers(self.handle))
 
     def set_streams(self, n: int) -> None:
         check(lib.hr_rerank_set_streams(self.handle, int(n)), "hr_rerank_set_streams")

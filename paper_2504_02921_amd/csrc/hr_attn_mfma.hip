@@ -105,8 +105,14 @@ struct ItemCtx {
     const char* layer_base;   // pool address of page 0 for this (layer, kv head)
 };
 
-template <int HD, int NW, int R, bool FP8>
-__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((HD == 64 && R == 1 && NW == 8) ? 4 : (HD * R <= 128 ? 2 : 1), 8))) attn_mfma_kernel(const half_t* __restrict__ q, const char* __restrict__ kv_new,
+// PREC: the 22-bit form of the first layers (split operands).  q and o are [T][hi n_q d | lo n_q d] halves (value = hi + lo),
+// the new tokens' K/V pages have a second buffer of lo pages (kv_new_lo, same arrangement), and the probabilities are
+// split in registers; every product that carries a hi x lo term is an extra MFMA chain into the same accumulator:
+//   S = K q_hi + K q_lo (+ K_lo q_hi for the pair's own keys),  O = V p_hi + V p_lo (+ V_lo p_hi likewise).
+// Document K/V from the pool are exact as stored.  One wave per SIMD (the extra fragments need the registers).
+template <int HD, int NW, int R, bool FP8, bool PREC>
+__global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PREC ? 1 : ((HD == 64 && R == 1 && NW == 8) ? 4 : (HD * R <= 128 ? 2 : 1)), 8))) attn_mfma_kernel(const half_t* __restrict__ q, const char* __restrict__ kv_new,
+                                                           const char* __restrict__ kv_new_lo,
                                                            half_t* __restrict__ o, MetaView mv, PoolView pv, int layer, int n_q,
                                                            const int32_t* __restrict__ m_cu, const int32_t* __restrict__ m_prefix,
                                                            const int32_t* __restrict__ m_pt, const int32_t* __restrict__ m_new_cu,
@@ -129,6 +135,8 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     extern __shared__ __attribute__((aligned(16))) char smem[];      // [2][kStageBytes] + scales + (fp8) expanded stage
     float* s_scale = (float*)(smem + 2 * kStageBytes);              // [2][PPS][2]  (fp8 only)
     char* hbuf = smem + 2 * kStageBytes + 2 * G::PPS * 2 * sizeof(float);   // fp8 only: the current stage as half pages
+    char* lobuf = hbuf + (FP8 ? 2 * kStageBytes : 0);                       // PREC only: [2][kStageBytes] lo pages of the pair's own keys
+    const int q_ld = (PREC ? 2 : 1) * n_q * HD;                             // row stride of q and o; lo halves n_q * HD further
 
     const int n_kv = pv.n_kv;
     const int g = n_q / n_kv;
@@ -234,8 +242,11 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             if (s < c.n_sub) {                                 // wave-uniform
                 int page, seq, key0;
                 sub_lookup(c, s, page, seq, key0);
-                const char* src = kv_new + ((size_t)(page + (slot & 1)) * n_kv + c.h) * GN::PAGE_BYTES + within;
-                __builtin_amdgcn_global_load_lds((gbl_ptr_t)src, (lds_ptr_t)(dst + ps * NT * 16), 16, 0, 0);
+                const size_t src_off = ((size_t)(page + (slot & 1)) * n_kv + c.h) * GN::PAGE_BYTES + within;
+                __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kv_new + src_off), (lds_ptr_t)(dst + ps * NT * 16), 16, 0, 0);
+                if constexpr (PREC)
+                    __builtin_amdgcn_global_load_lds((gbl_ptr_t)(kv_new_lo + src_off),
+                                                     (lds_ptr_t)(lobuf + buf * kStageBytes + wave_u * 1024 + ps * NT * 16), 16, 0, 0);
             }
         }
     };
@@ -266,6 +277,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     };
 
     halfx8 qf[R][KC];      // Q^T fragments (B operand), loaded once the first stage is on its way
+    halfx8 qf_lo[PREC ? R : 1][PREC ? KC : 1];      // PREC: their lo halves
     int row_i[R];          // query token index of the lane's row in block rb
     size_t row_off[R];     // element offset of that row in q / o
     bool row_ok[R];
@@ -301,7 +313,8 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
     // LDS latency hides under the softmax) -> softmax -> O^T += V^T P^T.
     // `sb` holds half pages; scaled_tag: they were expanded from fp8 codes and `sc` carries the pages' scales.
     // on[rb]: the wave's block rb takes part; nv[rb]: keys of the sub-tile that exist for it.
-    auto process = [&](auto scaled_tag, auto causal_tag, const char* sb, int st, const bool (&on)[R], const int (&nv)[R], const float* sc) {
+    auto process = [&](auto scaled_tag, auto causal_tag, const char* sb, int st, const bool (&on)[R], const int (&nv)[R], const float* sc,
+                       const char* sb_lo) {
         constexpr bool KV8 = decltype(scaled_tag)::value;
         constexpr bool CAUSAL = decltype(causal_tag)::value;
         using GG = GN;
@@ -323,6 +336,25 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                 if (!on[rb]) continue;                             // wave-uniform
 #pragma unroll
                 for (int kk = 0; kk < KC; ++kk) s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[kk], qf[rb][kk], s[rb], 0, 0, 0);
+                if constexpr (PREC) {
+#pragma unroll
+                    for (int kk = 0; kk < KC; ++kk) s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[kk], qf_lo[rb][kk], s[rb], 0, 0, 0);
+                }
+            }
+            if constexpr (PREC && CAUSAL) {
+                // the pair's own keys carry lo pages: K_lo q_hi
+                const char* kbl = sb_lo + (st * 2 + (ln >> 4)) * GG::PAGE_BYTES;
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk) {
+                    const int e = t * HD + (((2 * kk + hh) ^ k_swizzle(t, HD, GG::ESZ)) << 3);
+                    kf[kk] = *(const halfx8*)(kbl + e * 2);
+                }
+#pragma unroll
+                for (int rb = 0; rb < R; ++rb) {
+                    if (!on[rb]) continue;
+#pragma unroll
+                    for (int kk = 0; kk < KC; ++kk) s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[kk], qf[rb][kk], s[rb], 0, 0, 0);
+                }
             }
         }
         // fp8 pages: K scale goes into the softmax exponent (fp32).  The V scale is split into its power of two,
@@ -394,6 +426,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                     for (int r = 0; r < 16; ++r) oacc[rb][mb][r] *= alpha;
             }
             halfx8 pf[2];
+            halfx8 pl[PREC ? 2 : 1];          // PREC: what the rounding of P to half left out
 #pragma unroll
             for (int j = 0; j < 8; j += 2) {
                 const floatx2 a = {KV8 ? sr[j] * vs0 : sr[j], KV8 ? sr[j + 1] * vs0 : sr[j + 1]};
@@ -401,11 +434,33 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                 const halfx2 ha = __builtin_convertvector(a, halfx2), hb2 = __builtin_convertvector(b, halfx2);
                 pf[0][j] = ha[0]; pf[0][j + 1] = ha[1];
                 pf[1][j] = hb2[0]; pf[1][j + 1] = hb2[1];
+                if constexpr (PREC) {
+                    const floatx2 ra = a - __builtin_convertvector(ha, floatx2), rb2 = b - __builtin_convertvector(hb2, floatx2);
+                    const halfx2 la = __builtin_convertvector(ra, halfx2), lb = __builtin_convertvector(rb2, halfx2);
+                    pl[0][j] = la[0]; pl[0][j + 1] = la[1];
+                    pl[1][j] = lb[0]; pl[1][j + 1] = lb[1];
+                }
             }
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 oacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[mb][0], pf[0], oacc[rb][mb], 0, 0, 0);
                 oacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[mb][1], pf[1], oacc[rb][mb], 0, 0, 0);
+                if constexpr (PREC) {
+                    oacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[mb][0], pl[0], oacc[rb][mb], 0, 0, 0);
+                    oacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[mb][1], pl[1], oacc[rb][mb], 0, 0, 0);
+                }
+            }
+            if constexpr (PREC && CAUSAL) {
+                // V_lo p_hi for the pair's own keys (fragments read per block: this path is rare and short)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    const char* vbl = sb_lo + (st * 2 + s2) * GG::PAGE_BYTES + GG::BLOCK_BYTES;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        const halfx8 vl = *(const halfx8*)(vbl + ((hh * HD + mb * 32 + ln) * 8) * 2);
+                        oacc[rb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vl, pf[s2], oacc[rb][mb], 0, 0, 0);
+                    }
+                }
             }
         }
     };
@@ -431,9 +486,13 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
             const int rc = row < M ? row : M - 1;
             const int i = last_only ? qn - 1 : rc / g, a = last_only ? rc : rc - i * g;
             row_i[rb] = i;
-            row_off[rb] = ((size_t)(t0 + i) * n_q + c.h * g + a) * HD;
+            row_off[rb] = (size_t)(t0 + i) * q_ld + (size_t)(c.h * g + a) * HD;
 #pragma unroll
             for (int kk = 0; kk < KC; ++kk) qf[rb][kk] = *(const halfx8*)(q + row_off[rb] + (2 * kk + hh) * 8);
+            if constexpr (PREC) {
+#pragma unroll
+                for (int kk = 0; kk < KC; ++kk) qf_lo[rb][kk] = *(const halfx8*)(q + row_off[rb] + (size_t)n_q * HD + (2 * kk + hh) * 8);
+            }
         }
     };
 
@@ -503,7 +562,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                 int nv[R];
 #pragma unroll
                 for (int rb = 0; rb < R; ++rb) nv[rb] = cur.D - key0;
-                process(std::integral_constant<bool, FP8>{}, std::false_type{}, sb, st, blk_on, nv, sc);
+                process(std::integral_constant<bool, FP8>{}, std::false_type{}, sb, st, blk_on, nv, sc, nullptr);
             }
             if (tile + 1 < cur.n_tiles) scale_store(stage ^ 1);
             __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -537,7 +596,7 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                 if (!any) continue;                                // wave-uniform
 #pragma unroll
                 for (int rb = 0; rb < R; ++rb) row_i[rb] -= key0;
-                process(std::false_type{}, std::true_type{}, sb, st, on, nv, nullptr);
+                process(std::false_type{}, std::true_type{}, sb, st, on, nv, nullptr, lobuf + stage * kStageBytes);
 #pragma unroll
                 for (int rb = 0; rb < R; ++rb) row_i[rb] += key0;
             }
@@ -562,25 +621,46 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu((H
                 out_off[rb] = row_off[rb];
             }
             out_ok[rb] = row_ok[rb];
+            if constexpr (PREC) {
+                // [hi | lo] halves of the output row, stored right away (this variant does not defer its stores)
+                if (row_ok[rb]) {
+                    half_t* dst = o + out_off[rb];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+                    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4)
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            halfx4 hi, lo;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) opk[rb][mb][r4][e] = from_float<half_t>(oacc[rb][mb][r4 * 4 + e] * inv);
+                            for (int e = 0; e < 4; ++e) {
+                                const float v = oacc[rb][mb][r4 * 4 + e] * inv;
+                                hi[e] = from_float<half_t>(v);
+                                lo[e] = from_float<half_t>(v - (float)hi[e]);
+                            }
+                            *(halfx4*)(dst + mb * 32 + 8 * r4 + 4 * hh) = hi;
+                            *(halfx4*)(dst + (size_t)n_q * HD + mb * 32 + 8 * r4 + 4 * hh) = lo;
+                        }
+                }
+            } else {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) opk[rb][mb][r4][e] = from_float<half_t>(oacc[rb][mb][r4 * 4 + e] * inv);
+            }
         }
-        out_pending = true;
+        out_pending = !PREC;
         if (has_next) setup_rows(nxt);
         cur = nxt;
     }
     flush_out();
 }
 
-template <int HD, int NW, int R, bool FP8>
-hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const MetaView& mv, const PoolView& pv, int layer, int n_q,
-                      int last_only, const GroupView& gv, hipStream_t st) {
+template <int HD, int NW, int R, bool FP8, bool PREC>
+hipError_t launch_one(const half_t* q, const char* kv_new, const char* kv_new_lo, half_t* o, const MetaView& mv, const PoolView& pv,
+                      int layer, int n_q, int last_only, const GroupView& gv, hipStream_t st) {
     constexpr int SB = stage_bytes(FP8);
-    const size_t lds = 2 * SB + 2 * Geo<HD, FP8, SB>::PPS * 2 * sizeof(float) + (FP8 ? 2 * SB : 0);
+    const size_t lds = 2 * SB + 2 * Geo<HD, FP8, SB>::PPS * 2 * sizeof(float) + (FP8 ? 2 * SB : 0) + (PREC ? 2 * SB : 0);
     // once per kernel instantiation and device (a host thread may drive any device): the LDS attribute, and the size of
     // the persistent grid = as many workgroups as can be resident (LDS: two per CU), each looping over work items
     constexpr int kMaxDevices = 64;
@@ -590,22 +670,22 @@ hipError_t launch_one(const half_t* q, const char* kv_new, half_t* o, const Meta
     if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
     int max_wgs = max_wgs_dev[dev].load(std::memory_order_acquire);
     if (max_wgs == 0) {
-        hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<HD, NW, R, FP8>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<HD, NW, R, FP8, PREC>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)lds);
         if (e != hipSuccess) return e;
         int per_cu = 0, cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return hipErrorUnknown;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<HD, NW, R, FP8>, NW * 64, lds) != hipSuccess || per_cu < 1)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, attn_mfma_kernel<HD, NW, R, FP8, PREC>, NW * 64, lds) != hipSuccess || per_cu < 1)
             per_cu = 1;
         max_wgs = cus * per_cu;
         max_wgs_dev[dev].store(max_wgs, std::memory_order_release);
     }
     const int n_items = (gv.n_groups > 0 ? gv.n_groups : mv.n_seq) * pv.n_kv;
     const int grid = std::min(n_items, max_wgs);
-    attn_mfma_kernel<HD, NW, R, FP8><<<dim3((unsigned)grid), NW * 64, lds, st>>>(q, kv_new, o, mv, pv, layer, n_q, mv.cu, mv.prefix_len, mv.page_table,
-                                                                             mv.new_cu, pv.scales, last_only, gv.n_groups, gv.p0,
-                                                                             gv.blk_cu, gv.sub_cu, gv.blk_seq, gv.blk_row0, gv.sub_page,
-                                                                             gv.sub_seq, gv.sub_key0);
+    attn_mfma_kernel<HD, NW, R, FP8, PREC><<<dim3((unsigned)grid), NW * 64, lds, st>>>(q, kv_new, kv_new_lo, o, mv, pv, layer, n_q, mv.cu, mv.prefix_len,
+                                                                                   mv.page_table, mv.new_cu, pv.scales, last_only, gv.n_groups, gv.p0,
+                                                                                   gv.blk_cu, gv.sub_cu, gv.blk_seq, gv.blk_row0, gv.sub_page,
+                                                                                   gv.sub_seq, gv.sub_key0);
     return hipGetLastError();
 }
 
@@ -625,18 +705,34 @@ bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len) {
 }
 
 hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv, const PoolView& pv, int layer,
-                            int n_q, int max_q_len, hipStream_t st, bool last_only, const GroupView* groups) {
+                            int n_q, int max_q_len, hipStream_t st, bool last_only, const GroupView* groups, const void* kv_new_lo_pages) {
     if (mv.n_seq == 0) return hipSuccess;
     const GroupView gv = groups && !last_only ? *groups : GroupView{};
     const int rows = gv.n_groups > 0 ? gv.max_blocks * 32 : n_q / pv.n_kv * (last_only ? 1 : max_q_len);
     if (rows > kMaxRowsPerWg) return hipErrorInvalidValue;
     const half_t* qh = (const half_t*)q;
     const char* kvn = (const char*)kv_new_pages;
+    const char* kvl = (const char*)kv_new_lo_pages;
     half_t* oh = (half_t*)o;
     const bool fp8 = pv.kv_dtype == HR_FP8_E4M3;
-#define HR_ATTN_CASE(HD, NW, R)                                                                       \
-    return fp8 ? launch_one<HD, NW, R, true>(qh, kvn, oh, mv, pv, layer, n_q, last_only ? 1 : 0, gv, st)   \
-               : launch_one<HD, NW, R, false>(qh, kvn, oh, mv, pv, layer, n_q, last_only ? 1 : 0, gv, st)
+    if (kvl) {
+        // the 22-bit form: split q / o and lo pages of the new keys (see the kernel); one wave per SIMD, 8 waves
+        if (last_only) return hipErrorInvalidValue;
+#define HR_ATTN_PREC(HD, R)                                                                                 \
+    return fp8 ? launch_one<HD, 8, R, true, true>(qh, kvn, kvl, oh, mv, pv, layer, n_q, 0, gv, st)             \
+               : launch_one<HD, 8, R, false, true>(qh, kvn, kvl, oh, mv, pv, layer, n_q, 0, gv, st)
+        if (pv.d == 64) {
+            if (rows <= 256) { HR_ATTN_PREC(64, 1); }
+            HR_ATTN_PREC(64, 2);
+        } else {
+            if (rows <= 256) { HR_ATTN_PREC(128, 1); }
+            HR_ATTN_PREC(128, 2);
+        }
+#undef HR_ATTN_PREC
+    }
+#define HR_ATTN_CASE(HD, NW, R)                                                                                   \
+    return fp8 ? launch_one<HD, NW, R, true, false>(qh, kvn, nullptr, oh, mv, pv, layer, n_q, last_only ? 1 : 0, gv, st)   \
+               : launch_one<HD, NW, R, false, false>(qh, kvn, nullptr, oh, mv, pv, layer, n_q, last_only ? 1 : 0, gv, st)
     if (pv.d == 64) {
         if (rows <= 128) { HR_ATTN_CASE(64, 4, 1); }
         if (rows <= 256) { HR_ATTN_CASE(64, 4, 2); }

@@ -40,13 +40,14 @@ struct hr_model {
     hipEvent_t stage_ev = nullptr;
     bool stage_pending = false;
     int device = -1;                      // the HIP device that was current when the weights were loaded
+    int n_precise = 0;                    // leading layers of a scoring pass that run with split (hi + lo) operands
 };
 
 // Scratch of hr_rerank_score_static: the workspace of a scoring call as a file-scope device array, for callers that
 // cannot hand over (or allocate) a workspace.  Every GPU the library runs on holds its own copy until the process ends.
 // In host code the array's name is only a stand-in for the symbol: the device address comes from hipGetSymbolAddress,
 // once per device, and that pointer is what kernels, copies and fills get.
-constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+constexpr size_t kStaticScratchBytes = (size_t)128 << 20;
 static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
 
 namespace {
@@ -102,6 +103,16 @@ int static_scratch_ptr(char** out, int* dev_out = nullptr) {
     *out = g_scratch_ptr[dev];
     if (dev_out) *dev_out = dev;
     return HR_OK;
+}
+
+// How many leading layers of a scoring pass run with split (hi + lo) operands unless the caller says otherwise.
+// Measured on random-initialised models against the float64 definition: 16-bit operands leave a score error of rms
+// 0.002 at 24 layers x 896 hidden and 0.007 at 32 layers x 4096 hidden (scores ~ N(0, 1.8^2)), of which the first
+// layer's roundings alone account for 80 % and the first two for 94 % at the larger shape.  Two split layers bring that
+// shape to rms 0.002 for 1/16 more projection work; the smaller shape is left as it is.
+int default_precise_layers(const hr_model_cfg& c, bool mfma) {
+    if (!mfma) return 0;
+    return (int64_t)c.n_layers * c.hidden >= 65536 ? std::min(2, c.n_layers) : 0;
 }
 
 const void* layer_w(const hr_model* m, int l, size_t off) {
@@ -185,7 +196,7 @@ struct PrefillTarget {
 //   after_qkv0   if set, recorded on `st` behind the first layer's QKV projection
 int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaView& mv, const Workspace& ws, char* wsb,
                int max_keys, int max_new_len, float* scores, hipStream_t st, const PrefillTarget* fill = nullptr,
-               const GroupView* groups = nullptr, hipEvent_t after_qkv0 = nullptr) {
+               const GroupView* groups = nullptr, hipEvent_t after_qkv0 = nullptr, int n_precise = 0) {
     const hr_model_cfg& c = m->cfg;
     const int dt = c.dtype;
     const int H = c.hidden, d = c.head_dim, F = c.ffn;
@@ -220,8 +231,16 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
     if (self_prefix && !mfma_attn) return HR_ERR_UNSUPPORTED_SHAPE;
     // the shortened last layer needs one output row per sequence, the MFMA kernels, something to save (T > P), and
     // room for P fp32 rows in the q buffer
+    // Layers l < n_prec run with 22-bit operands: every activation that feeds an MFMA (the normalised rows, q, the new
+    // tokens' K/V, the probabilities, the attention output, the SwiGLU output) is carried as a pair of halves hi + lo and
+    // each product with a lo term is one more MFMA chain into the same fp32 accumulator; weights and cached document K/V
+    // are exact as stored.  A 16-bit operand's rounding in the first layers is what dominates the score error of a
+    // deep, wide model (the residual stream is still small there, and everything downstream amplifies it).
+    const int n_prec = (mfma_attn && m->mfma_gemm && pool && !fill && !self_prefix) ? std::min(n_precise, c.n_layers) : 0;
+    void* kvlo = wsb + ws.off_kvlo;
     const bool last_short = !m->no_last_short && mfma_attn && m->mfma_gemm && !fill && !self_prefix && mv.n_out == mv.n_seq &&
-                            T > mv.n_seq && (size_t)T * nq * dtype_size(dt) >= (size_t)mv.n_seq * H * sizeof(float) && H % 4 == 0;
+                            T > mv.n_seq && (size_t)T * nq * dtype_size(dt) >= (size_t)mv.n_seq * H * sizeof(float) && H % 4 == 0 &&
+                            n_prec < c.n_layers;
 
     // with the MFMA attention the new tokens' K/V are written straight into 16-slot pages (k and v regions together);
     // slots past a sequence's end are never written by any layer, so one clear per call keeps them finite
@@ -230,6 +249,29 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
     HR_TIMED(PC_EMBED, launch_embed(dt, m->embedding, mv, x, H, st));
     HR_TIMED(PC_EMBED, launch_rope_table(mv, rope, d, c.rope_base, st));
     for (int l = 0; l < c.n_layers; ++l) {
+        if (l < n_prec) {
+            HR_TIMED(PC_RMSNORM, launch_rmsnorm_split(x, m->norm1[l], y, T, H, c.rms_eps, st));
+            // the projection leaves fp32 rows (x += C on a cleared buffer); RoPE, the hi / lo split and the page scatter
+            // are a kernel of their own
+            HR_TIMED(PC_ELEMENTWISE, launch_fill_zero(f32, (size_t)T * nqkv * sizeof(float), st));
+            GemmArgs a{};
+            a.A = y; a.W = layer_w(m, l, m->pack.wqkv); a.M = T; a.N = nqkv; a.K = 2 * H; a.Kw = H; a.x = f32;
+            HR_TIMED(PC_GEMM_QKV, launch_gemm_mfma(EPI_RESID_ADD, a, st));
+            HR_TIMED(PC_ELEMENTWISE, launch_rope_pages_split(f32, rope, q, k, kvlo, mv.new_slot, T, c.n_q_heads, c.n_kv_heads, d, st));
+            if (l == 0 && after_qkv0) HR_HIP(hipEventRecord(after_qkv0, st));
+            HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, o, mv, pv, l, c.n_q_heads, max_new_len, st, false, groups, kvlo));
+            GemmArgs b{};
+            b.A = o; b.W = layer_w(m, l, m->pack.wo); b.M = T; b.N = H; b.K = 2 * nq; b.Kw = nq; b.x = x;
+            HR_TIMED(PC_GEMM_O, launch_gemm_mfma(EPI_RESID_ADD, b, st));
+            HR_TIMED(PC_RMSNORM, launch_rmsnorm_split(x, m->norm2[l], y, T, H, c.rms_eps, st));
+            GemmArgs gu{};
+            gu.A = y; gu.W = layer_w(m, l, m->pack.wgu); gu.M = T; gu.N = 2 * F; gu.K = 2 * H; gu.Kw = H; gu.out0 = mm; gu.split_out = 1;
+            HR_TIMED(PC_GEMM_GATE_UP, launch_gemm_mfma(EPI_SWIGLU, gu, st));
+            GemmArgs dn{};
+            dn.A = mm; dn.W = layer_w(m, l, m->pack.wd); dn.M = T; dn.N = H; dn.K = 2 * F; dn.Kw = F; dn.x = x;
+            HR_TIMED(PC_GEMM_DOWN, launch_gemm_mfma(EPI_RESID_ADD, dn, st));
+            continue;
+        }
         HR_TIMED(PC_RMSNORM, launch_rmsnorm(dt, x, m->norm1[l], y, T, H, c.rms_eps, st));
         if (m->mfma_gemm) {
             GemmArgs a{};
@@ -377,6 +419,9 @@ int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* w, void* pack
     m->no_doc_groups = ndg && ndg[0] == '1';
     const char* ns = getenv("HR_STREAMS");               // "1": scoring calls stay on the caller's stream (profiling runs)
     if (ns && ns[0] == '1') m->n_streams = 1;
+    m->n_precise = default_precise_layers(*cfg, m->mfma_gemm);
+    const char* npl = getenv("HR_PRECISE_LAYERS");       // A/B runs: overrides the default number of split-operand layers
+    if (npl && npl[0] >= '0' && npl[0] <= '9' && m->mfma_gemm) m->n_precise = std::min(atoi(npl), cfg->n_layers);
 
     // set-up that later calls must not have to do: the address of the static scratch on this device, the pinned
     // staging buffer for per-call metadata and its event
@@ -514,7 +559,8 @@ size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t tot
     if (!m || n_pairs < 0 || total_q_tokens < 0 || pt_stride < 0) return 0;
     // + room for the per-part alignment when the call runs as two halves (each with its own carving)
     return hr::make_workspace(m->cfg, n_pairs, total_q_tokens, pt_stride, !m->mfma_gemm, -1, 0,
-                              (int64_t)hr::group_plan_ints_bound(n_pairs, total_q_tokens, m->cfg.n_q_heads / m->cfg.n_kv_heads))
+                              (int64_t)hr::group_plan_ints_bound(n_pairs, total_q_tokens, m->cfg.n_q_heads / m->cfg.n_kv_heads),
+                              m->n_precise > 0)
                .total + (m->mfma_gemm ? kSplitSlackBytes : 0);
 }
 
@@ -575,7 +621,7 @@ static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_
 static int run_score_part(hr_model* m, const hr_pool* pool, const ScorePart& part, const hr::Workspace& ws, char* wsb, int max_q,
                           float* scores_dev, hipStream_t st, hipEvent_t after_qkv0 = nullptr) {
     return run_layers(m, pool, false, part.mv, ws, wsb, part.max_keys, max_q, scores_dev, st, nullptr,
-                      part.gv.n_groups > 0 ? &part.gv : nullptr, after_qkv0);
+                      part.gv.n_groups > 0 ? &part.gv : nullptr, after_qkv0, m->n_precise);
 }
 
 // A scoring call (already validated) in one piece on `st`, with the workspace at `wsb`.
@@ -612,7 +658,7 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     if ((uintptr_t)workspace_dev % hr::kAlign != 0) return HR_ERR_INVALID_ARG;
     const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     const int64_t grp_ints = (int64_t)hr::group_plan_ints_bound(n_pairs, T, g);
-    const hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints);
+    const hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints, m->n_precise > 0);
     if (workspace_bytes < ws.total) return HR_ERR_WORKSPACE_SMALL;
     hipStream_t st = (hipStream_t)stream;
     char* wsb = (char*)workspace_dev;
@@ -642,8 +688,8 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
         const int32_t n_b = n_pairs - n_a;
         const int64_t T_b = T - T_a;
         const int64_t gi_a = (int64_t)hr::group_plan_ints_bound(n_a, T_a, g), gi_b = (int64_t)hr::group_plan_ints_bound(n_b, T_b, g);
-        const hr::Workspace ws_a = hr::make_workspace(m->cfg, n_a, T_a, pt_stride, false, -1, 0, gi_a);
-        const hr::Workspace ws_b = hr::make_workspace(m->cfg, n_b, T_b, pt_stride, false, -1, 0, gi_b);
+        const hr::Workspace ws_a = hr::make_workspace(m->cfg, n_a, T_a, pt_stride, false, -1, 0, gi_a, m->n_precise > 0);
+        const hr::Workspace ws_b = hr::make_workspace(m->cfg, n_b, T_b, pt_stride, false, -1, 0, gi_b, m->n_precise > 0);
         if (ws_a.total + ws_b.total <= workspace_bytes) {
             const hr::MetaLayout ml_a = hr::make_meta_layout(n_a, T_a, pt_stride, -1, 0, gi_a);
             const hr::MetaLayout ml_b = hr::make_meta_layout(n_b, T_b, pt_stride, -1, 0, gi_b);
@@ -700,7 +746,7 @@ int hr_rerank_score_static(hr_model* m, const hr_pool* pool, int32_t n_pairs, co
     if (!scores_dev) return HR_ERR_INVALID_ARG;
     const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     const int64_t grp_ints = (int64_t)hr::group_plan_ints_bound(n_pairs, T, g);
-    const hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints);
+    const hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints, m->n_precise > 0);
     if (ws.total > kStaticScratchBytes) {
         snprintf(g_last_error, sizeof(g_last_error), "hr_rerank_score_static: this call needs %zu bytes of scratch, the static array holds %zu",
                  ws.total, kStaticScratchBytes);
@@ -717,6 +763,15 @@ int hr_rerank_score_static(hr_model* m, const hr_pool* pool, int32_t n_pairs, co
     m->prof_on = prof;
     return rc;
 }
+
+int hr_model_set_precise_layers(hr_model* m, int n_layers) {
+    if (!m || n_layers < -1 || n_layers > m->cfg.n_layers) return HR_ERR_INVALID_ARG;
+    if (n_layers > 0 && !m->mfma_gemm) return HR_ERR_UNSUPPORTED_SHAPE;
+    m->n_precise = n_layers < 0 ? default_precise_layers(m->cfg, m->mfma_gemm) : n_layers;
+    return HR_OK;
+}
+
+int hr_model_precise_layers(const hr_model* m) { return m ? m->n_precise : HR_ERR_INVALID_ARG; }
 
 int hr_rerank_parts(const hr_model* m, int64_t total_q_tokens) {
     if (!m || total_q_tokens < 0) return HR_ERR_INVALID_ARG;

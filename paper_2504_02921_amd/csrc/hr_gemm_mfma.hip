@@ -181,34 +181,43 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BM / WM / 32][BN /
         };
         half_t* out = (half_t*)a.out0;
         const int F = a.N / 2;
+        // split output (the layers that run with 22-bit operands): m = hi + lo is written as [M][hi F | lo F], one half
+        // after the other through the same stage
+        const int parts = a.split_out ? 2 : 1;
+        const int ldo = parts * F;
+        for (int part = 0; part < parts; ++part) {
+            if (part) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");     // the hi tile has been read out of the stage
 #pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            const int lr = wm * TM + i * 32 + frow;
+            for (int i = 0; i < MI; ++i) {
+                const int lr = wm * TM + i * 32 + frow;
 #pragma unroll
-            for (int j = 0; j < NI; j += 2)
+                for (int j = 0; j < NI; j += 2)
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int ch = ((wn * TN) / 2 + (j / 2) * 32) / 8 + r4;
-                    halfx4 w;
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        const int ch = ((wn * TN) / 2 + (j / 2) * 32) / 8 + r4;
+                        halfx4 w;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float g = acc[i][j][r4 * 4 + e], u = acc[i][j + 1][r4 * 4 + e];
-                        const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
-                        w[e] = from_float<half_t>(g * sg * u);
+                        for (int e = 0; e < 4; ++e) {
+                            const float g = acc[i][j][r4 * 4 + e], u = acc[i][j + 1][r4 * 4 + e];
+                            const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g));
+                            const float v = g * sg * u;
+                            const half_t hi = from_float<half_t>(v);
+                            w[e] = part ? from_float<half_t>(v - (float)hi) : hi;
+                        }
+                        *(halfx4*)(stage_row(lr) + ((ch ^ swz(lr)) << 3) + 4 * fh) = w;
                     }
-                    *(halfx4*)(stage_row(lr) + ((ch ^ swz(lr)) << 3) + 4 * fh) = w;
-                }
-        }
-        // LDS-only barrier: __syncthreads() would also wait for the next tile's loads, which were just requested
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            }
+            // LDS-only barrier: __syncthreads() would also wait for the next tile's loads, which were just requested
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #pragma unroll
-        for (int it = 0; it < ITER; ++it) {
-            const int L = it * NT + tid;
-            const int row = L / CPRO, pch = L % CPRO;
-            const int col = tile_n0 / 2 + ((pch ^ swz(row)) << 3);
-            const int64_t grow = tile_m0 + row;
-            if (grow >= a.M || col >= F) continue;          // F is a multiple of 32: whole chunks
-            *(uint4v*)(out + grow * F + col) = *(const uint4v*)(stage_row(row) + (pch << 3));
+            for (int it = 0; it < ITER; ++it) {
+                const int L = it * NT + tid;
+                const int row = L / CPRO, pch = L % CPRO;
+                const int col = tile_n0 / 2 + ((pch ^ swz(row)) << 3);
+                const int64_t grow = tile_m0 + row;
+                if (grow >= a.M || col >= F) continue;          // F is a multiple of 32: whole chunks
+                *(uint4v*)(out + grow * ldo + part * F + col) = *(const uint4v*)(stage_row(row) + (pch << 3));
+            }
         }
     } else {   // EPI_QKV_ROPE
         constexpr int hb = HB;                                  // 32-wide blocks per half head: head_dim = 64 * HB
@@ -372,6 +381,8 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int K = a.K;
+    const int Kw = a.Kw > 0 ? a.Kw : K;         // columns of W: K, or K / 2 when A carries [hi | lo] halves of a split operand
+    const int nkw = Kw / BK;
     const half_t* A = (const half_t*)a.A;
     const half_t* W = (const half_t*)a.W;
 
@@ -394,19 +405,20 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_mfma_kernel(GemmArgs a) {
         for (int p = 0; p < PB; ++p) {
             int r = n0 + p * RPP + lrow;
             r = r < a.N ? r : a.N - 1;
-            pb[p] = W + (size_t)r * K + lchunk * 8;
+            pb[p] = W + (size_t)r * Kw + lchunk * 8;
         }
     };
     set_tile(tc);
     auto dma = [&](int kt, int buf) {
         half_t* da = sA + buf * BM * BK + wave * 64 * 8;      // wave-uniform: the hardware adds 16 bytes per lane
         half_t* db = sB + buf * BN * BK + wave * 64 * 8;
+        const int ktw = kt < nkw ? kt : kt - nkw;             // the lo half of a split A meets the same W columns again
 #pragma unroll
         for (int p = 0; p < PA; ++p)
             __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pa[p] + kt * BK), (lds_ptr_t)(da + p * NT * 8), 16, 0, 0);
 #pragma unroll
         for (int p = 0; p < PB; ++p)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pb[p] + kt * BK), (lds_ptr_t)(db + p * NT * 8), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pb[p] + ktw * BK), (lds_ptr_t)(db + p * NT * 8), 16, 0, 0);
     };
 
     floatx16 acc[MI][NI];
@@ -521,6 +533,8 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_ring_kernel(GemmArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int K = a.K;
+    const int Kw = a.Kw > 0 ? a.Kw : K;
+    const int nkw = Kw / BK;
     const half_t* A = (const half_t*)a.A;
     const half_t* W = (const half_t*)a.W;
 
@@ -538,17 +552,18 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_ring_kernel(GemmArgs a) {
     for (int p = 0; p < PB; ++p) {
         int r = n0 + p * RPP + lrow;
         r = r < a.N ? r : a.N - 1;
-        pb[p] = W + (size_t)r * K + lchunk * 8;
+        pb[p] = W + (size_t)r * Kw + lchunk * 8;
     }
     auto dma = [&](int kt, int buf) {
         half_t* da = sA + buf * BM * BK + wave * 64 * 8;
         half_t* db = sB + buf * BN * BK + wave * 64 * 8;
+        const int ktw = kt < nkw ? kt : kt - nkw;
 #pragma unroll
         for (int p = 0; p < PA; ++p)
             __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pa[p] + kt * BK), (lds_ptr_t)(da + p * NT * 8), 16, 0, 0);
 #pragma unroll
         for (int p = 0; p < PB; ++p)
-            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pb[p] + kt * BK), (lds_ptr_t)(db + p * NT * 8), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gbl_ptr_t)(pb[p] + ktw * BK), (lds_ptr_t)(db + p * NT * 8), 16, 0, 0);
     };
 
     floatx16 acc[MI][NI];
@@ -685,6 +700,7 @@ bool gemm_mfma_supported(const hr_model_cfg& c) {
 hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st) {
     if (a.M == 0) return hipSuccess;
     if (a.K % BK != 0) return hipErrorInvalidValue;
+    if (a.Kw > 0 && (a.Kw % BK != 0 || (a.K != a.Kw && a.K != 2 * a.Kw))) return hipErrorInvalidValue;
     const bool wide_head = epi == EPI_QKV_ROPE && a.d == 128;       // a wave must span a whole 128-wide head
     // Few rows: when even 128 x 128 tiles do not give every CU one, the ring variants take over.  64-row tiles double
     // the tile count; they pay when that still fits one round of the chip (a ring workgroup has its CU to itself),

@@ -81,29 +81,36 @@ MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t
 }
 
 Workspace make_workspace(const hr_model_cfg& c, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch,
-                         int64_t n_out, int64_t dst_ints, int64_t grp_ints) {
+                         int64_t n_out, int64_t dst_ints, int64_t grp_ints, bool split_ops) {
     Workspace w;
     size_t asz = dtype_size(c.dtype);
     size_t H = c.hidden, d = c.head_dim, F = c.ffn;
     size_t nq = (size_t)c.n_q_heads * d, nkv = (size_t)c.n_kv_heads * d;
     size_t t = (size_t)T;
+    // split_ops: some layers run with 22-bit operands, i.e. activations as [hi | lo] pairs of halves: y, q, o and m take
+    // twice the room, the new tokens' K/V pages get a second buffer for their rounding residue, and the QKV projection of
+    // those layers leaves fp32 rows for a RoPE kernel of its own
+    const size_t sp = split_ops ? 2 : 1;
     MetaLayout ml = make_meta_layout(n_seq, T, pt_stride, n_out, dst_ints, grp_ints);
     w.meta_ints = ml.total;
     size_t o = 0;
     w.off_meta = o; o = align_up(o + ml.total * sizeof(int32_t));
     w.off_rope = o; o = align_up(o + t * (d / 2) * 2 * sizeof(float));
     w.off_x = o;    o = align_up(o + t * H * sizeof(float));
-    w.off_y = o;    o = align_up(o + t * H * asz);
-    w.off_q = o;    o = align_up(o + t * nq * asz);
+    w.off_y = o;    o = align_up(o + sp * t * H * asz);
+    w.off_q = o;    o = align_up(o + sp * t * nq * asz);
     // new-token K and V: either [T][n_kv][d] each, or pages of 16 slots (32-slot aligned per sequence), K|V blocks
     // interleaved like the pool; one region of 2 * (T + 32 n_seq) token slots serves both forms
     const size_t kv_slots = t + 32 * (size_t)n_seq;
     w.off_k = o;    o = align_up(o + kv_slots * nkv * asz);
     w.off_v = o;    o = align_up(o + kv_slots * nkv * asz);
-    w.off_o = o;    o = align_up(o + t * nq * asz);
-    w.off_m = o;    o = align_up(o + t * F * asz);
+    w.off_kvlo = o;
+    if (split_ops) o = align_up(o + 2 * kv_slots * nkv * asz);      // between K/V and o: cleared together with them
+    w.off_o = o;    o = align_up(o + sp * t * nq * asz);
+    w.off_m = o;    o = align_up(o + sp * t * F * asz);
     w.off_f32 = o;
     if (need_f32_scratch) o = align_up(o + t * std::max(nq + 2 * nkv, 2 * F) * sizeof(float));
+    else if (split_ops) o = align_up(o + t * (nq + 2 * nkv) * sizeof(float));
     w.total = o;
     return w;
 }

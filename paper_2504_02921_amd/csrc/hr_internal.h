@@ -51,13 +51,14 @@ PackLayout make_pack_layout(const hr_model_cfg& cfg);
 // Workspace carving for one call over `n_seq` sequences and `T` new tokens.
 struct Workspace {
     size_t meta_ints = 0;      // int32 count of the metadata block
-    size_t off_meta = 0, off_rope = 0, off_x = 0, off_y = 0, off_q = 0, off_k = 0, off_v = 0, off_o = 0,
+    size_t off_meta = 0, off_rope = 0, off_x = 0, off_y = 0, off_q = 0, off_k = 0, off_v = 0, off_kvlo = 0, off_o = 0,
            off_m = 0, off_f32 = 0;
     size_t total = 0;
 };
 // full_path: sequences carry their own document tokens (no page table).
+// split_ops: room for the layers that run with split (hi + lo) operands
 Workspace make_workspace(const hr_model_cfg& cfg, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch,
-                         int64_t n_out = -1, int64_t dst_ints = 0, int64_t grp_ints = 0);
+                         int64_t n_out = -1, int64_t dst_ints = 0, int64_t grp_ints = 0, bool split_ops = false);
 
 // Metadata block layout (int32 offsets inside the block), uploaded once per call.
 // new_slot[t] / new_cu[p]: where the K/V of new token t goes when the new keys are kept as 16-token

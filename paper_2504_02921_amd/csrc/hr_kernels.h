@@ -37,6 +37,11 @@ struct MetaView {
 hipError_t launch_embed(int dtype, const void* E, const MetaView& mv, float* x, int H, hipStream_t st);
 hipError_t launch_rope_table(const MetaView& mv, float2* tab, int head_dim, float base, hipStream_t st);
 hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st);
+// 22-bit operand form (16-bit models): y as [T][hi H | lo H] halves
+hipError_t launch_rmsnorm_split(const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st);
+// fp32 qkv [T][(n_q + 2 n_kv) d] -> RoPE -> q as [T][hi | lo] halves, new K/V as pages in kv_hi and their rounding residue in kv_lo
+hipError_t launch_rope_pages_split(const float* qkv, const float2* tab, void* q, void* kv_hi, void* kv_lo, const int32_t* new_slot,
+                                   int64_t T, int n_q, int n_kv, int d, hipStream_t st);
 // C[M][N] (+)= A[M][K] * W[N][K]^T, C fp32
 hipError_t launch_gemm_generic(int dtype, const void* A, const void* W, float* C, int64_t M, int N, int K,
                                bool accumulate, hipStream_t st);
@@ -65,6 +70,11 @@ struct GemmArgs {
     const void* W;      // [N][K] bf16 (packed)
     int64_t M;
     int N, K;
+    // Split A operand: 0 (or K) = plain; K / 2 = A is [M][K] holding [hi | lo] halves of a K/2-wide activation (the value
+    // is hi + lo, 22 significant bits) and W has K / 2 columns, met by both halves: C = hi W^T + lo W^T
+    int Kw;
+    // EPI_SWIGLU: m is written as [M][2 * N/2] = [hi | lo]; EPI_QKV_ROPE: q is written as [M][2 * n_q * d] = [hi | lo]
+    int split_out;
     // epilogue operands
     float* x;           // EPI_RESID_ADD: fp32 [M][N], x += acc
     void* out0;         // EPI_QKV_ROPE: q ; EPI_SWIGLU: m [M][N/2]
@@ -87,9 +97,11 @@ struct GroupView {
                   *sub_seq = nullptr, *sub_key0 = nullptr;
 };
 // kv_new_pages: the new tokens' K/V as pages (see GemmArgs::kv_pages).  groups: nullptr = every sequence on its own.
+// kv_new_lo_pages: if set, the 22-bit form: q and o are [T][hi | lo] halves, and this buffer (same arrangement as
+// kv_new_pages) holds what the rounding of the new tokens' K/V to half left out.
 hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv,
                             const PoolView& pv, int layer, int n_q, int max_q_len, hipStream_t st, bool last_only = false,
-                            const GroupView* groups = nullptr);
+                            const GroupView* groups = nullptr, const void* kv_new_lo_pages = nullptr);
 // fp8 pools: quantising copy of whole pages (amax -> scale -> E4M3 codes per page and kv head) from the half new-KV buffer
 hipError_t launch_pages_to_pool_fp8(const char* kv_new, char* pool_layer_base, float* scales_layer_base, const int32_t* src_page,
                                     const int32_t* dst_page, int n_pages, int n_kv, int d, hipStream_t st);

@@ -125,6 +125,47 @@ def test_bf16_wide_heads_with_projection_shapes_outside_the_mfma_family(hidden, 
     case.close()
 
 
+@pytest.mark.parametrize("d,n_q,n_kv,kv,qlen,n_layers", [
+    (64, 14, 2, "bf16", (5, 40), 4),        # 7 heads per kv head, up to 280 rows: two row blocks per wave
+    (128, 8, 2, "bf16", (20, 64), 3),       # head_dim 128, 256 rows
+    (128, 4, 1, "fp8", (3, 33), 3),         # fp8 pages: the V-scale mantissa sits on the split probabilities
+    (64, 8, 2, "bf16", (33, 64), 2),        # two sub-tiles of own keys
+    (128, 16, 2, "bf16", (40, 64), 2),      # 512 rows at head_dim 128: the register-starved variant
+])
+def test_split_operand_layers_score_an_order_of_magnitude_closer_to_the_oracle(d, n_q, n_kv, kv, qlen, n_layers):
+    """Every layer on split (hi + lo) operands: the 16-bit operand rounding, which is all that separates the MFMA path from
+    the float64 definition on these inputs, all but disappears; and a pair still scores the same bits alone and in a batch,
+    grouped with the pairs that share its document or not."""
+    model = small_model(dtype="bf16", n_layers=n_layers, hidden=256, n_q=n_q, n_kv=n_kv, d=d, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("split_ops", model, 6, 4, (20, 200), qlen, kv, pool_docs=7, zipf_a=0.6, seed=d + n_q)
+    w = wlmod.SeededWeights(model, seed=17, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(cfg, spare_pages=2)
+    case = H.Case(wl, w)
+    try:
+        case.fill_from_prefill()
+        want = case.oracle_scores()
+        assert case.model.gemm_path() == "mfma" and case.model.attention_path(case.pool) == "mfma"
+        case.model.set_precise_layers(0)
+        err_plain = np.abs(case.gpu_scores() - want).max()
+        case.model.set_precise_layers(n_layers)
+        assert case.model.precise_layers() == n_layers
+        got = case.gpu_scores()
+        err_split = np.abs(got - want).max()
+        print(f"max |err| plain {err_plain:.2e}, split {err_split:.2e}")
+        assert err_plain <= H.TOL["bf16"]
+        assert err_split <= 2e-5 and err_split <= err_plain / 50
+        for idx in ([0], [5, 6, 7, 20], list(range(wl.n_pairs - 3, wl.n_pairs))):
+            np.testing.assert_array_equal(case.gpu_scores(wl.subset(np.array(idx))), got[idx])
+        # only the first layer split: in between
+        case.model.set_precise_layers(1)
+        err_one = np.abs(case.gpu_scores() - want).max()
+        assert err_one <= H.TOL["bf16"]
+        case.model.set_precise_layers(-1)
+        assert case.model.precise_layers() == 0            # default for a shape this small
+    finally:
+        case.close()
+
+
 def test_fp8_pool_small_model():
     model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=8, n_kv=2, d=32, ffn=352)
     cfg = wlmod.WorkloadCfg("fp8_small", model, 2, 4, (20, 90), (3, 12), "fp8", seed=5)

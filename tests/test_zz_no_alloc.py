@@ -34,7 +34,7 @@ def test_static_scratch_entry_point_matches_the_workspace_one(dtype, d, n_q, n_k
     case = H.Case(wl, w)
     try:
         case.fill_from_prefill()
-        assert int(hb.lib.hr_rerank_static_scratch_bytes()) == 64 << 20
+        assert int(hb.lib.hr_rerank_static_scratch_bytes()) == 128 << 20
         out = torch.full((wl.n_pairs,), float("nan"), dtype=torch.float32, device="cuda:0")
         want_all = case.gpu_scores()                                   # hr_rerank_score, caller's workspace
         oracle_all = case.oracle_scores()
@@ -70,7 +70,7 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
     try:
         case.fill_synthetic(oracle_doc_ids=[])
         out = torch.zeros(4096, dtype=torch.float32, device="cuda:0")
-        # the same two pairs repeated until the workspace passes 64 MiB (2048 pairs x 32 tokens: x alone is 256 MiB)
+        # the same two pairs repeated until the workspace passes 128 MiB (2048 pairs x 32 tokens: x alone is 256 MiB)
         reps = 1024
         pt = np.tile(wl.page_table, (reps, 1))
         dl, ql = np.tile(wl.doc_lens, reps), np.tile(wl.query_lens, reps)
