@@ -357,6 +357,13 @@ int hr_profile_count(void);
 const char* hr_profile_name(int idx);
 int hr_profile_read(hr_model* model, double* ms_out, int64_t* launches_out);
 
+/* A yardstick for the roofline of the KV-streaming attention (which is bound by reading HBM): one read-only pass over
+ * `bytes` (whole KiB are read) of device memory at src_dev (16-byte aligned) with a kernel of the library's own, enqueued
+ * on `stream`; time it from outside.  to_lds = 0: 16-byte loads into registers; 1: the direct-to-LDS loads the attention
+ * kernel streams pages with.  sink_dev: >= 4 bytes of device memory that receive a fold of what was read (so that no load
+ * can be dropped).  HR_ERR_INVALID_ARG on null or misaligned pointers or bytes < 1024. */
+int hr_probe_read_bandwidth(const void* src_dev, size_t bytes, void* sink_dev, size_t sink_bytes, int to_lds, void* stream);
+
 /* Name of the kernel family a model / pool combination runs: "mfma" or "generic" ("none" for a null handle); never
  * NULL.  The MFMA attention is only chosen together with the MFMA projections. */
 const char* hr_attention_path(const hr_model* model, const hr_pool* pool);

@@ -60,7 +60,7 @@ EXPORTS = [
     "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_static_scratch_bytes",
     "hr_rerank_score_static", "hr_model_set_precise_layers", "hr_model_precise_layers", "hr_rerank_set_streams", "hr_rerank_parts", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
-    "hr_rerank_topk", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
+    "hr_rerank_topk", "hr_probe_read_bandwidth", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
 ]
 
 
@@ -117,6 +117,7 @@ def _load() -> C.CDLL:
         "hr_attention_path": (C.c_char_p, [C.c_void_p, C.c_void_p]),
         "hr_gemm_path": (C.c_char_p, [C.c_void_p]),
         "hr_rerank_topk": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+        "hr_probe_read_bandwidth": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]),
         "hr_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
         "hr_profile_select": (C.c_int, [C.c_void_p, C.c_uint32]),
         "hr_profile_count": (C.c_int, []),
@@ -207,6 +208,13 @@ def rerank_topk(scores, seg_offsets, k: int, with_scores: bool = False, stream=N
           "hr_rerank_topk")
     idx._hr_seg = seg_dev          # keep the offsets alive until the result is dropped (the kernel may still be queued)
     return (idx, sc) if with_scores else idx
+
+
+def probe_read_bandwidth(src, sink, to_lds: bool = False, stream=None) -> None:
+    """One read-only pass of the library's streaming yardstick kernel over the device tensor `src`."""
+    check(lib.hr_probe_read_bandwidth(C.c_void_p(src.data_ptr()), src.numel() * src.element_size(), C.c_void_p(sink.data_ptr()),
+                                      sink.numel() * sink.element_size(), 1 if to_lds else 0, _stream_ptr(stream)),
+          "hr_probe_read_bandwidth")
 
 
 class KVPool:

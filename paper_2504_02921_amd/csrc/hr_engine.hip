@@ -993,6 +993,13 @@ int hr_profile_read(hr_model* m, double* ms_out, int64_t* launches_out) {
     return HR_OK;
 }
 
+int hr_probe_read_bandwidth(const void* src_dev, size_t bytes, void* sink_dev, size_t sink_bytes, int to_lds, void* stream) {
+    if (!src_dev || !sink_dev || bytes < 1024 || sink_bytes < 4 || (uintptr_t)src_dev % 16 != 0 || (uintptr_t)sink_dev % 4 != 0)
+        return HR_ERR_INVALID_ARG;
+    HR_HIP(launch_probe_read(src_dev, bytes, sink_dev, sink_bytes, to_lds != 0, hr::device_cu_count(), (hipStream_t)stream));
+    return HR_OK;
+}
+
 const char* hr_last_error(void) { return g_last_error; }
 
 const char* hr_attention_path(const hr_model* m, const hr_pool* pool) {

@@ -115,6 +115,8 @@ hipError_t launch_pages_move(const PoolLayout& lay, char* pool_base, const int32
 hipError_t launch_pages_move4(const PoolLayout& lay, char* pool_base, const int32_t* page_ids_host, int64_t n_pages, char* records,
                               bool to_pool, hipStream_t st);
 hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t st);
+// read-only pass over `bytes` of src (whole KiB), folding what it reads into sink (>= 4 bytes); to_lds: direct-to-LDS loads
+hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, size_t sink_bytes, bool to_lds, int cus, hipStream_t st);
 // dst[i][:] = src[rows[i]][:] for n rows of `cols` floats (device arrays)
 hipError_t launch_gather_rows_f32(const float* src, const int32_t* rows, float* dst, int n, int cols, hipStream_t st);
 // per-segment top-k by rank counting: idx [n_seg][k] (-1 padded), optional scores [n_seg][k]

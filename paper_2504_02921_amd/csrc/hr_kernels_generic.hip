@@ -595,6 +595,60 @@ hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* y,
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Yardstick for the memory side: a read-only pass over a buffer.  Plain form: 16-byte loads into registers, four in
+// flight per lane, XOR-folded so that nothing can be dropped.  LDS form: the direct-to-LDS loads the attention kernel
+// streams with (16 bytes per lane, a ring of 16 one-KiB slots per wave, at most 16 loads in flight per wave).
+// ------------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void* probe_lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* probe_gbl_ptr_t;
+
+__global__ void __launch_bounds__(256) probe_read_kernel(const uint4* __restrict__ src, size_t n16, unsigned* __restrict__ sink,
+                                                         unsigned sink_mask) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc.x ^= a.x ^ b.x ^ c.x ^ d.x;
+        acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
+        acc.z ^= a.z ^ b.z ^ c.z ^ d.z;
+        acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 a = src[i];
+        acc.x ^= a.x; acc.y ^= a.y; acc.z ^= a.z; acc.w ^= a.w;
+    }
+    sink[((size_t)blockIdx.x * 256 + threadIdx.x) & sink_mask] = acc.x ^ acc.y ^ acc.z ^ acc.w;
+}
+
+__global__ void __launch_bounds__(256) probe_read_lds_kernel(const char* __restrict__ src, size_t n_kib, unsigned* __restrict__ sink,
+                                                             unsigned sink_mask) {
+    __shared__ __attribute__((aligned(16))) char ring[4 * 16 * 1024];       // 4 waves x 16 slots x 1 KiB
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const size_t n_waves = (size_t)gridDim.x * 4;
+    char* mine = ring + wave * 16 * 1024;
+    int slot = 0;
+    for (size_t k = (size_t)blockIdx.x * 4 + wave; k < n_kib; k += n_waves) {
+        __builtin_amdgcn_global_load_lds((probe_gbl_ptr_t)(src + k * 1024 + lane * 16), (probe_lds_ptr_t)(mine + slot * 1024), 16, 0, 0);
+        slot = (slot + 1) & 15;
+        __builtin_amdgcn_s_waitcnt(0x0F7F);       // vmcnt(15): the slot about to be reused has landed
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    sink[((size_t)blockIdx.x * 256 + threadIdx.x) & sink_mask] = *(const unsigned*)(mine + lane * 16);
+}
+
+hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, size_t sink_bytes, bool to_lds, int cus, hipStream_t st) {
+    if (bytes < 1024 || sink_bytes < 4) return hipSuccess;
+    unsigned mask = 1;
+    while ((size_t)(mask << 1) * 4 <= sink_bytes && mask < (1u << 20)) mask <<= 1;     // largest power of two of words that fits
+    const unsigned grid = (unsigned)std::max(1, cus) * 8;
+    if (to_lds) probe_read_lds_kernel<<<dim3(grid), 256, 0, st>>>((const char*)src, bytes / 1024, (unsigned*)sink, mask - 1);
+    else probe_read_kernel<<<dim3(grid), 256, 0, st>>>((const uint4*)src, bytes / 16, (unsigned*)sink, mask - 1);
+    return hipGetLastError();
+}
+
 hipError_t launch_rmsnorm_split(const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st) {
     if (T == 0) return hipSuccess;
     rmsnorm_split_kernel<<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps);
