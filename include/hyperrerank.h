@@ -153,7 +153,8 @@ int hr_doc_kv_write(hr_pool* pool, int32_t doc_len, const int32_t* page_ids,
  *   page_ids      host, ceil(doc_len/16) ids of pages that hold a document (written or prefilled)
  *   k_dev, v_dev  device, logical layout [n_layers][doc_len][n_kv_heads][head_dim] in the pool's own element type:
  *                 fp32 for HR_F32 pools, IEEE half for HR_BF16 pools (the pool keeps the caller's bf16 values as
- *                 halves, exactly, and prefilled pages are halves in the first place), E4M3 codes for fp8 pools
+ *                 halves: exactly for magnitudes in [2^-14, 65504], see hr_kv_pool_range_report for the rest; prefilled
+ *                 pages are halves in the first place), E4M3 codes for fp8 pools
  *   k_scales_dev, v_scales_dev   fp8 only: device fp32 [n_layers][n_pages][n_kv_heads]; else NULL
  * One gather kernel is enqueued on `stream`.  HR_ERR_PAGE_RANGE for an id out of range, HR_ERR_TABLE_SHORT for a page
  * that holds nothing, HR_ERR_LEN_RANGE for doc_len <= 0. */
@@ -199,6 +200,28 @@ int hr_kv_pages_in(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, cons
 size_t hr_kv_page_record4_bytes(const hr_pool* pool);
 int hr_kv_pages_out4(const hr_pool* pool, int32_t n_pages, const int32_t* page_ids, void* dst, void* stream);
 int hr_kv_pages_in4(hr_pool* pool, int32_t n_pages, const int32_t* page_ids, const void* src, void* stream);
+
+/* ---- what the 16-bit operand format met ----
+ * A 16-bit model computes on IEEE halves: the caller's bf16 weights and bf16 document K/V are converted once, when the
+ * weights are packed and when a document is written.  bf16 has the range of fp32, half does not: a magnitude of 65520 or
+ * more becomes infinity, and below 2^-14 half is subnormal (a bf16 value below 2^-17 loses bits, below 2^-25 it becomes
+ * zero).  The conversions count what they meet, and for fp8 pools the write also counts what the format cannot express:
+ *   overflow          values that became infinity (scores that depend on them come out non-finite)
+ *   underflow         values that half does not hold exactly (absolute error below 2^-25; random-initialised weights
+ *                     always have a few per ten thousand of these)
+ *   nonfinite_inputs  NaN or infinity in the caller's data
+ *   fp8_nan_codes     E4M3 codes 0x7f / 0xff (NaN; the kernels read them as +-480)
+ *   fp8_bad_scales    K or V scales that are not positive and finite, and V scales outside [2^-22, 2^8) (the power of
+ *                     two of a V scale is applied while the codes are expanded to half, which covers that range)
+ * Activations are not counted: one that exceeds the half range becomes infinity and makes the pair's score non-finite.
+ * The report calls copy 64 bytes from the device and wait for the work enqueued so far (not for use in a hot loop).
+ * Pages that arrive through hr_kv_pages_in / hr_doc_prefill are not counted (they were halves or codes already). */
+typedef struct hr_range_report {
+    int64_t overflow, underflow, nonfinite_inputs, fp8_nan_codes, fp8_bad_scales;
+    int64_t reserved[3];
+} hr_range_report;
+int hr_model_range_report(const hr_model* model, hr_range_report* out);      /* since hr_weights_load */
+int hr_kv_pool_range_report(const hr_pool* pool, hr_range_report* out);      /* over every hr_doc_kv_write so far */
 
 /* ---- weights ---- */
 

@@ -44,6 +44,14 @@ class hr_model_cfg(C.Structure):
                 ("rope_base", C.c_float), ("rms_eps", C.c_float)]
 
 
+class hr_range_report(C.Structure):
+    _fields_ = [("overflow", C.c_int64), ("underflow", C.c_int64), ("nonfinite_inputs", C.c_int64),
+                ("fp8_nan_codes", C.c_int64), ("fp8_bad_scales", C.c_int64), ("reserved", C.c_int64 * 3)]
+
+    def as_dict(self):
+        return {k: int(getattr(self, k)) for k in ("overflow", "underflow", "nonfinite_inputs", "fp8_nan_codes", "fp8_bad_scales")}
+
+
 _PP = C.POINTER(C.c_void_p)
 
 
@@ -60,7 +68,7 @@ EXPORTS = [
     "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_static_scratch_bytes",
     "hr_rerank_score_static", "hr_model_set_precise_layers", "hr_model_precise_layers", "hr_rerank_set_streams", "hr_rerank_parts", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
-    "hr_rerank_topk", "hr_probe_read_bandwidth", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
+    "hr_rerank_topk", "hr_model_range_report", "hr_kv_pool_range_report", "hr_probe_read_bandwidth", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
 ]
 
 
@@ -117,6 +125,8 @@ def _load() -> C.CDLL:
         "hr_attention_path": (C.c_char_p, [C.c_void_p, C.c_void_p]),
         "hr_gemm_path": (C.c_char_p, [C.c_void_p]),
         "hr_rerank_topk": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+        "hr_model_range_report": (C.c_int, [C.c_void_p, C.POINTER(hr_range_report)]),
+        "hr_kv_pool_range_report": (C.c_int, [C.c_void_p, C.POINTER(hr_range_report)]),
         "hr_probe_read_bandwidth": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int, C.c_void_p]),
         "hr_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
         "hr_profile_select": (C.c_int, [C.c_void_p, C.c_uint32]),
@@ -263,6 +273,11 @@ class KVPool:
         ids = _i32(page_ids)
         check(lib.hr_doc_kv_free(self.handle, _i32p(ids), len(ids)), "hr_doc_kv_free")
 
+    def range_report(self) -> dict:
+        r = hr_range_report()
+        check(lib.hr_kv_pool_range_report(self.handle, C.byref(r)), "hr_kv_pool_range_report")
+        return r.as_dict()
+
     @property
     def page_record_bytes(self) -> int:
         return int(lib.hr_kv_page_record_bytes(self.handle))
@@ -364,6 +379,11 @@ class Model:
             self._ws = None
             self._ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         return self._ws
+
+    def range_report(self) -> dict:
+        r = hr_range_report()
+        check(lib.hr_model_range_report(self.handle, C.byref(r)), "hr_model_range_report")
+        return r.as_dict()
 
     def gemm_path(self) -> str:
         return lib.hr_gemm_path(self.handle).decode()

@@ -440,16 +440,25 @@ int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* w, void* pack
     const size_t esz = hr::dtype_size(dt);
     const int H = cfg->hidden, d = cfg->head_dim, F = cfg->ffn;
     const int nq = cfg->n_q_heads * d, nkv = cfg->n_kv_heads * d;
+    long long* rc = (long long*)((char*)pack_dev + pl.counter_off);      // what the conversion to half meets (hr_model_range_report)
+    {
+        hipError_t e = hr::launch_fill_zero(rc, hr::kRangeCounterBytes, st);
+        if (e != hipSuccess) {
+            note_hip_error(e, "counter fill kernel");
+            hr_model_destroy(m);
+            return HR_ERR_DEVICE;
+        }
+    }
     for (int l = 0; l < cfg->n_layers; ++l) {
         char* slab = (char*)pack_dev + (size_t)l * pl.layer_elems * esz;
         char* wqkv = slab + pl.wqkv * esz;
-        hipError_t e = hr::launch_pack_rows(dt, w->wq[l], wqkv, nq, H, nq, 1, 0, st);
-        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wk[l], wqkv + (size_t)nq * H * esz, nkv, H, nkv, 1, 0, st);
-        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wv[l], wqkv + (size_t)(nq + nkv) * H * esz, nkv, H, nkv, 1, 0, st);
-        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wo[l], slab + pl.wo * esz, H, nq, H, 1, 0, st);
-        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wg[l], slab + pl.wgu * esz, F, H, pl.gu_interleave, 2, 0, st);
-        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wu[l], slab + pl.wgu * esz, F, H, pl.gu_interleave, 2, 1, st);
-        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wd[l], slab + pl.wd * esz, H, F, H, 1, 0, st);
+        hipError_t e = hr::launch_pack_rows(dt, w->wq[l], wqkv, nq, H, nq, 1, 0, rc, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wk[l], wqkv + (size_t)nq * H * esz, nkv, H, nkv, 1, 0, rc, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wv[l], wqkv + (size_t)(nq + nkv) * H * esz, nkv, H, nkv, 1, 0, rc, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wo[l], slab + pl.wo * esz, H, nq, H, 1, 0, rc, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wg[l], slab + pl.wgu * esz, F, H, pl.gu_interleave, 2, 0, rc, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wu[l], slab + pl.wgu * esz, F, H, pl.gu_interleave, 2, 1, rc, st);
+        if (e == hipSuccess) e = hr::launch_pack_rows(dt, w->wd[l], slab + pl.wd * esz, H, F, H, 1, 0, rc, st);
         if (e != hipSuccess) {
             note_hip_error(e, "weight packing kernels");
             hr_model_destroy(m);
@@ -482,7 +491,14 @@ int hr_doc_kv_write(hr_pool* pool, int32_t doc_len, const int32_t* page_ids, con
     if (!k_dev || !v_dev) return HR_ERR_INVALID_ARG;
     bool fp8 = pool->cfg.kv_dtype == HR_FP8_E4M3;
     if (fp8 && (!ks || !vs)) return HR_ERR_INVALID_ARG;
-    hipError_t e = hr::launch_kv_scatter(pool->lay, pool->base, page_ids, doc_len, k_dev, v_dev, ks, vs, (hipStream_t)stream);
+    long long* counters = (long long*)(pool->base + pool->lay.counter_off);
+    hipError_t e = hipSuccess;
+    if (!pool->counters_zeroed) {
+        e = hr::launch_fill_zero(counters, hr::kRangeCounterBytes, (hipStream_t)stream);
+        pool->counters_zeroed = e == hipSuccess;
+    }
+    if (e == hipSuccess)
+        e = hr::launch_kv_scatter(pool->lay, pool->base, page_ids, doc_len, k_dev, v_dev, ks, vs, counters, (hipStream_t)stream);
     if (e != hipSuccess) {
         note_hip_error(e, "pool scatter kernel");
         return HR_ERR_DEVICE;
@@ -991,6 +1007,30 @@ int hr_profile_read(hr_model* m, double* ms_out, int64_t* launches_out) {
     m->prof_used = 0;
     m->prof_class.clear();
     return HR_OK;
+}
+
+static int read_range_counters(const void* dev, hr_range_report* out) {
+    long long c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    HR_HIP(hipMemcpy(c, dev, sizeof(c), hipMemcpyDeviceToHost));        // waits for the work enqueued so far
+    out->overflow = c[hr::RC_OVERFLOW];
+    out->underflow = c[hr::RC_UNDERFLOW];
+    out->nonfinite_inputs = c[hr::RC_NONFINITE_IN];
+    out->fp8_nan_codes = c[hr::RC_FP8_NAN_CODE];
+    out->fp8_bad_scales = c[hr::RC_FP8_BAD_SCALE];
+    return HR_OK;
+}
+
+int hr_model_range_report(const hr_model* m, hr_range_report* out) {
+    if (!m || !out) return HR_ERR_INVALID_ARG;
+    *out = hr_range_report{};
+    return read_range_counters(m->pack_base + m->pack.counter_off, out);
+}
+
+int hr_kv_pool_range_report(const hr_pool* pool, hr_range_report* out) {
+    if (!pool || !out) return HR_ERR_INVALID_ARG;
+    *out = hr_range_report{};
+    if (!pool->counters_zeroed) return HR_OK;                          // nothing has been written through hr_doc_kv_write yet
+    return read_range_counters(pool->base + pool->lay.counter_off, out);
 }
 
 int hr_probe_read_bandwidth(const void* src_dev, size_t bytes, void* sink_dev, size_t sink_bytes, int to_lds, void* stream) {

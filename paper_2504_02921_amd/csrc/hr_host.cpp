@@ -40,7 +40,8 @@ PoolLayout make_layout(const hr_pool_cfg& c) {
     size_t blocks = (size_t)c.n_layers * c.num_pages * c.n_kv_heads * 2;
     l.data_bytes = align_up(blocks * l.block_elems * l.esz);
     l.scale_bytes = c.kv_dtype == HR_FP8_E4M3 ? align_up(blocks * sizeof(float)) : 0;
-    l.total_bytes = l.data_bytes + l.scale_bytes;
+    l.counter_off = l.data_bytes + l.scale_bytes;
+    l.total_bytes = l.counter_off + kRangeCounterBytes;
     return l;
 }
 
@@ -55,7 +56,8 @@ PackLayout make_pack_layout(const hr_model_cfg& c) {
     p.wgu = up(p.wo + H * (size_t)c.n_q_heads * d);
     p.wd = up(p.wgu + 2 * F * H);
     p.layer_elems = up(p.wd + H * F);
-    p.total_bytes = align_up(p.layer_elems * (size_t)c.n_layers * dtype_size(c.dtype));
+    p.counter_off = align_up(p.layer_elems * (size_t)c.n_layers * dtype_size(c.dtype));
+    p.total_bytes = p.counter_off + kRangeCounterBytes;
     p.gu_interleave = (c.ffn % 32 == 0) ? 32 : 1;
     return p;
 }

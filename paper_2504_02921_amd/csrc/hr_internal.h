@@ -11,6 +11,9 @@ namespace hr {
 
 constexpr int kPageTokens = HR_PAGE_TOKENS;
 constexpr size_t kAlign = 256;
+constexpr size_t kRangeCounterBytes = 256;     // room for 8 int64 counters of what the one-time conversions of caller data met
+// ... (weights, document K/V), indexed by
+enum RangeCounter { RC_OVERFLOW = 0, RC_UNDERFLOW = 1, RC_NONFINITE_IN = 2, RC_FP8_NAN_CODE = 3, RC_FP8_BAD_SCALE = 4 };
 
 inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 inline size_t dtype_size(int dt) { return dt == HR_F32 ? 4 : dt == HR_BF16 ? 2 : dt == HR_FP8_E4M3 ? 1 : 0; }
@@ -27,6 +30,7 @@ struct PoolLayout {
     size_t block_elems = 0;  // 16 * d
     size_t data_bytes = 0;   // aligned
     size_t scale_bytes = 0;  // aligned, 0 unless fp8
+    size_t counter_off = 0;  // 8 int64 range counters (kRangeCounterBytes) behind data and scales
     size_t total_bytes = 0;
 
     size_t block_index(int layer, int page, int kvh, int which) const {
@@ -43,6 +47,7 @@ PoolLayout make_layout(const hr_pool_cfg& cfg);
 struct PackLayout {
     size_t wqkv = 0, wo = 0, wgu = 0, wd = 0;   // element offsets within one layer's slab
     size_t layer_elems = 0;
+    size_t counter_off = 0;  // bytes: range counters behind the last layer's slab
     size_t total_bytes = 0;
     int gu_interleave = 1;   // rows of gate / up alternate in blocks of this many
 };
@@ -80,6 +85,7 @@ struct hr_pool {
     char* base = nullptr;
     std::vector<uint8_t> state;
     int64_t n_free = 0;
+    bool counters_zeroed = false;   // the range counters are cleared on the stream of the first write
 };
 
 // Host-side validation / bookkeeping (no HIP calls), used by the engine and testable on a CPU.

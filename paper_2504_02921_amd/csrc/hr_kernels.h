@@ -52,11 +52,12 @@ hipError_t launch_attn_generic(int dtype, const void* q, const void* k_new, cons
                                const MetaView& mv, const PoolView& pv, int layer, int n_q, int max_keys, hipStream_t st);
 hipError_t launch_score_head(int dtype, const float* x, const float* gain, const void* E, const MetaView& mv,
                              float* scores, int H, float eps, int yes_id, int no_id, hipStream_t st);
+// counters: 8 int64 in device memory (RangeCounter indices), or nullptr
 hipError_t launch_kv_scatter(const PoolLayout& lay, char* pool_base, const int32_t* page_ids_host, int doc_len,
-                             const void* k, const void* v, const float* ks, const float* vs, hipStream_t st);
+                             const void* k, const void* v, const float* ks, const float* vs, long long* counters, hipStream_t st);
 // dst row ((r / ib) * mul + sel) * ib + r % ib  <-  src row r   (rows of `cols` elements)
 hipError_t launch_pack_rows(int dtype, const void* src, void* dst, int rows, int cols, int ib, int mul, int sel,
-                            hipStream_t st);
+                            long long* counters, hipStream_t st);
 
 // ---- MFMA paths (bf16) ----
 bool gemm_mfma_supported(const hr_model_cfg& c);

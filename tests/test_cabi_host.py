@@ -37,11 +37,11 @@ def test_status_strings_are_distinct():
 
 def test_pool_bytes_and_cfg_validation():
     cfg = hb.make_pool_cfg(24, 2, 64, 20480, "bf16")
-    # [layer][page][kv head][K|V][16][d] bf16
-    assert hb.hr_kv_pool_bytes(cfg) == 24 * 20480 * 2 * 2 * 16 * 64 * 2
+    # [layer][page][kv head][K|V][16][d] bf16, then 256 bytes of range counters
+    assert hb.hr_kv_pool_bytes(cfg) == 24 * 20480 * 2 * 2 * 16 * 64 * 2 + 256
     cfg8 = hb.make_pool_cfg(32, 8, 128, 100, "fp8")
     data = 32 * 100 * 8 * 2 * 16 * 128
-    assert hb.hr_kv_pool_bytes(cfg8) == data + 32 * 100 * 8 * 2 * 4
+    assert hb.hr_kv_pool_bytes(cfg8) == data + 32 * 100 * 8 * 2 * 4 + 256
     for bad in (dict(head_dim=60), dict(head_dim=0), dict(num_pages=0), dict(n_layers=0), dict(kv_dtype=7), dict(page_tokens=32)):
         c = hb.make_pool_cfg(2, 2, 64, 8, "f32")
         for k, v in bad.items():

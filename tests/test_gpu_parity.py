@@ -166,6 +166,82 @@ def test_split_operand_layers_score_an_order_of_magnitude_closer_to_the_oracle(d
         case.close()
 
 
+def test_range_reports_count_what_half_and_e4m3_cannot_hold():
+    """The caller's bf16 weights and K/V become halves once; what does not fit is counted, and a value that overflowed
+    makes the scores that depend on it non-finite instead of silently wrong."""
+    import torch
+    model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=4, n_kv=2, d=64, ffn=320, vocab=500)
+
+    class Doctored:
+        def __init__(self, base, edits):
+            self.base, self.edits = base, edits
+
+        def get(self, kind, layer=-1):
+            a = self.base.get(kind, layer)
+            if (kind, layer) in self.edits:
+                a = a.copy()
+                for idx, val in self.edits[(kind, layer)]:
+                    a[idx] = val
+            return a
+
+    base = wlmod.SeededWeights(model, seed=18, std=0.05)
+    cfg = wlmod.WorkloadCfg("range", model, 1, 3, 40, 8, "bf16", seed=9)
+    wl = wlmod.make_workload(cfg)
+    clean = H.Case(wl, base)
+    try:
+        clean.fill_synthetic(oracle_doc_ids=[])
+        rep = clean.model.range_report()
+        assert rep["overflow"] == 0 and rep["nonfinite_inputs"] == 0 and rep["fp8_nan_codes"] == 0
+        inexact_clean = rep["underflow"]
+        assert clean.pool.range_report() == dict(overflow=0, underflow=clean.pool.range_report()["underflow"], nonfinite_inputs=0,
+                                                 fp8_nan_codes=0, fp8_bad_scales=0)
+        assert np.all(np.isfinite(clean.gpu_scores()))
+    finally:
+        clean.close()
+    w = Doctored(base, {("wd", 0): [((3, 5), 1.0e6), ((4, 6), 2.0 ** -30)], ("wq", 1): [((0, 0), float("nan"))]})
+    case = H.Case(wl, w)
+    try:
+        rep = case.model.range_report()
+        assert rep["overflow"] == 1 and rep["nonfinite_inputs"] == 1 and rep["underflow"] >= inexact_clean
+        case.fill_synthetic(oracle_doc_ids=[])
+        assert not np.any(np.isfinite(case.gpu_scores()))
+    finally:
+        case.close()
+    # clean weights, one document with a V value beyond the half range: counted, and only that pair's score is lost
+    case = H.Case(wl, base)
+    try:
+        kv = wlmod.synthetic_doc_kv(wl, 0, "cuda:0")
+        kv["v"][1, 7, 0, 3] = 7.0e4
+        case.pool.write(40, wl.pool_doc_pages[0], kv["k"], kv["v"])
+        for d in (1, 2):
+            kv = wlmod.synthetic_doc_kv(wl, d, "cuda:0")
+            case.pool.write(40, wl.pool_doc_pages[d], kv["k"], kv["v"])
+        rep = case.pool.range_report()
+        assert rep["overflow"] == 1 and rep["nonfinite_inputs"] == 0
+        got = case.gpu_scores()
+        assert not np.isfinite(got[0]) and np.all(np.isfinite(got[1:]))
+    finally:
+        case.close()
+    # fp8 pool: NaN codes and scales the expansion cannot apply
+    cfg8 = wlmod.WorkloadCfg("range8", model, 1, 2, 40, 8, "fp8", seed=9)
+    wl8 = wlmod.make_workload(cfg8)
+    case = H.Case(wl8, base)
+    try:
+        kv = wlmod.synthetic_doc_kv(wl8, 0, "cuda:0")
+        kv["k"][0, 0, 0, 0] = 0x7F
+        kv["v"][1, 2, 1, 5] = 0xFF
+        kv["k_scale"][0, 0, 0] = 0.0
+        kv["v_scale"][1, 1, 1] = 300.0
+        case.pool.write(40, wl8.pool_doc_pages[0], kv["k"], kv["v"], kv["k_scale"], kv["v_scale"])
+        kv = wlmod.synthetic_doc_kv(wl8, 1, "cuda:0")
+        case.pool.write(40, wl8.pool_doc_pages[1], kv["k"], kv["v"], kv["k_scale"], kv["v_scale"])
+        torch.cuda.synchronize()
+        rep = case.pool.range_report()
+        assert rep["fp8_nan_codes"] == 2 and rep["fp8_bad_scales"] == 2 and rep["overflow"] == 0
+    finally:
+        case.close()
+
+
 def test_fp8_pool_small_model():
     model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=8, n_kv=2, d=32, ffn=352)
     cfg = wlmod.WorkloadCfg("fp8_small", model, 2, 4, (20, 90), (3, 12), "fp8", seed=5)
