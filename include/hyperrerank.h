@@ -257,6 +257,9 @@ size_t hr_rerank_workspace_bytes(const hr_model* model, int32_t n_pairs, int64_t
  * Pairs of one call whose doc_lens and page-table rows are identical (the same cached document: Section 3.3,
  * pairwise independence makes a document's KV reusable for every query) share one pass over its pages in the
  * attention kernels; the scores are bit for bit those of the pairs scored alone.
+ * Pairs of one call with identical query token strings (the same query against several candidates) share the first
+ * layer's normalised rows and pre-RoPE q / k / v projections, which are equal for equal strings; each pair's rotation for
+ * its own positions doc_lens[p] + i is applied afterwards.  Same bits again.
  * A call with at least 8192 query tokens on the MFMA path whose O / down projection tiles would leave more than 15 % of
  * the device's workgroup slots empty in the rounds they take runs as two halves of the pairs, the first on `stream`,
  * the second on a stream of the library's own that starts behind the work already enqueued on `stream` and that
@@ -397,6 +400,7 @@ const char* hr_gemm_path(const hr_model* model);
  *   HR_FORCE_GENERIC=1      every step on the generic fp32-arithmetic kernels
  *   HR_NO_LAST_SHORTCUT=1   the last layer runs on every token instead of each pair's last one
  *   HR_NO_DOC_GROUPS=1      pairs that share a document are not batched into one attention work item
+ *   HR_NO_QUERY_SHARING=1   the first layer's projections are computed for every pair instead of once per distinct query
  *   HR_STREAMS=1            the initial value of hr_rerank_set_streams is 1
  * and one that does change results (within the tolerance): HR_PRECISE_LAYERS=n, the initial value of
  * hr_model_set_precise_layers. */

@@ -46,6 +46,11 @@ __device__ __forceinline__ float e4m3_to_float(uint8_t c) {
     return __uint_as_float(__float_as_uint(mag) | sign);
 }
 
+// Rotate-half RoPE of one channel pair (x1 at index j, x2 at j + d/2) with explicit roundings, so that every kernel
+// that applies it (the fused projection epilogue and the stand-alone RoPE kernels) produces the same bits.
+__device__ __forceinline__ float rope_lo(float x1, float x2, float c, float s) { return __fmaf_rn(x1, c, -__fmul_rn(x2, s)); }
+__device__ __forceinline__ float rope_hi(float x1, float x2, float c, float s) { return __fmaf_rn(x2, c, __fmul_rn(x1, s)); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);

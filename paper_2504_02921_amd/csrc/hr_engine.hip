@@ -27,6 +27,7 @@ struct hr_model {
     bool prof_on = false;
     bool no_last_short = false;           // HR_NO_LAST_SHORTCUT=1: run the last layer on every token (A/B runs)
     bool no_doc_groups = false;           // HR_NO_DOC_GROUPS=1: pairs that share a document are not batched (A/B runs)
+    bool no_query_share = false;          // HR_NO_QUERY_SHARING=1: the first layer's projections are computed per pair (A/B runs)
     int n_streams = 2;                    // a large scoring call runs as two halves on two streams (hr_rerank_set_streams)
     hipStream_t aux_stream = nullptr;     // the second one, created on first use
     hipEvent_t fork_ev = nullptr, join_ev = nullptr;
@@ -238,6 +239,7 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
     // deep, wide model (the residual stream is still small there, and everything downstream amplifies it).
     const int n_prec = (mfma_attn && m->mfma_gemm && pool && !fill && !self_prefix) ? std::min(n_precise, c.n_layers) : 0;
     void* kvlo = wsb + ws.off_kvlo;
+    const bool share0 = mfma_attn && m->mfma_gemm && pool && !fill && !self_prefix && mv.tok_src && mv.n_uniq > 0;
     const bool last_short = !m->no_last_short && mfma_attn && m->mfma_gemm && !fill && !self_prefix && mv.n_out == mv.n_seq &&
                             T > mv.n_seq && (size_t)T * nq * dtype_size(dt) >= (size_t)mv.n_seq * H * sizeof(float) && H % 4 == 0 &&
                             n_prec < c.n_layers;
@@ -249,15 +251,22 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
     HR_TIMED(PC_EMBED, launch_embed(dt, m->embedding, mv, x, H, st));
     HR_TIMED(PC_EMBED, launch_rope_table(mv, rope, d, c.rope_base, st));
     for (int l = 0; l < c.n_layers; ++l) {
+        // First layer, several sequences with the same token string (one query against its candidates): the normalised
+        // rows and the pre-RoPE q / k / v of equal strings are equal, so they are computed on the distinct rows only and
+        // every token takes its row, rotated for its own position (exact: same bits as computing every row).
+        const bool shared0 = l == 0 && share0;
+        const int64_t Tq = shared0 ? mv.n_uniq : T;                   // rows of this layer's first norm and QKV projection
+        const int32_t* rows0 = shared0 ? mv.rep_row : nullptr;
+        const int32_t* src0 = shared0 ? mv.tok_src : nullptr;
         if (l < n_prec) {
-            HR_TIMED(PC_RMSNORM, launch_rmsnorm_split(x, m->norm1[l], y, T, H, c.rms_eps, st));
+            HR_TIMED(PC_RMSNORM, launch_rmsnorm_split(x, m->norm1[l], y, Tq, H, c.rms_eps, st, rows0));
             // the projection leaves fp32 rows (x += C on a cleared buffer); RoPE, the hi / lo split and the page scatter
             // are a kernel of their own
-            HR_TIMED(PC_ELEMENTWISE, launch_fill_zero(f32, (size_t)T * nqkv * sizeof(float), st));
+            HR_TIMED(PC_ELEMENTWISE, launch_fill_zero(f32, (size_t)Tq * nqkv * sizeof(float), st));
             GemmArgs a{};
-            a.A = y; a.W = layer_w(m, l, m->pack.wqkv); a.M = T; a.N = nqkv; a.K = 2 * H; a.Kw = H; a.x = f32;
+            a.A = y; a.W = layer_w(m, l, m->pack.wqkv); a.M = Tq; a.N = nqkv; a.K = 2 * H; a.Kw = H; a.x = f32;
             HR_TIMED(PC_GEMM_QKV, launch_gemm_mfma(EPI_RESID_ADD, a, st));
-            HR_TIMED(PC_ELEMENTWISE, launch_rope_pages_split(f32, rope, q, k, kvlo, mv.new_slot, T, c.n_q_heads, c.n_kv_heads, d, st));
+            HR_TIMED(PC_ELEMENTWISE, launch_rope_pages(f32, rope, q, k, kvlo, mv.new_slot, src0, T, c.n_q_heads, c.n_kv_heads, d, st));
             if (l == 0 && after_qkv0) HR_HIP(hipEventRecord(after_qkv0, st));
             HR_TIMED(PC_ATTENTION, launch_attn_mfma(q, k, o, mv, pv, l, c.n_q_heads, max_new_len, st, false, groups, kvlo));
             GemmArgs b{};
@@ -272,8 +281,14 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
             HR_TIMED(PC_GEMM_DOWN, launch_gemm_mfma(EPI_RESID_ADD, dn, st));
             continue;
         }
-        HR_TIMED(PC_RMSNORM, launch_rmsnorm(dt, x, m->norm1[l], y, T, H, c.rms_eps, st));
-        if (m->mfma_gemm) {
+        HR_TIMED(PC_RMSNORM, launch_rmsnorm(dt, x, m->norm1[l], y, Tq, H, c.rms_eps, st, rows0));
+        if (shared0) {
+            HR_TIMED(PC_ELEMENTWISE, launch_fill_zero(f32, (size_t)Tq * nqkv * sizeof(float), st));
+            GemmArgs a{};
+            a.A = y; a.W = layer_w(m, l, m->pack.wqkv); a.M = Tq; a.N = nqkv; a.K = H; a.x = f32;
+            HR_TIMED(PC_GEMM_QKV, launch_gemm_mfma(EPI_RESID_ADD, a, st));
+            HR_TIMED(PC_ELEMENTWISE, launch_rope_pages(f32, rope, q, k, nullptr, mv.new_slot, src0, T, c.n_q_heads, c.n_kv_heads, d, st));
+        } else if (m->mfma_gemm) {
             GemmArgs a{};
             a.A = y; a.W = layer_w(m, l, m->pack.wqkv); a.M = T; a.N = nqkv; a.K = H;
             a.out0 = q; a.out1 = k; a.out2 = v; a.rope = rope; a.n_q = c.n_q_heads; a.n_kv = c.n_kv_heads; a.d = d;
@@ -417,6 +432,8 @@ int hr_weights_load(const hr_model_cfg* cfg, const hr_weight_ptrs* w, void* pack
     m->no_last_short = nls && nls[0] == '1';
     const char* ndg = getenv("HR_NO_DOC_GROUPS");
     m->no_doc_groups = ndg && ndg[0] == '1';
+    const char* nqs = getenv("HR_NO_QUERY_SHARING");
+    m->no_query_share = nqs && nqs[0] == '1';
     const char* ns = getenv("HR_STREAMS");               // "1": scoring calls stay on the caller's stream (profiling runs)
     if (ns && ns[0] == '1') m->n_streams = 1;
     m->n_precise = default_precise_layers(*cfg, m->mfma_gemm);
@@ -576,7 +593,7 @@ size_t hr_rerank_workspace_bytes(const hr_model* m, int32_t n_pairs, int64_t tot
     // + room for the per-part alignment when the call runs as two halves (each with its own carving)
     return hr::make_workspace(m->cfg, n_pairs, total_q_tokens, pt_stride, !m->mfma_gemm, -1, 0,
                               (int64_t)hr::group_plan_ints_bound(n_pairs, total_q_tokens, m->cfg.n_q_heads / m->cfg.n_kv_heads),
-                              m->n_precise > 0)
+                              m->n_precise > 0, m->mfma_gemm)
                .total + (m->mfma_gemm ? kSplitSlackBytes : 0);
 }
 
@@ -628,9 +645,25 @@ static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_
             gv.sub_key0 = dv;
         }
     }
+    // sequences with the same token string share the first layer's normalised rows and projections, where that at least
+    // halves the rows (the shared rows take the y and fp32 buffers)
+    int64_t n_uniq = 0;
+    if (mfma_attn && !m->no_query_share && ml.rep_row > ml.tok_src && n_pairs >= 2) {
+        const hr::QueryShare qs = hr::make_query_share(n_pairs, query_lens, query_tokens);
+        if (qs.n_uniq * 2 <= T) {
+            std::memcpy(stage + ml.tok_src, qs.tok_src.data(), sizeof(int32_t) * qs.tok_src.size());
+            std::memcpy(stage + ml.rep_row, qs.rep_row.data(), sizeof(int32_t) * qs.rep_row.size());
+            n_uniq = qs.n_uniq;
+        }
+    }
     HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, stage, (ml.grp + plan_ints) * sizeof(int32_t), hipMemcpyHostToDevice, st));
     for (int32_t p = 0; p < n_pairs; ++p) out->max_keys = std::max(out->max_keys, doc_lens[p] + query_lens[p]);
     out->mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, n_pairs, T, pt_stride);
+    if (n_uniq > 0) {
+        out->mv.tok_src = (const int32_t*)(wsb + ws.off_meta) + ml.tok_src;
+        out->mv.rep_row = (const int32_t*)(wsb + ws.off_meta) + ml.rep_row;
+        out->mv.n_uniq = (int32_t)n_uniq;
+    }
     return HR_OK;
 }
 
@@ -645,7 +678,7 @@ static int score_one_piece(hr_model* m, const hr_pool* pool, int32_t n_pairs, co
                            const int32_t* doc_lens, const int32_t* query_tokens, const int32_t* query_lens, int64_t T, bool mfma_attn,
                            int max_q, const hr::Workspace& ws, int64_t grp_ints, char* wsb, float* scores_dev, hipStream_t st,
                            bool staging_may_grow) {
-    const hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, pt_stride, -1, 0, grp_ints);
+    const hr::MetaLayout ml = hr::make_meta_layout(n_pairs, T, pt_stride, -1, 0, grp_ints, m->mfma_gemm);
     int rc = stage_reserve(m, ml.total, staging_may_grow);
     if (rc != HR_OK) return rc;
     ScorePart part;
@@ -674,7 +707,7 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     if ((uintptr_t)workspace_dev % hr::kAlign != 0) return HR_ERR_INVALID_ARG;
     const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     const int64_t grp_ints = (int64_t)hr::group_plan_ints_bound(n_pairs, T, g);
-    const hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints, m->n_precise > 0);
+    const hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints, m->n_precise > 0, m->mfma_gemm);
     if (workspace_bytes < ws.total) return HR_ERR_WORKSPACE_SMALL;
     hipStream_t st = (hipStream_t)stream;
     char* wsb = (char*)workspace_dev;
@@ -704,11 +737,11 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
         const int32_t n_b = n_pairs - n_a;
         const int64_t T_b = T - T_a;
         const int64_t gi_a = (int64_t)hr::group_plan_ints_bound(n_a, T_a, g), gi_b = (int64_t)hr::group_plan_ints_bound(n_b, T_b, g);
-        const hr::Workspace ws_a = hr::make_workspace(m->cfg, n_a, T_a, pt_stride, false, -1, 0, gi_a, m->n_precise > 0);
-        const hr::Workspace ws_b = hr::make_workspace(m->cfg, n_b, T_b, pt_stride, false, -1, 0, gi_b, m->n_precise > 0);
+        const hr::Workspace ws_a = hr::make_workspace(m->cfg, n_a, T_a, pt_stride, false, -1, 0, gi_a, m->n_precise > 0, true);
+        const hr::Workspace ws_b = hr::make_workspace(m->cfg, n_b, T_b, pt_stride, false, -1, 0, gi_b, m->n_precise > 0, true);
         if (ws_a.total + ws_b.total <= workspace_bytes) {
-            const hr::MetaLayout ml_a = hr::make_meta_layout(n_a, T_a, pt_stride, -1, 0, gi_a);
-            const hr::MetaLayout ml_b = hr::make_meta_layout(n_b, T_b, pt_stride, -1, 0, gi_b);
+            const hr::MetaLayout ml_a = hr::make_meta_layout(n_a, T_a, pt_stride, -1, 0, gi_a, true);
+            const hr::MetaLayout ml_b = hr::make_meta_layout(n_b, T_b, pt_stride, -1, 0, gi_b, true);
             rc = stage_reserve(m, ml_a.total + ml_b.total);
             if (rc != HR_OK) return rc;
             if (!m->aux_stream) {
@@ -762,7 +795,7 @@ int hr_rerank_score_static(hr_model* m, const hr_pool* pool, int32_t n_pairs, co
     if (!scores_dev) return HR_ERR_INVALID_ARG;
     const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     const int64_t grp_ints = (int64_t)hr::group_plan_ints_bound(n_pairs, T, g);
-    const hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints, m->n_precise > 0);
+    const hr::Workspace ws = hr::make_workspace(m->cfg, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, grp_ints, m->n_precise > 0, m->mfma_gemm);
     if (ws.total > kStaticScratchBytes) {
         snprintf(g_last_error, sizeof(g_last_error), "hr_rerank_score_static: this call needs %zu bytes of scratch, the static array holds %zu",
                  ws.total, kStaticScratchBytes);

@@ -293,8 +293,8 @@ __device__ __forceinline__ void gemm_epilogue(floatx16 (&acc)[BM / WM / 32][BN /
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
                             const float lo = acc[i][jl][r4 * 4 + e], hi = acc[i][jh][r4 * 4 + e];
-                            wl[e] = from_float<half_t>(rot ? lo * cs_c[e] - hi * cs_s[e] : lo);
-                            wh[e] = from_float<half_t>(rot ? hi * cs_c[e] + lo * cs_s[e] : hi);
+                            wl[e] = from_float<half_t>(rot ? rope_lo(lo, hi, cs_c[e], cs_s[e]) : lo);
+                            wh[e] = from_float<half_t>(rot ? rope_hi(lo, hi, cs_c[e], cs_s[e]) : hi);
                         }
                         res[i][jl][r4] = wl;
                         res[i][jh][r4] = wh;

@@ -62,7 +62,7 @@ PackLayout make_pack_layout(const hr_model_cfg& c) {
     return p;
 }
 
-MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t n_out, int64_t dst_ints, int64_t grp_ints) {
+MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t n_out, int64_t dst_ints, int64_t grp_ints, bool share) {
     if (n_out < 0) n_out = n_seq;
     MetaLayout m;
     auto up = [](size_t e) { return (e + 63) / 64 * 64; };
@@ -77,13 +77,15 @@ MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t
     m.new_cu = o;      o = up(o + (size_t)n_seq + 1);
     m.out_row = o;     o = up(o + (size_t)n_out);
     m.dst_table = o;   o = up(o + (size_t)dst_ints);
+    m.tok_src = o;     o = up(o + (share ? (size_t)T : 0));
+    m.rep_row = o;     o = up(o + (share ? (size_t)T / 2 + 1 : 0));
     m.grp = o;         o = up(o + (size_t)grp_ints);
     m.total = o;
     return m;
 }
 
 Workspace make_workspace(const hr_model_cfg& c, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch,
-                         int64_t n_out, int64_t dst_ints, int64_t grp_ints, bool split_ops) {
+                         int64_t n_out, int64_t dst_ints, int64_t grp_ints, bool split_ops, bool share) {
     Workspace w;
     size_t asz = dtype_size(c.dtype);
     size_t H = c.hidden, d = c.head_dim, F = c.ffn;
@@ -93,7 +95,7 @@ Workspace make_workspace(const hr_model_cfg& c, int64_t n_seq, int64_t T, int64_
     // twice the room, the new tokens' K/V pages get a second buffer for their rounding residue, and the QKV projection of
     // those layers leaves fp32 rows for a RoPE kernel of its own
     const size_t sp = split_ops ? 2 : 1;
-    MetaLayout ml = make_meta_layout(n_seq, T, pt_stride, n_out, dst_ints, grp_ints);
+    MetaLayout ml = make_meta_layout(n_seq, T, pt_stride, n_out, dst_ints, grp_ints, share);
     w.meta_ints = ml.total;
     size_t o = 0;
     w.off_meta = o; o = align_up(o + ml.total * sizeof(int32_t));
@@ -113,6 +115,7 @@ Workspace make_workspace(const hr_model_cfg& c, int64_t n_seq, int64_t T, int64_
     w.off_f32 = o;
     if (need_f32_scratch) o = align_up(o + t * std::max(nq + 2 * nkv, 2 * F) * sizeof(float));
     else if (split_ops) o = align_up(o + t * (nq + 2 * nkv) * sizeof(float));
+    else if (share) o = align_up(o + (t / 2 + 1) * (nq + 2 * nkv) * sizeof(float));     // shared first-layer rows: at most T / 2
     w.total = o;
     return w;
 }
@@ -255,6 +258,53 @@ void fill_meta(int32_t* meta, const MetaLayout& ml, int64_t n_seq, const int32_t
     }
     if (page_table && pt_stride > 0)
         std::memcpy(meta + ml.page_table, page_table, sizeof(int32_t) * (size_t)n_seq * (size_t)pt_stride);
+}
+
+QueryShare make_query_share(int64_t n_seq, const int32_t* new_lens, const int32_t* tokens) {
+    QueryShare qs;
+    std::vector<int64_t> start((size_t)n_seq + 1, 0);
+    for (int64_t p = 0; p < n_seq; ++p) start[p + 1] = start[p] + new_lens[p];
+    qs.tok_src.resize((size_t)start[n_seq]);
+    // sequences in the order (length, hash of the string, index); equal strings end up next to each other and are told
+    // apart from mere hash collisions by comparing the tokens
+    std::vector<uint64_t> hash((size_t)n_seq);
+    for (int64_t p = 0; p < n_seq; ++p) {
+        uint64_t h = 1469598103934665603ull;
+        for (int64_t t = start[p]; t < start[p + 1]; ++t) h = (h ^ (uint32_t)tokens[t]) * 1099511628211ull;
+        hash[p] = h;
+    }
+    std::vector<int32_t> order((size_t)n_seq);
+    for (int64_t p = 0; p < n_seq; ++p) order[p] = (int32_t)p;
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (new_lens[a] != new_lens[b]) return new_lens[a] < new_lens[b];
+        if (hash[a] != hash[b]) return hash[a] < hash[b];
+        return a < b;
+    });
+    std::vector<int32_t> leader((size_t)n_seq, -1);          // first sequence (lowest index) with the same string
+    for (int64_t i = 0; i < n_seq;) {
+        int64_t j = i;
+        while (j < n_seq && new_lens[order[j]] == new_lens[order[i]] && hash[order[j]] == hash[order[i]]) ++j;
+        for (int64_t a = i; a < j; ++a) {
+            if (leader[order[a]] >= 0) continue;
+            leader[order[a]] = order[a];
+            for (int64_t b = a + 1; b < j; ++b)
+                if (leader[order[b]] < 0 && std::memcmp(tokens + start[order[a]], tokens + start[order[b]],
+                                                        sizeof(int32_t) * (size_t)new_lens[order[a]]) == 0)
+                    leader[order[b]] = order[a];
+        }
+        i = j;
+    }
+    std::vector<int64_t> first_row((size_t)n_seq, -1);       // unique row of a leader's first token
+    for (int64_t p = 0; p < n_seq; ++p) {
+        const int32_t ld = leader[p];
+        if (ld == p) {
+            first_row[p] = qs.n_uniq;
+            for (int64_t t = start[p]; t < start[p + 1]; ++t) qs.rep_row.push_back((int32_t)t);
+            qs.n_uniq += new_lens[p];
+        }
+        for (int64_t i = 0; i < new_lens[p]; ++i) qs.tok_src[start[p] + i] = (int32_t)(first_row[ld] + i);
+    }
+    return qs;
 }
 
 ChunkPlan make_chunk_plan(int64_t n_seq, const int32_t* lens, int chunk) {

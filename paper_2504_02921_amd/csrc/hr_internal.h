@@ -63,19 +63,20 @@ struct Workspace {
 // full_path: sequences carry their own document tokens (no page table).
 // split_ops: room for the layers that run with split (hi + lo) operands
 Workspace make_workspace(const hr_model_cfg& cfg, int64_t n_seq, int64_t T, int64_t pt_stride, bool need_f32_scratch,
-                         int64_t n_out = -1, int64_t dst_ints = 0, int64_t grp_ints = 0, bool split_ops = false);
+                         int64_t n_out = -1, int64_t dst_ints = 0, int64_t grp_ints = 0, bool split_ops = false, bool share = false);
 
 // Metadata block layout (int32 offsets inside the block), uploaded once per call.
 // new_slot[t] / new_cu[p]: where the K/V of new token t goes when the new keys are kept as 16-token
 // pages per sequence (each sequence starts on a 32-slot boundary so that MFMA sub-tiles are whole).
 struct MetaLayout {
     size_t cu = 0, tok_id = 0, tok_pos = 0, tok_seq = 0, prefix_len = 0, page_table = 0, new_slot = 0, new_cu = 0, out_row = 0,
-           dst_table = 0, grp = 0, total = 0;
+           dst_table = 0, tok_src = 0, rep_row = 0, grp = 0, total = 0;
 };
 // n_out: rows whose score is read (one per pair); dst_ints: extra table for the prefill target pages; grp_ints: room
 // for a group plan (group_plan_ints_bound)
+// share: room for the tables of sequences with identical token strings (tok_src [T], rep_row [T / 2 + 1])
 MetaLayout make_meta_layout(int64_t n_seq, int64_t T, int64_t pt_stride, int64_t n_out = -1, int64_t dst_ints = 0,
-                            int64_t grp_ints = 0);
+                            int64_t grp_ints = 0, bool share = false);
 
 }  // namespace hr
 
@@ -106,6 +107,16 @@ int score_check_args(const hr_model_cfg& mc, const hr_pool* pool, int32_t n_pair
 void fill_meta(int32_t* meta, const MetaLayout& ml, int64_t n_seq, const int32_t* prefix_lens,
                const int32_t* new_lens, const int32_t* tokens, const int32_t* page_table, int64_t pt_stride,
                const int32_t* out_rows = nullptr, int64_t n_out = 0);
+
+// Sequences with identical new-token strings (the same query scored against several documents: Section 3.3, pairwise
+// independence) have identical embeddings and, in the first layer, identical normalised rows and pre-RoPE q / k / v: those
+// are computed once per distinct string.  rep_row[u] = a token row in [0, T) that carries unique row u's token;
+// tok_src[t] = the unique row of token t.
+struct QueryShare {
+    std::vector<int32_t> rep_row, tok_src;
+    int64_t n_uniq = 0;
+};
+QueryShare make_query_share(int64_t n_seq, const int32_t* new_lens, const int32_t* tokens);
 
 // A long sequence run as chunks of at most `chunk` tokens: chunk c of a sequence is a pseudo-sequence whose
 // prefix is the sequence's own earlier tokens, found as pages of the call's new-token K/V buffer.  Used by the

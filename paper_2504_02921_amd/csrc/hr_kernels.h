@@ -27,6 +27,11 @@ struct MetaView {
     const int32_t* new_slot;    // [T] slot of each new token in the paged new-KV buffer
     const int32_t* new_cu;      // [n_seq + 1] first slot of each sequence (multiples of 32)
     const int32_t* out_row;     // [n_out] token row whose score is read
+    // sequences with identical token strings (set when at most half of the token rows are distinct): token t's first-layer
+    // projection is row tok_src[t] of n_uniq shared rows, and rep_row[u] is a token row that carries shared row u's token
+    const int32_t* tok_src;
+    const int32_t* rep_row;
+    int32_t n_uniq;
     int32_t n_out;
     int32_t pt_stride;
     int32_t n_seq;
@@ -36,12 +41,16 @@ struct MetaView {
 // ---- generic (any shape, VALU arithmetic in fp32) ----
 hipError_t launch_embed(int dtype, const void* E, const MetaView& mv, float* x, int H, hipStream_t st);
 hipError_t launch_rope_table(const MetaView& mv, float2* tab, int head_dim, float base, hipStream_t st);
-hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st);
+// rows: optional gather (device array of T row indices into x): y row t <- x row rows[t]
+hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st,
+                          const int32_t* rows = nullptr);
 // 22-bit operand form (16-bit models): y as [T][hi H | lo H] halves
-hipError_t launch_rmsnorm_split(const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st);
-// fp32 qkv [T][(n_q + 2 n_kv) d] -> RoPE -> q as [T][hi | lo] halves, new K/V as pages in kv_hi and their rounding residue in kv_lo
-hipError_t launch_rope_pages_split(const float* qkv, const float2* tab, void* q, void* kv_hi, void* kv_lo, const int32_t* new_slot,
-                                   int64_t T, int n_q, int n_kv, int d, hipStream_t st);
+hipError_t launch_rmsnorm_split(const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st,
+                                const int32_t* rows = nullptr);
+// fp32 qkv rows -> RoPE -> q and the new tokens' K/V as pages.  kv_lo != nullptr: the split form (q as [T][hi | lo] halves,
+// the rounding residue of K/V in kv_lo).  tok_src != nullptr: token t reads qkv row tok_src[t] instead of row t.
+hipError_t launch_rope_pages(const float* qkv, const float2* tab, void* q, void* kv_hi, void* kv_lo, const int32_t* new_slot,
+                             const int32_t* tok_src, int64_t T, int n_q, int n_kv, int d, hipStream_t st);
 // C[M][N] (+)= A[M][K] * W[N][K]^T, C fp32
 hipError_t launch_gemm_generic(int dtype, const void* A, const void* W, float* C, int64_t M, int N, int K,
                                bool accumulate, hipStream_t st);

@@ -62,12 +62,13 @@ __device__ __forceinline__ float block_max_256(float v, float* red) {
     return r;
 }
 
+// rows: optional gather, y row t <- x row rows[t]
 template <typename T>
 __global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                      T* __restrict__ y, int H, float eps) {
+                                                      T* __restrict__ y, int H, float eps, const int32_t* __restrict__ rows) {
     __shared__ float red[4];
     size_t t = blockIdx.x;
-    const float* xr = x + t * H;
+    const float* xr = x + (rows ? (size_t)rows[t] : t) * H;
     float ss = 0.f;
     for (int c = threadIdx.x; c < H; c += 256) { float v = xr[c]; ss += v * v; }
     ss = block_sum_256(ss, red);
@@ -80,10 +81,10 @@ __global__ void __launch_bounds__(256) rmsnorm_kernel(const float* __restrict__ 
 // reduction and the scaling (one pass over HBM), 16-byte loads, 8-byte stores.
 template <int VPT>
 __global__ void __launch_bounds__(256) rmsnorm_vec_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                          half_t* __restrict__ y, int H, float eps) {
+                                                          half_t* __restrict__ y, int H, float eps, const int32_t* __restrict__ rows) {
     __shared__ float red[4];
     const size_t t = blockIdx.x;
-    const float4* xr = (const float4*)(x + t * H);
+    const float4* xr = (const float4*)(x + (rows ? (size_t)rows[t] : t) * H);
     const float4* gr = (const float4*)gain;
     const int n4 = H >> 2;
     float4 v[VPT];
@@ -115,10 +116,10 @@ __global__ void __launch_bounds__(256) rmsnorm_vec_kernel(const float* __restric
 
 // Split form for the layers that run with 22-bit operands: y = hi + lo, written as [T][hi H | lo H] halves.
 __global__ void __launch_bounds__(256) rmsnorm_split_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                            half_t* __restrict__ y, int H, float eps) {
+                                                            half_t* __restrict__ y, int H, float eps, const int32_t* __restrict__ rows) {
     __shared__ float red[4];
     const size_t t = blockIdx.x;
-    const float* xr = x + t * H;
+    const float* xr = x + (rows ? (size_t)rows[t] : t) * H;
     float ss = 0.f;
     for (int c = threadIdx.x; c < H; c += 256) { const float v = xr[c]; ss += v * v; }
     ss = block_sum_256(ss, red);
@@ -207,41 +208,49 @@ __global__ void rope_split_kernel(const float* __restrict__ qkv, const float2* _
     for (int idx = threadIdx.x; idx < n_kv * d; idx += blockDim.x) v[t * n_kv * d + idx] = from_float<T>(vr[idx]);
 }
 
-// The same step for the layers that run with 22-bit operands, behind an MFMA projection that left fp32 qkv:
-// q goes out as [T][hi n_q d | lo n_q d] halves, and the new tokens' K and V as 16-slot pages in the pool arrangement
-// (token t at slot new_slot[t]) twice over: the values rounded to half in kv_hi, what the rounding left out in kv_lo.
-__global__ void rope_pages_split_kernel(const float* __restrict__ qkv, const float2* __restrict__ tab, half_t* __restrict__ q,
-                                        half_t* __restrict__ kv_hi, half_t* __restrict__ kv_lo, const int32_t* __restrict__ new_slot,
-                                        int n_q, int n_kv, int d) {
+// The same step behind an MFMA projection that left fp32 rows, with the new tokens' K and V written as 16-slot pages in
+// the pool arrangement (token t at slot new_slot[t]).  Used where the projection's fused epilogue cannot be:
+//   SPLIT   the layers that run with 22-bit operands: q goes out as [T][hi n_q d | lo n_q d] halves, and K / V twice
+//           over: the values rounded to half in kv_hi, what the rounding left out in kv_lo;
+//   tok_src the first layer when several sequences carry the same token string: token t takes row tok_src[t] of a
+//           projection that was computed once per distinct string (its own position's rotation still applies).
+template <bool SPLIT>
+__global__ void rope_pages_kernel(const float* __restrict__ qkv, const float2* __restrict__ tab, half_t* __restrict__ q,
+                                  half_t* __restrict__ kv_hi, half_t* __restrict__ kv_lo, const int32_t* __restrict__ new_slot,
+                                  const int32_t* __restrict__ tok_src, int n_q, int n_kv, int d) {
     const size_t t = blockIdx.x;
     const int half = d / 2;
     const int nqkv = (n_q + 2 * n_kv) * d;
-    const float* row = qkv + t * nqkv;
+    const float* row = qkv + (tok_src ? (size_t)tok_src[t] : t) * nqkv;
     const float2* tr = tab + t * half;
     const int slot = new_slot[t];
     const size_t page_elems = (size_t)2 * kPageTokens * d;          // K block | V block of one (page, kv head)
     const int ts = slot & 15;
     const int rot_heads = n_q + n_kv;
+    const size_t q_ld = (size_t)(SPLIT ? 2 : 1) * n_q * d;
     for (int idx = threadIdx.x; idx < rot_heads * half; idx += blockDim.x) {
         const int hd = idx / half, j = idx - hd * half;
         const float x1 = row[hd * d + j], x2 = row[hd * d + j + half];
         const float2 cs = tr[j];
-        const float o1 = x1 * cs.x - x2 * cs.y;
-        const float o2 = x2 * cs.x + x1 * cs.y;
+        const float o1 = rope_lo(x1, x2, cs.x, cs.y);
+        const float o2 = rope_hi(x1, x2, cs.x, cs.y);
         const half_t h1 = from_float<half_t>(o1), h2 = from_float<half_t>(o2);
-        const half_t l1 = from_float<half_t>(o1 - (float)h1), l2 = from_float<half_t>(o2 - (float)h2);
         if (hd < n_q) {
-            half_t* dst = q + t * 2 * n_q * d + (size_t)hd * d;
+            half_t* dst = q + t * q_ld + (size_t)hd * d;
             dst[j] = h1;
             dst[j + half] = h2;
-            dst[(size_t)n_q * d + j] = l1;
-            dst[(size_t)n_q * d + j + half] = l2;
+            if constexpr (SPLIT) {
+                dst[(size_t)n_q * d + j] = from_float<half_t>(o1 - (float)h1);
+                dst[(size_t)n_q * d + j + half] = from_float<half_t>(o2 - (float)h2);
+            }
         } else {
             const size_t blk = ((size_t)(slot >> 4) * n_kv + (hd - n_q)) * page_elems;
             kv_hi[blk + k_elem(ts, j, d, 2)] = h1;
             kv_hi[blk + k_elem(ts, j + half, d, 2)] = h2;
-            kv_lo[blk + k_elem(ts, j, d, 2)] = l1;
-            kv_lo[blk + k_elem(ts, j + half, d, 2)] = l2;
+            if constexpr (SPLIT) {
+                kv_lo[blk + k_elem(ts, j, d, 2)] = from_float<half_t>(o1 - (float)h1);
+                kv_lo[blk + k_elem(ts, j + half, d, 2)] = from_float<half_t>(o2 - (float)h2);
+            }
         }
     }
     const float* vr = row + (size_t)rot_heads * d;
@@ -251,7 +260,7 @@ __global__ void rope_pages_split_kernel(const float* __restrict__ qkv, const flo
         const half_t hi = from_float<half_t>(v);
         const size_t blk = ((size_t)(slot >> 4) * n_kv + h) * page_elems + (size_t)kPageTokens * d;
         kv_hi[blk + v_elem(ts, c, d)] = hi;
-        kv_lo[blk + v_elem(ts, c, d)] = from_float<half_t>(v - (float)hi);
+        if constexpr (SPLIT) kv_lo[blk + v_elem(ts, c, d)] = from_float<half_t>(v - (float)hi);
     }
 }
 
@@ -613,15 +622,16 @@ hipError_t launch_rope_table(const MetaView& mv, float2* tab, int head_dim, floa
     return hipGetLastError();
 }
 
-hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st) {
+hipError_t launch_rmsnorm(int dtype, const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st,
+                          const int32_t* rows) {
     if (T == 0) return hipSuccess;
     if (dtype != HR_F32 && H % 4 == 0 && H <= 4096) {
-        if (H <= 1024) rmsnorm_vec_kernel<1><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps);
-        else if (H <= 2048) rmsnorm_vec_kernel<2><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps);
-        else rmsnorm_vec_kernel<4><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps);
+        if (H <= 1024) rmsnorm_vec_kernel<1><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps, rows);
+        else if (H <= 2048) rmsnorm_vec_kernel<2><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps, rows);
+        else rmsnorm_vec_kernel<4><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps, rows);
         return hipGetLastError();
     }
-    HR_DISPATCH_ACT(dtype, rmsnorm_kernel<AT><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (AT*)y, H, eps));
+    HR_DISPATCH_ACT(dtype, rmsnorm_kernel<AT><<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (AT*)y, H, eps, rows));
     return hipGetLastError();
 }
 
@@ -681,16 +691,22 @@ hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, size_t s
     return hipGetLastError();
 }
 
-hipError_t launch_rmsnorm_split(const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st) {
+hipError_t launch_rmsnorm_split(const float* x, const float* gain, void* y, int64_t T, int H, float eps, hipStream_t st,
+                                const int32_t* rows) {
     if (T == 0) return hipSuccess;
-    rmsnorm_split_kernel<<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps);
+    rmsnorm_split_kernel<<<dim3((unsigned)T), 256, 0, st>>>(x, gain, (half_t*)y, H, eps, rows);
     return hipGetLastError();
 }
 
-hipError_t launch_rope_pages_split(const float* qkv, const float2* tab, void* q, void* kv_hi, void* kv_lo, const int32_t* new_slot,
-                                   int64_t T, int n_q, int n_kv, int d, hipStream_t st) {
+hipError_t launch_rope_pages(const float* qkv, const float2* tab, void* q, void* kv_hi, void* kv_lo, const int32_t* new_slot,
+                             const int32_t* tok_src, int64_t T, int n_q, int n_kv, int d, hipStream_t st) {
     if (T == 0) return hipSuccess;
-    rope_pages_split_kernel<<<dim3((unsigned)T), 256, 0, st>>>(qkv, tab, (half_t*)q, (half_t*)kv_hi, (half_t*)kv_lo, new_slot, n_q, n_kv, d);
+    if (kv_lo)
+        rope_pages_kernel<true><<<dim3((unsigned)T), 256, 0, st>>>(qkv, tab, (half_t*)q, (half_t*)kv_hi, (half_t*)kv_lo, new_slot, tok_src,
+                                                                   n_q, n_kv, d);
+    else
+        rope_pages_kernel<false><<<dim3((unsigned)T), 256, 0, st>>>(qkv, tab, (half_t*)q, (half_t*)kv_hi, nullptr, new_slot, tok_src, n_q,
+                                                                    n_kv, d);
     return hipGetLastError();
 }
 

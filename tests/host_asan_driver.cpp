@@ -1,6 +1,7 @@
 // Host-only logic of the library (layouts, chunk plan, metadata builder, validation) run on exact-size buffers
 // under AddressSanitizer / UBSan.  Built and run by tests/test_host_asan.py; no GPU involved.
 #include <cstdio>
+#include <cstring>
 #include <cstdint>
 #include <cstdlib>
 #include <vector>
@@ -202,6 +203,36 @@ int main() {
         const double f8b = hr::gemm_tile_fill(12800, 4096, 256);
         CHECK(f8b > 0.83 && f8b < 0.84);                                               // 640 of 768 slots
         CHECK(hr::gemm_tile_fill(25600, 4096, 256) == 1.0);                            // 1280 tall tiles = 5 full rounds
+    }
+    {   // sequences with the same token string share first-layer rows: tables written into a layout of exactly the computed size
+        // strings: A = {5, 6, 7}, B = {5, 6}, C = {9}; sequences A B A C B A C
+        const std::vector<int32_t> lens = {3, 2, 3, 1, 2, 3, 1};
+        const std::vector<int32_t> toks = {5, 6, 7, 5, 6, 5, 6, 7, 9, 5, 6, 5, 6, 7, 9};
+        const int64_t n = (int64_t)lens.size(), T = (int64_t)toks.size();
+        const hr::QueryShare qs = hr::make_query_share(n, lens.data(), toks.data());
+        CHECK(qs.n_uniq == 6 && (int64_t)qs.rep_row.size() == 6 && (int64_t)qs.tok_src.size() == T);
+        const std::vector<int32_t> want_rep = {0, 1, 2, 3, 4, 8};
+        const std::vector<int32_t> want_src = {0, 1, 2, 3, 4, 0, 1, 2, 5, 3, 4, 0, 1, 2, 5};
+        CHECK(qs.rep_row == want_rep && qs.tok_src == want_src);
+        for (int64_t t = 0; t < T; ++t) CHECK(toks[qs.rep_row[qs.tok_src[t]]] == toks[t]);
+        const hr::MetaLayout ml = hr::make_meta_layout(n, T, 4, -1, 0, 10, true);
+        CHECK(ml.rep_row >= ml.tok_src + (size_t)T && ml.grp >= ml.rep_row + (size_t)T / 2 + 1 && ml.total >= ml.grp + 10);
+        CHECK(qs.n_uniq * 2 <= T);                           // the tables fit the room the layout gives them
+        std::vector<int32_t> meta(ml.total, -7);
+        std::memcpy(meta.data() + ml.tok_src, qs.tok_src.data(), sizeof(int32_t) * qs.tok_src.size());
+        std::memcpy(meta.data() + ml.rep_row, qs.rep_row.data(), sizeof(int32_t) * qs.rep_row.size());
+        // equal hashes of different strings must not merge: same length, tokens differ in one place
+        const std::vector<int32_t> l2 = {2, 2, 2};
+        const std::vector<int32_t> t2 = {1, 2, 1, 3, 1, 2};
+        const hr::QueryShare q2 = hr::make_query_share(3, l2.data(), t2.data());
+        CHECK(q2.n_uniq == 4 && q2.tok_src[4] == 0 && q2.tok_src[5] == 1 && q2.tok_src[2] == 2);
+        const hr::QueryShare q0 = hr::make_query_share(0, l2.data(), t2.data());
+        CHECK(q0.n_uniq == 0 && q0.tok_src.empty());
+        // workspace: the split form doubles the activation buffers, the shared form adds fp32 rows for half the tokens
+        hr_model_cfg mc{2, 256, 4, 2, 64, 320, 500, 1, 2, HR_BF16, 10000.0f, 1e-6f};
+        const hr::Workspace w0 = hr::make_workspace(mc, 4, 100, 3, false), w1 = hr::make_workspace(mc, 4, 100, 3, false, -1, 0, 0, true),
+                            w2 = hr::make_workspace(mc, 4, 100, 3, false, -1, 0, 0, false, true);
+        CHECK(w1.total > w0.total && w2.total > w0.total && w1.off_kvlo >= w1.off_v && w1.off_o > w1.off_kvlo && w0.off_o == w0.off_kvlo);
     }
     std::printf("host logic clean under sanitizers\n");
     return 0;

@@ -166,6 +166,36 @@ def test_split_operand_layers_score_an_order_of_magnitude_closer_to_the_oracle(d
         case.close()
 
 
+@pytest.mark.parametrize("d,n_q,n_kv,kv,n_split", [(64, 14, 2, "bf16", 0), (128, 8, 2, "fp8", 0), (64, 4, 2, "bf16", 2), (128, 8, 2, "bf16", 1)])
+def test_first_layer_projections_are_shared_across_a_querys_candidates(d, n_q, n_kv, kv, n_split, monkeypatch):
+    """One query against several candidates: the pairs carry the same query string, so the first layer's normalised
+    rows and pre-RoPE q / k / v are computed once per query and rotated per pair.  Same bits as computing every pair's
+    rows, in any pair order, and within tolerance of the oracle."""
+    model = small_model(dtype="bf16", n_layers=3, hidden=256, n_q=n_q, n_kv=n_kv, d=d, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("share_q", model, 4, 6, (20, 150), (3, 40), kv, pool_docs=11, zipf_a=0.5, seed=d + n_q + n_split)
+    w = wlmod.SeededWeights(model, seed=19, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(cfg, spare_pages=2)
+    order = np.random.default_rng(4).permutation(wl.n_pairs)            # the candidates of a query are not adjacent
+    mixed = wl.subset(order)
+    outs = {}
+    for off in ("0", "1"):
+        monkeypatch.setenv("HR_NO_QUERY_SHARING", off)
+        case = H.Case(wl, w)
+        try:
+            case.fill_from_prefill()
+            case.model.set_precise_layers(n_split)
+            outs[off] = (case.gpu_scores(), case.gpu_scores(mixed), case.gpu_scores(wl.subset(np.array([3]))))
+            if off == "0":
+                want = case.oracle_scores()
+                H.assert_scores_close(outs[off][0], want, H.TOL["bf16"], "shared first layer")
+        finally:
+            case.close()
+    for a, b in zip(outs["0"], outs["1"]):
+        np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(outs["0"][1], outs["0"][0][order])
+    np.testing.assert_array_equal(outs["0"][2], outs["0"][0][[3]])
+
+
 def test_range_reports_count_what_half_and_e4m3_cannot_hold():
     """The caller's bf16 weights and K/V become halves once; what does not fit is counted, and a value that overflowed
     makes the scores that depend on it non-finite instead of silently wrong."""
