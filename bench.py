@@ -29,6 +29,7 @@ and for the headline workload also
   host_tier           the same batch when every document's pages first come from pinned host memory
                       (bus-inclusive rate, page-in overlapped with scoring; never `value`)
   host_tier_4bit      the same with 4-bit records in the tier (16-bit pools)
+  small_request       one query with 20 candidates: latency of a plain call, of a fixed-shape plan, of its graph replay
 """
 
 import argparse
@@ -342,6 +343,43 @@ def measure(name, args, shared, legs, dev="cuda:0"):
     elif roof_attn and shared.get("ceilings"):
         roof_attn["frac_of_read_only_kernel"] = round(roof_attn["achieved"] / shared["ceilings"]["hbm_read_GBps"], 4)
 
+    # ---- one request: one query with its candidates (latency, not throughput) ---------------------------------
+    if "small_request" in legs:
+        n_small = min(cfg.n_cands, 20)
+        sub = wl.subset(np.arange(n_small))
+        out_small = torch.empty(n_small, dtype=torch.float32, device=dev)
+
+        def timed_calls(fn, n=30):
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(n):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / n * 1e3
+
+        ms_call = timed_calls(lambda: model.score(pool, sub.page_table, sub.doc_lens, sub.query_tokens, sub.query_lens, out=out_small))
+        ref_small = out_small.clone()
+        small = {"pairs": n_small, "query_tokens": sub.total_q_tokens, "hr_rerank_score_ms": round(ms_call, 4)}
+        try:
+            plan = hb.Plan(model, pool, sub.doc_lens, sub.query_lens, sub.page_table.shape[1])
+            plan.set_inputs(sub.page_table, sub.query_tokens)
+            small["plan_run_ms"] = round(timed_calls(lambda: plan.run(out_small)), 4)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                plan.run(out_small)
+            small["graph_replay_ms"] = round(timed_calls(graph.replay), 4)
+            assert torch.equal(out_small, ref_small), "plan / graph replay scores differ from hr_rerank_score"
+            small["note"] = ("one query with its first candidates, documents resident: hr_rerank_score (host builds and uploads the metadata "
+                             "every call), hr_rerank_plan_run (fixed shape, stream work only), and the plan recorded once into a HIP graph "
+                             "and replayed; same score bits in all three")
+            del graph
+            plan.close()
+        except hb.HrError as e:
+            small["note"] = str(e)
+        res["small_request"] = small
+
     # ---- same-GPU no-reuse reference on a few pairs ------------------------------------------
     if "no_reuse" in legs and args.no_reuse_pairs > 0:
         # sized so that the leg stays at a few seconds: ~0.5 M tokens of [doc ; query] at the 0.5B shape, ~70 k at the 8B shape
@@ -553,7 +591,7 @@ def main():
     others = [x for x in also.split(",") if x and x != "none" and x != args.workload]
 
     shared = {"models": {}}
-    legs = {"cpu", "no_reuse", "prefill", "host_tier"} | (set() if args.no_ceilings else {"ceilings"})
+    legs = {"cpu", "no_reuse", "prefill", "host_tier", "small_request"} | (set() if args.no_ceilings else {"ceilings"})
     t_start = time.time()
     main_res = measure(args.workload, args, shared, legs)
     other_res = {}
@@ -565,7 +603,7 @@ def main():
             shared["models"].pop(key)[0].close()
         gc.collect()
         torch.cuda.empty_cache()
-        extra = {"c3_llama8b": {"cpu"}, "c5_long_fp8": {"no_reuse"}}.get(name, set())
+        extra = {"c3_llama8b": {"cpu", "small_request"}, "c5_long_fp8": {"no_reuse"}}.get(name, set())
         other_res[name] = measure(name, args, shared, extra)
         log(f"[{name}] done at {time.time() - t_start:.0f}s: {other_res[name]['value']} pairs/s")
 
@@ -576,7 +614,7 @@ def main():
         "dtype": main_res.pop("dtype"), "data": "synthetic",
     }
     line.update(main_res)
-    for k in ("ceilings", "cpu_baseline", "no_reuse", "doc_prefill", "host_tier", "host_tier_4bit"):
+    for k in ("ceilings", "cpu_baseline", "no_reuse", "doc_prefill", "host_tier", "host_tier_4bit", "small_request"):
         line.setdefault(k, None)
     line["other_workloads"] = other_res or None
     line["paper_context"] = "2-3x end-to-end service throughput from reranker KV reuse on 8x A100 (Table 1); not this metric"

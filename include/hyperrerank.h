@@ -23,7 +23,8 @@
  *     when a call's metadata needs more) and, once a scoring call has been cut in two halves, one stream and three
  *     events per model handle (released by hr_model_destroy).
  *   - Calls that upload per-call metadata (scoring, prefill) wait on the host for the previous upload of the same
- *     handle and copy from its staging buffer: they are not meant to be recorded into a HIP graph.
+ *     handle and copy from its staging buffer: they are not meant to be recorded into a HIP graph.  hr_rerank_plan_run
+ *     is the form that is.
  *   - Every call returns HR_OK (0) or a negative hr_status.  Every argument check happens before anything is enqueued
  *     or any library state changes; only HR_ERR_DEVICE (a HIP call failed mid-way) can leave part of a call's work on the
  *     stream, and the outputs of that call are then undefined.  Nothing throws or aborts.
@@ -269,6 +270,33 @@ int hr_rerank_score(hr_model* model, const hr_pool* pool, int32_t n_pairs,
                     const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
                     const int32_t* query_tokens, const int32_t* query_lens,
                     void* workspace_dev, size_t workspace_bytes, float* scores_dev, void* stream);
+
+/* ---- fixed-shape plans: a scoring call whose launches can be recorded once and replayed (Section 4.2: the static
+ * [document prefix | query suffix] layout exists so that the reranker's execution can be captured ahead of time) ----
+ * A plan fixes the shape of a call: the number of pairs and every pair's document and query length.  Which pages and
+ * which query tokens it scores can change between runs.  hr_rerank_plan_run enqueues one host-to-device copy from a
+ * pinned block the plan owns, and the kernels; it never waits on the host, allocates nothing and uses `stream` only,
+ * so it may be recorded into a HIP graph (stream capture) and replayed.  The work of a plan depends on the lengths
+ * alone: pairs are not regrouped by shared documents or shared query strings as hr_rerank_score does, which changes no
+ * score bit.
+ *   hr_rerank_plan_create      host: checks the lengths, carves `workspace_dev` (>= hr_rerank_workspace_bytes for these
+ *                              sizes, private to the plan while it lives) and allocates the pinned metadata block (the one
+ *                              allocation of a plan's life).  Uses the model's split-operand setting at this moment.
+ *   hr_rerank_plan_set_inputs  host: validates page_table [n_pairs][pt_stride] and query_tokens (flat, pair after pair)
+ *                              like hr_rerank_score and writes them into the pinned block.  The copy in a run or replay
+ *                              reads that block when it executes: do not call this while a run or replay that has not
+ *                              finished could still read the block.
+ *   hr_rerank_plan_run         stream work only (see above); scores_dev fp32 [n_pairs].  HR_ERR_INVALID_ARG before the
+ *                              first set_inputs.  Run it once outside capture first: the first launch of a kernel sets
+ *                              its function attributes.
+ * Plans of one model share its kernels but no state; a plan must not outlive its model, pool or workspace. */
+typedef struct hr_plan hr_plan;
+int hr_rerank_plan_create(hr_model* model, const hr_pool* pool, int32_t n_pairs, const int32_t* doc_lens,
+                          const int32_t* query_lens, int32_t pt_stride, void* workspace_dev, size_t workspace_bytes,
+                          hr_plan** out);
+int hr_rerank_plan_set_inputs(hr_plan* plan, const int32_t* page_table, const int32_t* query_tokens);
+int hr_rerank_plan_run(hr_plan* plan, float* scores_dev, void* stream);
+void hr_rerank_plan_destroy(hr_plan* plan);
 
 /* hr_rerank_score for callers that cannot allocate or hand over a workspace: code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc.  Same arguments, validation, kernels and scores (bit for bit) as

@@ -66,7 +66,8 @@ EXPORTS = [
     "hr_kv_pool_alloc_pages", "hr_doc_kv_write", "hr_doc_kv_read", "hr_doc_kv_free", "hr_kv_page_record_bytes", "hr_kv_pages_out",
     "hr_kv_pages_in", "hr_kv_page_record4_bytes", "hr_kv_pages_out4", "hr_kv_pages_in4", "hr_weights_pack_bytes", "hr_weights_load",
     "hr_model_destroy", "hr_rerank_workspace_bytes", "hr_rerank_score", "hr_rerank_static_scratch_bytes",
-    "hr_rerank_score_static", "hr_model_set_precise_layers", "hr_model_precise_layers", "hr_rerank_set_streams", "hr_rerank_parts", "hr_rerank_validate",
+    "hr_rerank_score_static", "hr_rerank_plan_create", "hr_rerank_plan_set_inputs", "hr_rerank_plan_run",
+    "hr_rerank_plan_destroy", "hr_model_set_precise_layers", "hr_model_precise_layers", "hr_rerank_set_streams", "hr_rerank_parts", "hr_rerank_validate",
     "hr_rerank_full_workspace_bytes", "hr_rerank_score_full", "hr_doc_prefill_workspace_bytes", "hr_doc_prefill", "hr_attention_path", "hr_gemm_path",
     "hr_rerank_topk", "hr_model_range_report", "hr_kv_pool_range_report", "hr_probe_read_bandwidth", "hr_profile_enable", "hr_profile_select", "hr_profile_count", "hr_profile_name", "hr_profile_read",
 ]
@@ -112,6 +113,11 @@ def _load() -> C.CDLL:
         "hr_rerank_static_scratch_bytes": (C.c_size_t, []),
         "hr_rerank_score_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, i32p, C.c_int32, i32p, i32p, i32p,
                                              C.c_void_p, C.c_void_p]),
+        "hr_rerank_plan_create": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, i32p, i32p, C.c_int32, C.c_void_p, C.c_size_t,
+                                            C.POINTER(C.c_void_p)]),
+        "hr_rerank_plan_set_inputs": (C.c_int, [C.c_void_p, i32p, i32p]),
+        "hr_rerank_plan_run": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+        "hr_rerank_plan_destroy": (None, [C.c_void_p]),
         "hr_model_set_precise_layers": (C.c_int, [C.c_void_p, C.c_int]),
         "hr_model_precise_layers": (C.c_int, [C.c_void_p]),
         "hr_rerank_set_streams": (C.c_int, [C.c_void_p, C.c_int]),
@@ -334,6 +340,41 @@ class KVPool:
 
 
 _LAYER_KINDS = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "norm1", "norm2")
+
+
+class Plan:
+    """A fixed-shape scoring plan (hr_rerank_plan_*): owns its workspace tensor; run() is stream work only."""
+
+    def __init__(self, model: "Model", pool: KVPool, doc_lens, query_lens, pt_stride: int):
+        import torch
+        self.model, self.pool = model, pool
+        dl, ql = _i32(doc_lens), _i32(query_lens)
+        self.n_pairs, self.pt_stride = len(dl), int(pt_stride)
+        nbytes = int(lib.hr_rerank_workspace_bytes(model.handle, self.n_pairs, int(ql.sum()), self.pt_stride))
+        self.ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=model.device)
+        out = C.c_void_p()
+        check(lib.hr_rerank_plan_create(model.handle, pool.handle, self.n_pairs, _i32p(dl), _i32p(ql), self.pt_stride,
+                                        C.c_void_p(self.ws.data_ptr()), self.ws.numel(), C.byref(out)), "hr_rerank_plan_create")
+        self.handle = out
+
+    def set_inputs(self, page_table, query_tokens) -> None:
+        pt, qt = _i32(page_table), _i32(query_tokens)
+        check(lib.hr_rerank_plan_set_inputs(self.handle, _i32p(pt), _i32p(qt)), "hr_rerank_plan_set_inputs")
+
+    def run(self, out, stream=None):
+        check(lib.hr_rerank_plan_run(self.handle, C.c_void_p(out.data_ptr()), _stream_ptr(stream)), "hr_rerank_plan_run")
+        return out[:self.n_pairs]
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib.hr_rerank_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 class Model:

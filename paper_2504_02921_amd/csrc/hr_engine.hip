@@ -612,9 +612,15 @@ struct ScorePart {
     int max_keys = 0;
 };
 
-static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
-                              const int32_t* query_tokens, const int32_t* query_lens, int64_t T, bool mfma_attn, const hr::Workspace& ws,
-                              const hr::MetaLayout& ml, int64_t grp_ints, int32_t* stage, char* wsb, hipStream_t st, ScorePart* out) {
+// Builds a part's metadata (already validated) at `stage`: the token / position / slot tables, the page table, and the
+// two content-dependent plans: pairs that share a document (one attention work item per kv head) and pairs that share
+// a query string (first-layer rows computed once).  content_plans = false leaves both out, so that the layout of the
+// work depends on the lengths alone (fixed-shape plans, whose launches are recorded once and replayed with other
+// tokens and pages).  *upload_ints = how much of the block the device needs.
+static void build_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
+                             const int32_t* query_tokens, const int32_t* query_lens, int64_t T, bool mfma_attn, const hr::Workspace& ws,
+                             const hr::MetaLayout& ml, int64_t grp_ints, int32_t* stage, char* wsb, bool content_plans, ScorePart* out,
+                             size_t* upload_ints) {
     hr::fill_meta(stage, ml, n_pairs, doc_lens, query_lens, query_tokens, page_table, pt_stride);
     // Pairs that share a document become one attention work item per kv head (up to 16 row blocks at 64-wide heads,
     // 8 at 128-wide heads, where two blocks per wave do not fit the register file at two waves per SIMD).
@@ -626,7 +632,8 @@ static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_
         // of at most four, one per wave of the smallest kernel, each streaming the document for its share of the rows
         const bool scarce = n_pairs <= hr::kGroupCutMaxSeqs && (int64_t)n_pairs * m->cfg.n_kv_heads * 2 <= hr::device_cu_count();
         const int cap = scarce ? 4 : (m->cfg.head_dim == 64 ? 16 : 8);
-        const hr::GroupPlan plan = hr::make_group_plan(n_pairs, doc_lens, query_lens, page_table, pt_stride, g, cap, scarce);
+        const hr::GroupPlan plan = hr::make_group_plan(n_pairs, doc_lens, query_lens, content_plans ? page_table : nullptr, pt_stride, g,
+                                                       cap, scarce);
         // also without a shared document when the pairs differ in length: the plan's heaviest-first order keeps the
         // persistent workgroups' last items short
         if ((plan.shared || plan.uneven || plan.cut) && plan.ints() <= (size_t)grp_ints) {
@@ -648,7 +655,7 @@ static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_
     // sequences with the same token string share the first layer's normalised rows and projections, where that at least
     // halves the rows (the shared rows take the y and fp32 buffers)
     int64_t n_uniq = 0;
-    if (mfma_attn && !m->no_query_share && ml.rep_row > ml.tok_src && n_pairs >= 2) {
+    if (content_plans && mfma_attn && !m->no_query_share && ml.rep_row > ml.tok_src && n_pairs >= 2) {
         const hr::QueryShare qs = hr::make_query_share(n_pairs, query_lens, query_tokens);
         if (qs.n_uniq * 2 <= T) {
             std::memcpy(stage + ml.tok_src, qs.tok_src.data(), sizeof(int32_t) * qs.tok_src.size());
@@ -656,7 +663,7 @@ static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_
             n_uniq = qs.n_uniq;
         }
     }
-    HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, stage, (ml.grp + plan_ints) * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    out->max_keys = 0;
     for (int32_t p = 0; p < n_pairs; ++p) out->max_keys = std::max(out->max_keys, doc_lens[p] + query_lens[p]);
     out->mv = make_meta_view((const int32_t*)(wsb + ws.off_meta), ml, n_pairs, T, pt_stride);
     if (n_uniq > 0) {
@@ -664,6 +671,16 @@ static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_
         out->mv.rep_row = (const int32_t*)(wsb + ws.off_meta) + ml.rep_row;
         out->mv.n_uniq = (int32_t)n_uniq;
     }
+    *upload_ints = ml.grp + plan_ints;
+}
+
+static int prepare_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_table, int32_t pt_stride, const int32_t* doc_lens,
+                              const int32_t* query_tokens, const int32_t* query_lens, int64_t T, bool mfma_attn, const hr::Workspace& ws,
+                              const hr::MetaLayout& ml, int64_t grp_ints, int32_t* stage, char* wsb, hipStream_t st, ScorePart* out) {
+    size_t upload_ints = 0;
+    build_score_part(m, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens, T, mfma_attn, ws, ml, grp_ints, stage, wsb, true,
+                     out, &upload_ints);
+    HR_HIP(hipMemcpyAsync(wsb + ws.off_meta, stage, upload_ints * sizeof(int32_t), hipMemcpyHostToDevice, st));
     return HR_OK;
 }
 
@@ -811,6 +828,106 @@ int hr_rerank_score_static(hr_model* m, const hr_pool* pool, int32_t n_pairs, co
                          scratch, scores_dev, (hipStream_t)stream, false);
     m->prof_on = prof;
     return rc;
+}
+
+// ---- fixed-shape scoring plans -----------------------------------------------------------------------------------
+struct hr_plan {
+    hr_model* m = nullptr;
+    const hr_pool* pool = nullptr;
+    int32_t n_pairs = 0, pt_stride = 0;
+    int64_t T = 0, grp_ints = 0;
+    int max_q = 0;
+    bool mfma_attn = false, inputs_set = false;
+    int n_precise = 0;                               // as the model was set when the plan was made (the workspace is carved for it)
+    std::vector<int32_t> doc_lens, query_lens;
+    hr::Workspace ws;
+    hr::MetaLayout ml;
+    char* wsb = nullptr;
+    int32_t* stage = nullptr;                        // pinned, ml.total ints, owned by the plan
+    size_t upload_ints = 0;
+    ScorePart part;
+};
+
+int hr_rerank_plan_create(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int32_t* doc_lens, const int32_t* query_lens,
+                          int32_t pt_stride, void* workspace_dev, size_t workspace_bytes, hr_plan** out) {
+    if (!out) return HR_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!m || !pool || n_pairs <= 0 || pt_stride < 0 || !doc_lens || !query_lens || !workspace_dev) return HR_ERR_INVALID_ARG;
+    if ((uintptr_t)workspace_dev % hr::kAlign != 0) return HR_ERR_INVALID_ARG;
+    const hr_model_cfg& mc = m->cfg;
+    if (pool->cfg.n_layers != mc.n_layers || pool->cfg.n_kv_heads != mc.n_kv_heads || pool->cfg.head_dim != mc.head_dim) return HR_ERR_MISMATCH;
+    if ((mc.dtype == HR_F32) != (pool->cfg.kv_dtype == HR_F32)) return HR_ERR_MISMATCH;
+    int max_q = 0;
+    for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
+    const bool mfma_attn = use_mfma_attn(m, pool->cfg.kv_dtype, max_q);
+    int64_t T = 0;
+    for (int32_t p = 0; p < n_pairs; ++p) {
+        if (doc_lens[p] < 0 || query_lens[p] <= 0) return HR_ERR_LEN_RANGE;
+        if ((int64_t)doc_lens[p] + query_lens[p] > (mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys)) return HR_ERR_LEN_RANGE;
+        if (((int64_t)doc_lens[p] + hr::kPageTokens - 1) / hr::kPageTokens > pt_stride) return HR_ERR_TABLE_SHORT;
+        T += query_lens[p];
+    }
+    if (T > (int64_t)1 << 30) return HR_ERR_LEN_RANGE;
+    hr_plan* pl = new (std::nothrow) hr_plan();
+    if (!pl) return HR_ERR_INVALID_ARG;
+    pl->m = m; pl->pool = pool; pl->n_pairs = n_pairs; pl->pt_stride = pt_stride; pl->T = T; pl->max_q = max_q;
+    pl->mfma_attn = mfma_attn; pl->n_precise = m->n_precise;
+    pl->doc_lens.assign(doc_lens, doc_lens + n_pairs);
+    pl->query_lens.assign(query_lens, query_lens + n_pairs);
+    pl->grp_ints = (int64_t)hr::group_plan_ints_bound(n_pairs, T, mc.n_q_heads / mc.n_kv_heads);
+    pl->ws = hr::make_workspace(mc, n_pairs, T, pt_stride, !m->mfma_gemm, -1, 0, pl->grp_ints, m->n_precise > 0, m->mfma_gemm);
+    pl->ml = hr::make_meta_layout(n_pairs, T, pt_stride, -1, 0, pl->grp_ints, m->mfma_gemm);
+    pl->wsb = (char*)workspace_dev;
+    if (workspace_bytes < pl->ws.total) {
+        delete pl;
+        return HR_ERR_WORKSPACE_SMALL;
+    }
+    hipError_t e = hipHostMalloc((void**)&pl->stage, std::max<size_t>(pl->ml.total, 64) * sizeof(int32_t), hipHostMallocDefault);
+    if (e != hipSuccess) {
+        note_hip_error(e, "hipHostMalloc (plan metadata)");
+        delete pl;
+        return HR_ERR_DEVICE;
+    }
+    std::memset(pl->stage, 0, pl->ml.total * sizeof(int32_t));
+    *out = pl;
+    return HR_OK;
+}
+
+int hr_rerank_plan_set_inputs(hr_plan* pl, const int32_t* page_table, const int32_t* query_tokens) {
+    if (!pl || !query_tokens) return HR_ERR_INVALID_ARG;
+    int64_t T = 0;
+    int rc = hr::score_check_args(pl->m->cfg, pl->pool, pl->n_pairs, page_table, pl->pt_stride, pl->doc_lens.data(), query_tokens,
+                                  pl->query_lens.data(), pl->mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys, &T);
+    if (rc != HR_OK) return rc;
+    build_score_part(pl->m, pl->n_pairs, page_table, pl->pt_stride, pl->doc_lens.data(), query_tokens, pl->query_lens.data(), pl->T,
+                     pl->mfma_attn, pl->ws, pl->ml, pl->grp_ints, pl->stage, pl->wsb, false, &pl->part, &pl->upload_ints);
+    pl->inputs_set = true;
+    return HR_OK;
+}
+
+int hr_rerank_plan_run(hr_plan* pl, float* scores_dev, void* stream) {
+    if (!pl || !scores_dev) return HR_ERR_INVALID_ARG;
+    if (!pl->inputs_set) {
+        snprintf(g_last_error, sizeof(g_last_error), "hr_rerank_plan_run: no inputs set (hr_rerank_plan_set_inputs)");
+        return HR_ERR_INVALID_ARG;
+    }
+    hr_model* m = pl->m;
+    hipStream_t st = (hipStream_t)stream;
+    // everything below is stream work only: one copy from the plan's own pinned block and the kernels.  No host wait, no
+    // allocation, no event, no second stream, no timing.
+    HR_HIP(hipMemcpyAsync(pl->wsb + pl->ws.off_meta, pl->stage, pl->upload_ints * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    const bool prof = m->prof_on;
+    m->prof_on = false;
+    const int rc = run_layers(m, pl->pool, false, pl->part.mv, pl->ws, pl->wsb, pl->part.max_keys, pl->max_q, scores_dev, st, nullptr,
+                              pl->part.gv.n_groups > 0 ? &pl->part.gv : nullptr, nullptr, pl->n_precise);
+    m->prof_on = prof;
+    return rc;
+}
+
+void hr_rerank_plan_destroy(hr_plan* pl) {
+    if (!pl) return;
+    if (pl->stage) (void)hipHostFree(pl->stage);
+    delete pl;
 }
 
 int hr_model_set_precise_layers(hr_model* m, int n_layers) {

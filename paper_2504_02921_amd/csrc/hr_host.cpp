@@ -367,7 +367,7 @@ GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32
         // run of sequences whose rows equal the first one's (a sequence without a document is a run of its own)
         const int32_t lead = order[i];
         int64_t j = i + 1;
-        if (prefix_lens[lead] > 0)
+        if (prefix_lens[lead] > 0 && pt)                   // without a page table every sequence is taken to have its own document
             while (j < n_seq && first_page(order[j]) == first_page(lead) && prefix_lens[order[j]] == prefix_lens[lead] &&
                    std::memcmp(pt + (int64_t)order[j] * pt_stride, pt + (int64_t)lead * pt_stride,
                                sizeof(int32_t) * (size_t)pages_of(lead)) == 0)

@@ -2,7 +2,7 @@
 entry point, the whole batch in one call), against the CPU oracle's scores stored under tests/golden/.
 
 The stored scores were written by tests/golden/make_golden.py, which calls only the float64 oracle and the seeded
-input generators: every pair of configs 2 and 3, 1228 stratified pairs of config 4 (four of every query, two whole
+input generators: every pair of configs 2 and 3, 1220 stratified pairs of config 4 (four of every query, two whole
 queries, the extreme lengths) and 106 pairs of config 5 (one whole query, two of each other query).  The document
 KV of these shapes is the seeded opaque stand-in (a CPU document prefill at 0.5B / 8B shapes would take hours); it is
 a counter-based draw whose bytes do not depend on the device, which this test checks on a sample of documents before
