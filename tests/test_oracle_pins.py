@@ -493,3 +493,34 @@ def test_generator_casts_and_workload_shapes():
     c2 = wlmod.make_workload(wlmod.CONFIGS["c2_qwen0p5b"])
     assert c2.n_pairs == 640 and c2.total_q_tokens == 20480 and c2.kv_stream_bytes() == 640 * 512 * 12288
     assert abs(c2.gemm_flop() - 14.7e12) < 0.1e12
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name,picks", [("c2_qwen0p5b", [0, 333]), ("c4_ragged", [0, 1, -1])])
+def test_stored_scores_are_what_the_oracle_computes_today(name, picks):
+    """tests/golden/<config>_scores.json (what the GPU suite compares against at the full sizes) against a fresh oracle
+    run on a few of their pairs: same seeded inputs, same float64 arithmetic, so the same numbers to rounding order."""
+    import json
+    import os
+    import sys
+    golden = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    if golden not in sys.path:
+        sys.path.insert(0, golden)
+    import make_golden
+    with open(os.path.join(golden, f"{name}_scores.json")) as f:
+        g = json.load(f)
+    cfg = wlmod.CONFIGS[name]
+    wl = wlmod.make_workload(cfg)
+    pairs = np.array(g["pairs"], dtype=np.int64)
+    assert np.array_equal(pairs, make_golden.golden_pairs(wl))
+    assert g["inputs_sha256"] == make_golden.inputs_digest(wl, pairs)
+    stored = np.array([float(x) for x in g["scores"]])
+    sel = np.array([pairs[i] for i in picks])
+    w = wlmod.SeededWeights(cfg.model, seed=cfg.seed)
+    opool = orr.PagedKV(cfg.model.n_layers, cfg.model.n_kv_heads, cfg.model.head_dim, 16, cfg.kv_dtype)
+    for d in sorted(set(int(wl.pair_doc[p]) for p in sel)):
+        make_golden.write_doc(opool, wl, d)
+    sub = wl.subset(sel)
+    got = orr.score_cached(w, cfg.model, opool, sub.page_table, sub.doc_lens, sub.query_tokens, sub.query_lens)
+    want = np.array([stored[np.searchsorted(pairs, p)] for p in sel])
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-9)
