@@ -288,6 +288,8 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PR
     bool blk_on[R];        // the wave's block rb exists in the current work item   (these three: uniform over the wave)
     int blk_seq[R];        // ... and belongs to this pair
     int blk_qn[R];         // ... which has this many query tokens
+    int blk_row0[R];       // ... first row of the block within the pair
+    int blk_t0[R];         // ... first token row of the pair
 
     // fp8 pools: the stage that has just landed is expanded to half pages once, by all threads together (8 codes
     // per step and thread), instead of by every wave for its own fragments: the conversions are the largest
@@ -488,6 +490,8 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PR
             const int t0 = m_cu[seq], qn = m_cu[seq + 1] - t0;
             blk_seq[rb] = seq;
             blk_qn[rb] = qn;
+            blk_row0[rb] = row0;
+            blk_t0[rb] = t0;
             const int M = last_only ? g : qn * g;                  // rows of this pair
             const int row = row0 + ln;
             row_ok[rb] = blk_on[rb] && row < M;
@@ -507,21 +511,26 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PR
     // The previous item's output waits, packed, in registers and is stored behind the next item's first barrier (the
     // split-operand variant stores at once).
     constexpr bool DEFER = !PREC;
-    halfx4 opk[DEFER ? R : 1][DEFER ? MB : 1][4];
-    size_t out_off[R];
-    bool out_ok[R];
+    // In the accumulator layout a lane holds 8 bytes of each of 4 x MB places of one row, and a store instruction
+    // touches 32 rows with 16 bytes each (measured: the 16 such stores per block cost ~8 k cycles per work item, queued in
+    // front of the next stage's loads).  The output is therefore turned through LDS, 32 channels at a time, into whole
+    // 64-byte row segments: chunk c = lane + 64 j (j = 0, 1) is 16 bytes, piece c & 3 of row c >> 2 of the block.
+    typedef __attribute__((ext_vector_type(4))) unsigned ochunk_t;
+    ochunk_t opk[DEFER ? R : 1][DEFER ? MB : 1][2];
+    size_t out_off[R][2];
+    bool out_ok[R][2];
     bool out_pending = false;
     auto flush_out = [&]() {
         if (!out_pending) return;
 #pragma unroll
-        for (int rb = 0; rb < R; ++rb) {
-            if (!out_ok[rb]) continue;
-            half_t* dst = o + out_off[rb];
+        for (int rb = 0; rb < R; ++rb)
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
+            for (int j = 0; j < 2; ++j) {
+                if (!out_ok[rb][j]) continue;
+                half_t* dst = o + out_off[rb][j] + (lane & 3) * 8;
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) *(halfx4*)(dst + mb * 32 + 8 * r4 + 4 * hh) = opk[rb][mb][r4];
-        }
+                for (int mb = 0; mb < MB; ++mb) *(ochunk_t*)(dst + mb * 32) = opk[rb][mb][j];
+            }
         out_pending = false;
     };
 
@@ -621,21 +630,20 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PR
         // ---- normalise; the output is packed to half and kept in registers: the stores are issued after the next
         // item's first barrier (flush_out), so neither their issue nor their completion sits in front of a vmcnt wait.
         // The next item's Q fragments are requested now so their latency hides as well.
+        if constexpr (DEFER) {
+            // every wave is past its reads of the stage the last own-key tile sat in; that stage is free until the next
+            // item's second tile is requested (behind the next barrier), and 2 KiB of it per wave turn the output
+            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        }
+        char* tbuf = smem + (stage ^ 1) * kStageBytes + wave_u * (kStageBytes / NW);
 #pragma unroll
         for (int rb = 0; rb < R; ++rb) {
             const float l = row_sum2(l_run[rb]);
             const float inv = 1.0f / l;
-            if (last_only) {                                   // ungrouped: block b holds rows 32 b .. of the pair
-                const int row = (wave + rb * NW) * 32 + ln;
-                out_off[rb] = ((size_t)blk_seq[rb] * n_q + cur.h * g + (row < g ? row : g - 1)) * HD;
-            } else {
-                out_off[rb] = row_off[rb];
-            }
-            out_ok[rb] = row_ok[rb];
             if constexpr (PREC) {
                 // [hi | lo] halves of the output row, stored right away (this variant does not defer its stores)
                 if (row_ok[rb]) {
-                    half_t* dst = o + out_off[rb];
+                    half_t* dst = o + row_off[rb];
 #pragma unroll
                     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -651,26 +659,39 @@ __global__ void __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PR
                             *(halfx4*)(dst + (size_t)n_q * HD + mb * 32 + 8 * r4 + 4 * hh) = lo;
                         }
                 }
-            } else if constexpr (!DEFER) {
-                if (row_ok[rb]) {
-                    half_t* dst = o + out_off[rb];
+            } else {
+                // where the two chunk rows of this lane go (same row arithmetic as setup_rows)
+                const int M = last_only ? g : blk_qn[rb] * g;
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
+                for (int j = 0; j < 2; ++j) {
+                    const int row = blk_row0[rb] + (lane >> 2) + 16 * j;
+                    out_ok[rb][j] = blk_on[rb] && row < M;
+                    const int rc = row < M ? row : M - 1;
+                    const int i = last_only ? 0 : rc / g, a = last_only ? rc : rc - i * g;
+                    out_off[rb][j] = last_only ? ((size_t)blk_seq[rb] * n_q + cur.h * g + a) * HD
+                                               : (size_t)(blk_t0[rb] + i) * q_ld + (size_t)(cur.h * g + a) * HD;
+                }
+                // as many 32-channel units (2 KiB each) per round trip as the wave's share of the stage holds
+                constexpr int UPR = (kStageBytes / NW / 2048) < MB ? (kStageBytes / NW / 2048) : MB;
+                static_assert(UPR >= 1 && MB % UPR == 0, "units per round");
+#pragma unroll
+                for (int mb0 = 0; mb0 < MB; mb0 += UPR) {
+#pragma unroll
+                    for (int u = 0; u < UPR; ++u)
 #pragma unroll
                         for (int r4 = 0; r4 < 4; ++r4) {
                             halfx4 w;
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) w[e] = from_float<half_t>(oacc[rb][mb][r4 * 4 + e] * inv);
-                            *(halfx4*)(dst + mb * 32 + 8 * r4 + 4 * hh) = w;
+                            for (int e = 0; e < 4; ++e) w[e] = from_float<half_t>(oacc[rb][mb0 + u][r4 * 4 + e] * inv);
+                            *(halfx4*)(tbuf + u * 2048 + ln * 64 + r4 * 16 + hh * 8) = w;
                         }
+                    __builtin_amdgcn_wave_barrier();       // LDS accesses of one wave execute in order: written, then read back
+#pragma unroll
+                    for (int u = 0; u < UPR; ++u)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) opk[rb][mb0 + u][j] = *(const ochunk_t*)(tbuf + u * 2048 + (lane + 64 * j) * 16);
+                    __builtin_amdgcn_wave_barrier();
                 }
-            } else {
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) opk[rb][mb][r4][e] = from_float<half_t>(oacc[rb][mb][r4 * 4 + e] * inv);
             }
         }
         out_pending = DEFER;
