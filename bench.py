@@ -132,7 +132,7 @@ def measure(name, args, shared, legs, dev="cuda:0"):
         f"gemm={model.gemm_path()} attention={model.attention_path(pool)}")
 
     scores = torch.empty(wl.n_pairs, dtype=torch.float32, device=dev)
-    if args.calibration_copy_mib > 0 and "ceilings" in legs:
+    if args.calibration_copy_mib > 0:
         src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
@@ -575,6 +575,7 @@ def main():
     ap.add_argument("--host-tier-batches", type=int, default=6,
                     help="batches of the paged leg: every batch's documents come from pinned host memory (0 = skip)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the yardsticks (streaming kernels, library GEMM)")
+    ap.add_argument("--no-small-request", action="store_true", help="skip the one-query latency leg")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run a plain device copy of this many MiB (known traffic, for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -591,7 +592,7 @@ def main():
     others = [x for x in also.split(",") if x and x != "none" and x != args.workload]
 
     shared = {"models": {}}
-    legs = {"cpu", "no_reuse", "prefill", "host_tier", "small_request"} | (set() if args.no_ceilings else {"ceilings"})
+    legs = {"cpu", "no_reuse", "prefill", "host_tier"} | (set() if args.no_ceilings else {"ceilings"}) | (set() if args.no_small_request else {"small_request"})
     t_start = time.time()
     main_res = measure(args.workload, args, shared, legs)
     other_res = {}
@@ -603,7 +604,7 @@ def main():
             shared["models"].pop(key)[0].close()
         gc.collect()
         torch.cuda.empty_cache()
-        extra = {"c3_llama8b": {"cpu", "small_request"}, "c5_long_fp8": {"no_reuse"}}.get(name, set())
+        extra = {"c3_llama8b": {"cpu"} | (set() if args.no_small_request else {"small_request"}), "c5_long_fp8": {"no_reuse"}}.get(name, set())
         other_res[name] = measure(name, args, shared, extra)
         log(f"[{name}] done at {time.time() - t_start:.0f}s: {other_res[name]['value']} pairs/s")
 
