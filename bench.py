@@ -265,6 +265,13 @@ def measure(name, args, shared, legs, dev="cuda:0"):
                      "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic.get("attention"), "traffic_source": traffic_src,
                      "avg_launch_ms": round(avg_s * 1e3, 4), "algorithmic_bytes_per_launch": int(kv_bytes_per_launch),
                      "algorithmic_bytes_are": "every pair's document K/V once per layer (per-pair equivalent)"}
+        # The launch also has to read q and the new tokens' K/V pages and write o (16-bit each): at short documents that is
+        # a third of what it moves, so the KV-stream figure alone understates how close the launch is to the memory system.
+        other_bytes = 2 * T * nq * 2 + T * 2 * m.n_kv_heads * d * 2
+        roof_attn["all_operand_bytes_per_launch"] = int(kv_bytes_per_launch + other_bytes)
+        roof_attn["all_operand_GBps"] = round((kv_bytes_per_launch + other_bytes) / avg_s / 1e9, 1)
+        roof_attn["frac_all_operands"] = round((kv_bytes_per_launch + other_bytes) / avg_s / 1e9 / HBM_PEAK_GBS, 4)
+        roof_attn["all_operands_are"] = "KV stream + q read + the new tokens' K/V pages read + o written (plain layers' widths)"
         if distinct_doc_bytes < 0.999 * kv_bytes_per_launch:
             roof_attn["streamed_bytes_per_launch_lower_bound"] = int(distinct_doc_bytes)
             roof_attn["streamed_GBps_lower_bound"] = round(distinct_doc_bytes / avg_s / 1e9, 1)

@@ -18,7 +18,7 @@ subset that holds the extreme lengths and whole queries for the ranking check):
 
     python tests/golden/make_golden.py c3_llama8b [--store-gb 12]
 
-Run time on 8 cores: c2 ~5 min, c4 ~10 min, c5 ~40 min, c3 ~60 min.
+Run time on 8 cores: c2 ~7 min, c4 ~9 min, c5 ~32 min, c3 ~34 min.
 """
 
 import argparse
