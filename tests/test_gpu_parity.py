@@ -833,3 +833,56 @@ def test_demo_walkthrough_runs_and_is_consistent():
     assert same
     for q in range(3):
         assert best[q, 0] == int(np.argmax(scores[q * 6:(q + 1) * 6]))
+
+
+@pytest.mark.timeout(300)
+def test_two_model_handles_driven_from_two_host_threads_score_independently():
+    """Different model handles are independent: two host threads, each with its own handle, stream and workspace, score
+    different batches against one (read-only) pool at the same time, first launches of every kernel included; every call
+    returns the bits of the same call made alone."""
+    import threading
+    import torch
+    from paper_2504_02921_amd import binding as hb
+    model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=4, n_kv=2, d=64, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("threads", model, 6, 5, (20, 200), (3, 40), "bf16", pool_docs=9, zipf_a=0.5, seed=23)
+    w = wlmod.SeededWeights(model, seed=29, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(cfg, spare_pages=2)
+    case = H.Case(wl, w)
+    other = None
+    try:
+        case.fill_from_prefill()
+        other = hb.Model(model, w, "cuda:0")
+        half = wl.n_pairs // 2
+        parts = [wl.subset(np.arange(0, half)), wl.subset(np.arange(half, wl.n_pairs))]
+        models = [case.model, other]
+        got, errors = [[], []], []
+
+        def worker(i):
+            try:
+                st = torch.cuda.Stream()
+                with torch.cuda.stream(st):
+                    for _ in range(12):
+                        s = models[i].score(case.pool, parts[i].page_table, parts[i].doc_lens, parts[i].query_tokens, parts[i].query_lens)
+                        st.synchronize()
+                        got[i].append(s.cpu().numpy().copy())
+            except Exception as e:                      # noqa: BLE001  (reported below, in the main thread)
+                errors.append(repr(e))
+
+        threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join(timeout=120)
+        assert not any(t.is_alive() for t in threads), "a scoring thread did not finish"
+        assert not errors, errors
+        torch.cuda.synchronize()
+        whole = case.gpu_scores()                       # one handle, one thread, the whole batch
+        H.assert_scores_close(whole, case.oracle_scores(), H.TOL["bf16"], "threads")
+        for i, sl in enumerate((slice(0, half), slice(half, wl.n_pairs))):
+            assert len(got[i]) == 12
+            for s in got[i]:
+                np.testing.assert_array_equal(s.astype(np.float64), whole[sl])
+    finally:
+        if other is not None:
+            other.close()
+        case.close()
