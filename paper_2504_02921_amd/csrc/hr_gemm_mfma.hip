@@ -712,6 +712,10 @@ hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st)
         if (wide_head) return launch_ring<EPI_QKV_ROPE, 64, 256, 2, 2, 2, 3>(a, st);
         const int64_t cost64 = ((t64 + cus - 1) / cus) * (64 + 128), cost128 = ((tiles128 + cus - 1) / cus) * (128 + 128);
         const bool r64 = cost64 <= cost128;
+        // residual-add launches with so few rows that even 64 x 64 tiles fit one round: four times the workgroups of the
+        // 128 x 128 shape, each with eight k-tiles in flight (nine stages of 16 KiB)
+        const int64_t t6464 = ((a.M + 63) / 64) * ((a.N + 63) / 64);
+        if (epi == EPI_RESID_ADD && t6464 <= cus) return launch_ring<EPI_RESID_ADD, 64, 64, 2, 2, 1, 9>(a, st);
         switch (epi) {
             case EPI_QKV_ROPE:
                 return r64 ? launch_ring<EPI_QKV_ROPE, 64, 128, 2, 2, 1, 5>(a, st) : launch_ring<EPI_QKV_ROPE, 128, 128, 2, 2, 1, 4>(a, st);
