@@ -419,7 +419,9 @@ int hr_profile_read(hr_model* model, double* ms_out, int64_t* launches_out);
 int hr_probe_read_bandwidth(const void* src_dev, size_t bytes, void* sink_dev, size_t sink_bytes, int to_lds, void* stream);
 
 /* Name of the kernel family a model / pool combination runs: "mfma" or "generic" ("none" for a null handle); never
- * NULL.  The MFMA attention is only chosen together with the MFMA projections. */
+ * NULL.  The MFMA attention is only chosen together with the MFMA projections.  hr_attention_path answers for short
+ * queries: a single call whose longest query times the query heads per kv head exceeds 512 rows runs its attention on
+ * the generic kernel (next to the MFMA projections), with the same results within the tolerance of the model's dtype. */
 const char* hr_attention_path(const hr_model* model, const hr_pool* pool);
 const char* hr_gemm_path(const hr_model* model);
 

@@ -93,6 +93,9 @@ def test_bf16_mfma_projection_shapes(d, n_q, n_kv, hidden, ffn):
     (128, 4, 1, "fp8", (60, 260), (20, 40)),    # fp8 pages, head_dim 128
     (64, 4, 4, "fp8", (16, 129), (1, 33)),      # fp8 pages, head_dim 64, no grouping
     (64, 8, 2, "bf16", 0, (1, 40)),             # no cached document at all: plain causal pass
+    (64, 16, 2, "bf16", (50, 150), (60, 64)),   # group of 8 x 64 query tokens: 512 rows, the most a work item holds
+    (128, 8, 1, "bf16", (40, 120), (40, 64)),   # head_dim 128 with more than 256 rows: 8 waves x 2 blocks
+    (128, 8, 1, "fp8", (40, 120), (40, 64)),    # the same over fp8 pages
 ])
 def test_mfma_attention_shapes_and_edges(d, n_q, n_kv, kv, doc_len, q_len):
     hidden = 256
@@ -109,6 +112,18 @@ def test_mfma_attention_shapes_and_edges(d, n_q, n_kv, kv, doc_len, q_len):
     else:
         case, got, want = run_case(cfg, w, H.TOL["bf16"])
     assert case.model.attention_path(case.pool) == "mfma"
+    case.close()
+
+
+def test_more_query_rows_than_a_work_item_holds_take_the_generic_kernels():
+    """9 query heads per kv head x 64 query tokens = 576 rows per (pair, kv head), more than the 512 an MFMA attention work
+    item holds: such a call runs its attention on the generic kernel (new K/V row-major instead of pages) next to the MFMA
+    projections, and still matches."""
+    model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=18, n_kv=2, d=64, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("many_rows", model, 2, 3, (30, 90), (60, 64), "bf16", pool_docs=5, zipf_a=0.3, seed=77)
+    w = wlmod.SeededWeights(model, seed=16, std=0.05, gain_jitter=0.1)
+    case, got, want = run_case(cfg, w, H.TOL["bf16"])
+    assert case.model.gemm_path() == "mfma"
     case.close()
 
 
