@@ -736,16 +736,14 @@ hipError_t launch_one(const half_t* q, const char* kv_new, const char* kv_new_lo
 
 }  // namespace
 
-// rows per workgroup = (n_q / n_kv) * max_q_len must fit NW * R blocks of 32; the pair's own keys must fit the
-// two LDS stages as half pseudo-pages
+// rows per workgroup = (n_q / n_kv) * max_q_len must fit NW * R blocks of 32 (the pair's own keys may take any number of
+// stages: they are streamed like document pages)
 bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len) {
     if (c.dtype != HR_BF16) return false;
     if (kv_dtype != HR_BF16 && kv_dtype != HR_FP8_E4M3) return false;
     if (c.head_dim != 64 && c.head_dim != 128) return false;
     const int g = c.n_q_heads / c.n_kv_heads;
     if ((int64_t)g * max_q_len > kMaxRowsPerWg) return false;
-    const int q_keys = (max_q_len + 31) / 32 * 32;
-    if ((int64_t)q_keys * c.head_dim * 4 > 2 * stage_bytes(kv_dtype == HR_FP8_E4M3)) return false;
     return true;
 }
 

@@ -128,6 +128,24 @@ int main() {
         }
         for (int64_t p = 0; p < n; ++p)
             for (char c : seen[p]) CHECK(c == 1);
+        // many sequences of up to 16 blocks cut into pieces of at most 8 (128-wide heads): fits the room reserved for a plan
+        {
+            const int64_t nn = 300;
+            const int g8 = 8;
+            std::vector<int32_t> md(nn), mq(nn), mpt(nn);
+            int64_t Tm = 0;
+            for (int64_t p = 0; p < nn; ++p) {
+                md[p] = 16;
+                mq[p] = 1 + (int32_t)((p * 37) % 64);
+                mpt[p] = (int32_t)(p % 7);                   // a few shared first pages (same length: shared documents)
+                Tm += mq[p];
+            }
+            hr::GroupPlan cp8 = hr::make_group_plan(nn, md.data(), mq.data(), mpt.data(), 1, g8, 8, true);
+            CHECK(cp8.cut && cp8.max_blocks <= 8 && cp8.ints() <= hr::group_plan_ints_bound(nn, Tm, g8));
+            std::vector<int> blocks(nn, 0);
+            for (size_t b = 0; b < cp8.blk_seq.size(); ++b) ++blocks[cp8.blk_seq[b]];
+            for (int64_t p = 0; p < nn; ++p) CHECK(blocks[p] == (mq[p] * g8 + 31) / 32);
+        }
         std::vector<int32_t> rd = {16, 48, 32};                   // nothing shared, lengths differ: heaviest first
         hr::GroupPlan rp = hr::make_group_plan(3, rd.data(), uq.data(), upt.data(), 1, g, cap);
         CHECK(!rp.shared && rp.uneven && rp.p0[0] == 1 && rp.p0[1] == 2 && rp.p0[2] == 0);

@@ -96,6 +96,9 @@ def test_bf16_mfma_projection_shapes(d, n_q, n_kv, hidden, ffn):
     (64, 16, 2, "bf16", (50, 150), (60, 64)),   # group of 8 x 64 query tokens: 512 rows, the most a work item holds
     (128, 8, 1, "bf16", (40, 120), (40, 64)),   # head_dim 128 with more than 256 rows: 8 waves x 2 blocks
     (128, 8, 1, "fp8", (40, 120), (40, 64)),    # the same over fp8 pages
+    (128, 8, 2, "fp8", (40, 120), (65, 128)),   # fp8 pages, own keys over up to four stages, 512 rows
+    (64, 4, 2, "fp8", (16, 90), (130, 200)),    # head_dim 64, fp8 pages, up to 200 own keys
+    (64, 4, 2, "bf16", (16, 90), (130, 256)),   # 512 rows from 256 query tokens
 ])
 def test_mfma_attention_shapes_and_edges(d, n_q, n_kv, kv, doc_len, q_len):
     hidden = 256
@@ -113,6 +116,28 @@ def test_mfma_attention_shapes_and_edges(d, n_q, n_kv, kv, doc_len, q_len):
         case, got, want = run_case(cfg, w, H.TOL["bf16"])
     assert case.model.attention_path(case.pool) == "mfma"
     case.close()
+
+
+@pytest.mark.parametrize("kv", ["bf16", "fp8"])
+def test_wide_heads_with_more_than_eight_row_blocks_cut_or_not_same_bits(kv, monkeypatch):
+    """128-wide heads, up to 512 rows per (pair, kv head): the scoring call cuts such a pair into two work items of at most
+    eight row blocks; with the group plan switched off the kernel with two blocks per wave runs instead.  Same bits."""
+    model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=8, n_kv=1, d=128, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("wide_cut", model, 3, 3, (40, 120), (40, 64), kv, pool_docs=5, zipf_a=0.3, seed=55)
+    w = wlmod.SeededWeights(model, seed=18, std=0.05, gain_jitter=0.1)
+    wl = wlmod.make_workload(cfg, spare_pages=2)
+    outs = {}
+    for off in ("0", "1"):
+        monkeypatch.setenv("HR_NO_DOC_GROUPS", off)
+        case = H.Case(wl, w)
+        try:
+            case.fill_from_prefill()
+            outs[off] = case.gpu_scores()
+            if off == "0":
+                H.assert_scores_close(outs[off], case.oracle_scores(), H.TOL["bf16"], "wide heads, cut")
+        finally:
+            case.close()
+    np.testing.assert_array_equal(outs["0"], outs["1"])
 
 
 def test_more_query_rows_than_a_work_item_holds_take_the_generic_kernels():
