@@ -420,8 +420,11 @@ int hr_probe_read_bandwidth(const void* src_dev, size_t bytes, void* sink_dev, s
 
 /* Name of the kernel family a model / pool combination runs: "mfma" or "generic" ("none" for a null handle); never
  * NULL.  The MFMA attention is only chosen together with the MFMA projections.  hr_attention_path answers for short
- * queries: a single call whose longest query times the query heads per kv head exceeds 512 rows runs its attention on
- * the generic kernel (next to the MFMA projections), with the same results within the tolerance of the model's dtype. */
+ * queries.  One attention work item holds 512 rows (query tokens x query heads per kv head) at 64-wide heads and 256 at
+ * 128-wide heads; a scoring call spreads a longer query's rows over up to eight work items (each streams the document),
+ * and beyond that (or with HR_NO_DOC_GROUPS=1, which switches the plan off that does the spreading) runs its attention on
+ * the generic kernel next to the MFMA projections: same results within the tolerance of the model's dtype, and a
+ * document plus query of at most 15000 tokens. */
 const char* hr_attention_path(const hr_model* model, const hr_pool* pool);
 const char* hr_gemm_path(const hr_model* model);
 

@@ -747,6 +747,16 @@ bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len) {
     return true;
 }
 
+// The same for a call that travels with a group plan: the row blocks of a long query are spread over work items of at most
+// 16 blocks (8 at 128-wide heads), up to kMaxPiecesPerSeq of them.
+bool attn_mfma_supported_cut(const hr_model_cfg& c, int kv_dtype, int max_q_len) {
+    if (attn_mfma_supported(c, kv_dtype, max_q_len)) return true;
+    if (!attn_mfma_supported(c, kv_dtype, 1)) return false;
+    const int64_t blocks = ((int64_t)(c.n_q_heads / c.n_kv_heads) * max_q_len + 31) / 32;
+    const int cap = c.head_dim == 64 ? 16 : 8;
+    return (blocks + cap - 1) / cap <= kMaxPiecesPerSeq;
+}
+
 hipError_t launch_attn_mfma(const void* q, const void* kv_new_pages, void* o, const MetaView& mv, const PoolView& pv, int layer,
                             int n_q, int max_q_len, hipStream_t st, bool last_only, const GroupView* groups, const void* kv_new_lo_pages) {
     if (mv.n_seq == 0) return hipSuccess;

@@ -81,8 +81,12 @@ void note_hip_error(hipError_t e, const char* what) {
 
 // The MFMA attention reads the new tokens' K/V as pool-format pages, which only the MFMA QKV projection's epilogue
 // writes: the two kernel families are chosen together.
-bool use_mfma_attn(const hr_model* m, int kv_dtype, int max_new_len) {
-    return !m->force_generic && m->mfma_gemm && attn_mfma_supported(m->cfg, kv_dtype, max_new_len);
+// may_cut: the call can spread a sequence's row blocks over several work items (a group plan travels with it), so more
+// rows per kv head than one work item holds are fine as long as kMaxPiecesPerSeq items of the largest size take them.
+bool use_mfma_attn(const hr_model* m, int kv_dtype, int max_new_len, bool may_cut = false) {
+    if (m->force_generic || !m->mfma_gemm) return false;
+    if (may_cut && !m->no_doc_groups) return attn_mfma_supported_cut(m->cfg, kv_dtype, max_new_len);
+    return attn_mfma_supported(m->cfg, kv_dtype, max_new_len);
 }
 
 constexpr int kMaxDevices = 64;
@@ -228,8 +232,9 @@ int run_layers(hr_model* m, const hr_pool* pool, bool self_prefix, const MetaVie
         pv.num_pages = 1;
         if (self_prefix) pv.data = (const char*)k;     // layer index 0 of a one-layer "pool" = the new-KV page buffer
     }
-    const bool mfma_attn = use_mfma_attn(m, pv.kv_dtype, max_new_len);
+    const bool mfma_attn = use_mfma_attn(m, pv.kv_dtype, max_new_len, groups && groups->n_groups > 0);
     if (self_prefix && !mfma_attn) return HR_ERR_UNSUPPORTED_SHAPE;
+    if (!mfma_attn && max_keys > kGenericMaxKeys) return HR_ERR_UNSUPPORTED_SHAPE;     // the generic attention keeps a row's scores in LDS
     // the shortened last layer needs one output row per sequence, the MFMA kernels, something to save (T > P), and
     // room for P fp32 rows in the q buffer
     // Layers l < n_prec run with 22-bit operands: every activation that feeds an MFMA (the normalised rows, q, the new
@@ -627,15 +632,22 @@ static void build_score_part(hr_model* m, int32_t n_pairs, const int32_t* page_t
     const int g = m->cfg.n_q_heads / m->cfg.n_kv_heads;
     hr::GroupView& gv = out->gv;
     size_t plan_ints = 0;                                    // of the room reserved for a plan, what this call uses
-    if (mfma_attn && !m->no_doc_groups && pt_stride > 0) {
+    int max_q = 0;
+    for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
+    const int64_t blocks_max = ((int64_t)g * max_q + 31) / 32;           // row blocks of the longest query, per kv head
+    const int cap_full = m->cfg.head_dim == 64 ? 16 : 8;                 // what one work item holds
+    if (mfma_attn && !m->no_doc_groups && (pt_stride > 0 || blocks_max > cap_full)) {
         // few work items (less than half the CUs would get one): a pair's row blocks are spread over several work items
         // of at most four, one per wave of the smallest kernel, each streaming the document for its share of the rows
-        const bool scarce = n_pairs <= hr::kGroupCutMaxSeqs && (int64_t)n_pairs * m->cfg.n_kv_heads * 2 <= hr::device_cu_count();
-        const int cap = scarce ? 4 : (m->cfg.head_dim == 64 ? 16 : 8);
+        const bool scarce = n_pairs <= hr::kGroupCutMaxSeqs && (int64_t)n_pairs * m->cfg.n_kv_heads * 2 <= hr::device_cu_count() &&
+                            blocks_max <= 4 * hr::kMaxPiecesPerSeq;
+        const int cap = scarce ? 4 : cap_full;
         // 128-wide heads: a pair with more than 8 row blocks is cut in two work items as well.  Two blocks per wave do not
         // fit the registers there (the kernel for 9-16 blocks spills), and two items that each stream the document run
         // the 512-row shape 1.8 times faster (measured at the 8B shape, 128-token queries; same bits).
-        const bool cut_long = scarce || m->cfg.head_dim == 128;
+        // Queries of more rows than any work item holds are cut the same way (use_mfma_attn has checked that
+        // kMaxPiecesPerSeq pieces are enough, and the room reserved for a plan covers that many).
+        const bool cut_long = scarce || m->cfg.head_dim == 128 || blocks_max > cap_full;
         const hr::GroupPlan plan = hr::make_group_plan(n_pairs, doc_lens, query_lens, content_plans ? page_table : nullptr, pt_stride, g,
                                                        cap, cut_long);
         // also without a shared document when the pairs differ in length: the plan's heaviest-first order keeps the
@@ -718,7 +730,7 @@ int hr_rerank_score(hr_model* m, const hr_pool* pool, int32_t n_pairs, const int
     int max_q = 0;
     if (n_pairs > 0 && query_lens)
         for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
-    const bool mfma_attn = use_mfma_attn(m, pool->cfg.kv_dtype, max_q);
+    const bool mfma_attn = use_mfma_attn(m, pool->cfg.kv_dtype, max_q, true);
     int64_t T = 0;
     int rc = hr::score_check_args(m->cfg, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens,
                                   mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys, &T);
@@ -807,7 +819,7 @@ int hr_rerank_score_static(hr_model* m, const hr_pool* pool, int32_t n_pairs, co
     int max_q = 0;
     if (n_pairs > 0 && query_lens)
         for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
-    const bool mfma_attn = use_mfma_attn(m, pool->cfg.kv_dtype, max_q);
+    const bool mfma_attn = use_mfma_attn(m, pool->cfg.kv_dtype, max_q, true);
     int64_t T = 0;
     int rc = hr::score_check_args(m->cfg, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens,
                                   mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys, &T);
@@ -863,7 +875,7 @@ int hr_rerank_plan_create(hr_model* m, const hr_pool* pool, int32_t n_pairs, con
     if ((mc.dtype == HR_F32) != (pool->cfg.kv_dtype == HR_F32)) return HR_ERR_MISMATCH;
     int max_q = 0;
     for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
-    const bool mfma_attn = use_mfma_attn(m, pool->cfg.kv_dtype, max_q);
+    const bool mfma_attn = use_mfma_attn(m, pool->cfg.kv_dtype, max_q, true);
     int64_t T = 0;
     for (int32_t p = 0; p < n_pairs; ++p) {
         if (doc_lens[p] < 0 || query_lens[p] <= 0) return HR_ERR_LEN_RANGE;
@@ -960,7 +972,7 @@ int hr_rerank_validate(const hr_model_cfg* cfg, const hr_pool* pool, int32_t n_p
     int max_q = 0;
     if (n_pairs > 0 && query_lens)
         for (int32_t p = 0; p < n_pairs; ++p) max_q = std::max(max_q, query_lens[p]);
-    const bool mfma_attn = hr::gemm_mfma_supported(*cfg) && hr::attn_mfma_supported(*cfg, pool->cfg.kv_dtype, max_q);
+    const bool mfma_attn = hr::gemm_mfma_supported(*cfg) && hr::attn_mfma_supported_cut(*cfg, pool->cfg.kv_dtype, max_q);
     return hr::score_check_args(*cfg, pool, n_pairs, page_table, pt_stride, doc_lens, query_tokens, query_lens,
                                 mfma_attn ? kMfmaMaxKeys : kGenericMaxKeys, nullptr);
 }

@@ -337,10 +337,10 @@ ChunkPlan make_chunk_plan(int64_t n_seq, const int32_t* lens, int chunk) {
 }
 
 size_t group_plan_ints_bound(int64_t n_seq, int64_t T, int g) {
-    // every sequence adds at most one partial block and one partial sub-tile; a call of few sequences may cut each of
-    // them into up to 4 groups (16 blocks at most, 4 per group), any other call (128-wide heads) into 2 of at most 8
-    // blocks; each piece lists the sequence's sub-tiles
-    const size_t cut = n_seq <= kGroupCutMaxSeqs ? 4 : 2;
+    // every sequence adds at most one partial block and one partial sub-tile; a sequence may be cut into up to
+    // kMaxPiecesPerSeq work items (few sequences: pieces of 4 blocks; long queries: pieces of 8 or 16), each of which
+    // lists the sequence's sub-tiles
+    const size_t cut = kMaxPiecesPerSeq;
     const size_t nb = (size_t)(T * g / 32 + n_seq), ns = (size_t)(T / 32 + n_seq) * cut, ng = (size_t)n_seq * cut;
     return ng + 2 * (ng + 1) + 2 * nb + 3 * ns;
 }

@@ -154,6 +154,7 @@ struct GroupPlan {
 // Groups come in order of decreasing work (document keys x blocks), so that a round-robin walk starts the long ones
 // first.
 constexpr int64_t kGroupCutMaxSeqs = 128;      // more sequences than this always give every other CU a work item
+constexpr int kMaxPiecesPerSeq = 8;            // a sequence's row blocks are spread over at most this many work items
 GroupPlan make_group_plan(int64_t n_seq, const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* page_table,
                           int64_t pt_stride, int g, int cap_blocks, bool cut_long = false);
 size_t group_plan_ints_bound(int64_t n_seq, int64_t T, int g);

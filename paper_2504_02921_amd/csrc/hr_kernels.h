@@ -99,7 +99,8 @@ struct GemmArgs {
 };
 hipError_t launch_gemm_mfma(GemmEpilogue epi, const GemmArgs& a, hipStream_t st);
 
-bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len);
+bool attn_mfma_supported(const hr_model_cfg& c, int kv_dtype, int max_q_len);          // one work item per (sequence, kv head)
+bool attn_mfma_supported_cut(const hr_model_cfg& c, int kv_dtype, int max_q_len);      // ... or several, by a group plan
 // Device-side view of a group plan (GroupPlan): sequences that share a cached document are one work item per kv head.
 struct GroupView {
     int32_t n_groups = 0, max_blocks = 0;

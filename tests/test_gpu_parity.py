@@ -140,16 +140,33 @@ def test_wide_heads_with_more_than_eight_row_blocks_cut_or_not_same_bits(kv, mon
     np.testing.assert_array_equal(outs["0"], outs["1"])
 
 
-def test_more_query_rows_than_a_work_item_holds_take_the_generic_kernels():
-    """9 query heads per kv head x 64 query tokens = 576 rows per (pair, kv head), more than the 512 an MFMA attention work
-    item holds: such a call runs its attention on the generic kernel (new K/V row-major instead of pages) next to the MFMA
-    projections, and still matches."""
-    model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=18, n_kv=2, d=64, ffn=320, vocab=500)
-    cfg = wlmod.WorkloadCfg("many_rows", model, 2, 3, (30, 90), (60, 64), "bf16", pool_docs=5, zipf_a=0.3, seed=77)
+@pytest.mark.parametrize("d,n_q,n_kv,kv,q_len", [
+    (64, 18, 2, "bf16", (60, 64)),       # 9 heads per kv head x 64 tokens = 576 rows: two work items
+    (64, 16, 2, "bf16", (65, 128)),      # up to 1024 rows
+    (128, 8, 2, "bf16", (130, 256)),     # 128-wide heads, up to 1024 rows: four work items of eight blocks
+    (128, 8, 2, "fp8", (130, 256)),      # the same over fp8 pages (the pair's own keys take up to eight stages)
+])
+def test_more_query_rows_than_a_work_item_holds(d, n_q, n_kv, kv, q_len, monkeypatch):
+    """More rows per (pair, kv head) than the 512 an MFMA attention work item holds: the scoring call spreads such a pair's
+    row blocks over several work items, each of which streams the document and the pair's own keys.  With the group plan
+    switched off the attention of such a call runs on the generic kernel (new K/V row-major instead of pages) next to the
+    MFMA projections.  Both match the oracle; a pair scores the same bits alone and in the batch."""
+    model = small_model(dtype="bf16", n_layers=2, hidden=256, n_q=n_q, n_kv=n_kv, d=d, ffn=320, vocab=500)
+    cfg = wlmod.WorkloadCfg("many_rows", model, 2, 3, (30, 90), q_len, kv, pool_docs=5, zipf_a=0.3, seed=77)
     w = wlmod.SeededWeights(model, seed=16, std=0.05, gain_jitter=0.1)
-    case, got, want = run_case(cfg, w, H.TOL["bf16"])
-    assert case.model.gemm_path() == "mfma"
-    case.close()
+    wl = wlmod.make_workload(cfg, spare_pages=2)
+    for off in ("0", "1"):
+        monkeypatch.setenv("HR_NO_DOC_GROUPS", off)
+        case = H.Case(wl, w)
+        try:
+            case.fill_from_prefill()
+            assert case.model.gemm_path() == "mfma"
+            got = case.gpu_scores()
+            H.assert_scores_close(got, case.oracle_scores(), H.TOL["bf16"], f"many rows, plan off={off}")
+            if off == "0":
+                np.testing.assert_array_equal(case.gpu_scores(wl.subset(np.array([wl.n_pairs - 1]))), got[-1:])
+        finally:
+            case.close()
 
 
 @pytest.mark.parametrize("hidden,ffn", [(256, 688), (200, 320)])
