@@ -165,6 +165,8 @@ def test_more_query_rows_than_a_work_item_holds(d, n_q, n_kv, kv, q_len, monkeyp
             H.assert_scores_close(got, case.oracle_scores(), H.TOL["bf16"], f"many rows, plan off={off}")
             if off == "0":
                 np.testing.assert_array_equal(case.gpu_scores(wl.subset(np.array([wl.n_pairs - 1]))), got[-1:])
+                case.model.set_precise_layers(2)          # the split-operand form of the attention over the same pieces
+                H.assert_scores_close(case.gpu_scores(), case.oracle_scores(), H.TOL["bf16"], "many rows, split operands")
         finally:
             case.close()
 
