@@ -21,12 +21,14 @@ def _same_shape_other_inputs(wl, seed):
     return np.ascontiguousarray(wl.page_table[perm]), toks, perm
 
 
-@pytest.mark.parametrize("dtype,d,n_q,n_kv,kv,n_split,tol", [("bf16", 64, 14, 2, "bf16", 0, 2e-2), ("bf16", 128, 8, 2, "fp8", 1, 2e-2),
-                                                             ("f32", 32, 4, 2, "f32", 0, 1e-4)])
-def test_plan_runs_and_graph_replays_give_the_bits_of_the_plain_call(dtype, d, n_q, n_kv, kv, n_split, tol):
+@pytest.mark.parametrize("dtype,d,n_q,n_kv,kv,n_split,tol,qlen", [
+    ("bf16", 64, 14, 2, "bf16", 0, 2e-2, (3, 40)), ("bf16", 128, 8, 2, "fp8", 1, 2e-2, (3, 40)), ("f32", 32, 4, 2, "f32", 0, 1e-4, (3, 40)),
+    ("bf16", 64, 16, 2, "bf16", 0, 2e-2, (70, 100)),     # up to 800 rows per kv head: the plan spreads a pair over two work items
+])
+def test_plan_runs_and_graph_replays_give_the_bits_of_the_plain_call(dtype, d, n_q, n_kv, kv, n_split, tol, qlen):
     import torch
     model = wlmod.ModelCfg("plan", 3, 256, n_q, n_kv, d, 320, 500, 10000.0, 1e-6, dtype=dtype)
-    cfg = wlmod.WorkloadCfg("plan", model, 2, 5, 70, (3, 40), kv, seed=d + n_q)
+    cfg = wlmod.WorkloadCfg("plan", model, 2, 5, 70, qlen, kv, seed=d + n_q)
     w = wlmod.SeededWeights(model, seed=23, std=0.05, gain_jitter=0.1)
     wl = wlmod.make_workload(cfg, spare_pages=3)
     case = H.Case(wl, w)
